@@ -1,0 +1,165 @@
+/*
+ * ll.h -- C ABI of the MI355X (gfx950) batch-1 LLaMA decode / prefill path.
+ *
+ * The problem is the one the paper states in Alg. 1: given a prompt P and
+ * model weights W, emit tokens t_1..t_n, one per decoding step, on a single
+ * GPU at batch 1 (Sec. IV-E).  The paper replays one captured graph per
+ * sequence length and keeps sampling, KV-cache update and position handling on
+ * the host side (Sec. III-A, III-B).  This library instead captures ONE decode
+ * graph for all lengths: position, KV length and the next token id live in a
+ * device-resident state block that the kernels read and the last kernel of the
+ * step advances, so the decode loop needs no host round trip.
+ *
+ * One process-global instance.  Not thread-safe: one caller thread.
+ *
+ * Memory: every pointer inside ll_weights, and `workspace`, are DEVICE
+ * pointers owned by the caller (allocated e.g. through PyTorch) and must stay
+ * valid until ll_shutdown().  `tokens`, `out_tokens` and every ll_dbg_* output
+ * are HOST pointers.  After ll_init() the library allocates no device memory
+ * and never frees caller memory; it owns only its graphs, two small pinned
+ * host buffers and host bookkeeping.
+ *
+ * Weights are IEEE binary16, row-major [out, in] (y = W x); RMSNorm gains are
+ * binary16 [d_model]; tok_emb and lm_head are [vocab, d_model] and not tied.
+ *
+ * Errors: every call returns >= 0 on success and a negative LL_E_* code on
+ * failure; ll_last_error() then describes it.  A failed call leaves the
+ * decoder state unchanged.  No exception crosses this boundary.
+ */
+#ifndef LL_H
+#define LL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  LL_OK = 0,
+  LL_E_NOT_INIT = -1,   /* call needs a successful ll_init() first */
+  LL_E_BAD_CONFIG = -2, /* unsupported or inconsistent ll_config */
+  LL_E_BAD_ARG = -3,    /* null pointer, n < 1, token outside [0, vocab) ... */
+  LL_E_CAPACITY = -4,   /* the request would run past max_seq cached positions */
+  LL_E_WORKSPACE = -5,  /* workspace smaller than ll_workspace_bytes() or misaligned */
+  LL_E_STATE = -6,      /* e.g. ll_prefill on a non-empty context, decode on an empty one */
+  LL_E_HIP = -7,        /* a HIP runtime call failed; see ll_last_error() */
+  LL_E_ALREADY_INIT = -8
+};
+
+/* ll_config.flags */
+enum {
+  LL_FLAG_EAGER = 1 /* launch every kernel individually instead of replaying graphs
+                       (same kernels, same order: isolates the dispatch cost the
+                       paper's Sec. I-B / III-B attribute to per-kernel launches) */
+};
+
+/* Model shape.  Constraints: n_heads * head_dim == d_model; head_dim is 64 or
+ * 128; d_model and ffn_hidden are multiples of 8; max_seq >= 2. */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, head_dim, ffn_hidden, vocab, max_seq;
+  float rope_theta; /* RoPE base, e.g. 10000 */
+  float rms_eps;    /* added to the mean square inside the root */
+  int32_t flags;    /* LL_FLAG_* */
+} ll_config;
+
+typedef struct {
+  const void *attn_norm;              /* [d_model] */
+  const void *wq, *wk, *wv, *wo;      /* [d_model, d_model] */
+  const void *ffn_norm;               /* [d_model] */
+  const void *w_gate, *w_up;          /* [ffn_hidden, d_model] */
+  const void *w_down;                 /* [d_model, ffn_hidden] */
+} ll_layer_weights;
+
+typedef struct {
+  const void *tok_emb;                /* [vocab, d_model] */
+  const ll_layer_weights *layers;     /* HOST array of n_layers entries (device pointers inside) */
+  const void *final_norm;             /* [d_model] */
+  const void *lm_head;                /* [vocab, d_model] */
+} ll_weights;
+
+/* Bytes of device workspace ll_init() needs for this shape (KV cache, RoPE
+ * table, activations, split-K partials, logits, state block).  Pure function;
+ * returns 0 for a configuration ll_init() would reject. */
+size_t ll_workspace_bytes(const ll_config *cfg);
+
+/* Binds weights, carves the workspace (256-byte aligned device pointer),
+ * uploads the RoPE cos/sin table, warms every kernel up and captures the
+ * decode graph and one prefill graph per prompt-length bucket on `hip_stream`
+ * (a hipStream_t; NULL selects the default stream).  Context starts empty. */
+int ll_init(const ll_config *cfg, const ll_weights *w, void *workspace, size_t workspace_bytes,
+            void *hip_stream);
+
+/* Time-to-first-token call (the paper's TTFT metric, Sec. IV-E / Table I):
+ * runs the whole prompt (1 <= n, n + 1 <= max_seq, n <= ll_max_prompt())
+ * through the MFMA prefill path, fills KV positions 0..n-1 and returns the
+ * first generated token t_1 (greedy: lowest index among the maxima of the
+ * logits at position n-1).  Requires an empty context (after ll_init or
+ * ll_reset), else LL_E_STATE.  Blocks until the token is on the host. */
+int32_t ll_prefill(const int32_t *tokens, int32_t n);
+
+/* One decoding step (Alg. 1 loop body): feeds the previous step's token at the
+ * next position, appends its key/value rows, returns the next greedy token.
+ * Blocks until the token is on the host.  LL_E_STATE on an empty context,
+ * LL_E_CAPACITY once max_seq positions are cached. */
+int32_t ll_decode_step(void);
+
+/* k decoding steps enqueued back to back with ONE synchronisation at the end;
+ * out_tokens (host, k entries, may be NULL) receives the generated ids.
+ * Returns the last token. */
+int32_t ll_decode_n(int32_t k, int32_t *out_tokens);
+
+/* Empties the context (position 0, no cached keys); weights, graphs and the
+ * workspace binding are kept. */
+int ll_reset(void);
+
+/* Destroys graphs and host buffers; caller memory is untouched. */
+int ll_shutdown(void);
+
+/* Longest prompt ll_prefill() accepts for the current instance. */
+int32_t ll_max_prompt(void);
+
+/* Number of cached positions (0 when empty), or LL_E_NOT_INIT. */
+int32_t ll_position(void);
+
+/* Text of the most recent failure on this thread ("" if none). */
+const char *ll_last_error(void);
+
+/* ---- measurement and test hooks (not part of the four-call contract) ---- */
+
+/* Logits [vocab] of the most recent prefill/decode step, copied to the host. */
+int ll_dbg_get_logits(float *host_out);
+/* Residual stream [d_model] before the final norm of the most recent step. */
+int ll_dbg_get_hidden(float *host_out);
+/* Overrides the token the next decode step will feed (teacher forcing). */
+int ll_dbg_force_next_token(int32_t tok);
+/* Cached keys (which = 0) or values (which = 1) of one layer, positions
+ * [0, n_pos), converted to float, laid out [n_pos][d_model] on the host. */
+int ll_dbg_get_kv(int32_t layer, int32_t which, int32_t n_pos, float *host_out);
+
+/* Runs `steps` decode steps eagerly with a hipEvent pair around every kernel
+ * launch and returns per-kernel-class mean durations.  The context advances by
+ * `steps` tokens.  us_out[LL_KC_COUNT] receives microseconds per launch and
+ * launches_out[LL_KC_COUNT] (nullable) the launches per step of each class. */
+enum {
+  LL_KC_EMBED = 0,
+  LL_KC_QKV = 1,     /* RMSNorm + QKV GEMV + RoPE + KV write */
+  LL_KC_ATTN = 2,    /* split-K decode attention + combine */
+  LL_KC_OPROJ = 3,   /* O GEMV + residual */
+  LL_KC_GATEUP = 4,  /* RMSNorm + gate/up GEMV + SwiGLU */
+  LL_KC_DOWN = 5,    /* down GEMV + residual */
+  LL_KC_LMHEAD = 6,  /* final RMSNorm + LM-head GEMV + block argmax */
+  LL_KC_SAMPLE = 7,  /* final argmax + state advance */
+  LL_KC_COUNT = 8
+};
+int ll_dbg_profile_decode(int32_t steps, float *us_out, int32_t *launches_out);
+
+/* Device time of `k` decode-step replays measured with one hipEvent pair on
+ * the library's stream (milliseconds for all k steps), tokens discarded. */
+int ll_dbg_time_decode(int32_t k, float *ms_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LL_H */

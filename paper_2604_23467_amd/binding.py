@@ -1,0 +1,233 @@
+"""Thin ctypes binding of ``libll.so`` (declarations: ``include/ll.h``).
+
+Argument marshalling only: every step of the decode / prefill path runs in the
+HIP kernels behind the C ABI.  PyTorch appears here solely as the owner of
+device memory (weights, workspace) and of the HIP stream.  There is no CPU
+fallback: a missing library raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libll.so")
+
+LL_OK = 0
+LL_E_NOT_INIT, LL_E_BAD_CONFIG, LL_E_BAD_ARG, LL_E_CAPACITY = -1, -2, -3, -4
+LL_E_WORKSPACE, LL_E_STATE, LL_E_HIP, LL_E_ALREADY_INIT = -5, -6, -7, -8
+LL_FLAG_EAGER = 1
+KERNEL_CLASSES = ("embed", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "sample")
+LAYER_KEYS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
+
+EXPORTS = ("ll_workspace_bytes", "ll_init", "ll_prefill", "ll_decode_step", "ll_decode_n", "ll_reset",
+           "ll_shutdown", "ll_max_prompt", "ll_position", "ll_last_error", "ll_dbg_get_logits",
+           "ll_dbg_get_hidden", "ll_dbg_force_next_token", "ll_dbg_get_kv", "ll_dbg_profile_decode",
+           "ll_dbg_time_decode")
+
+
+class LLConfig(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in
+                ("n_layers", "d_model", "n_heads", "head_dim", "ffn_hidden", "vocab", "max_seq")] + \
+               [("rope_theta", C.c_float), ("rms_eps", C.c_float), ("flags", C.c_int32)]
+
+
+class LLLayerWeights(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in LAYER_KEYS]
+
+
+class LLWeights(C.Structure):
+    _fields_ = [("tok_emb", C.c_void_p), ("layers", C.POINTER(LLLayerWeights)),
+                ("final_norm", C.c_void_p), ("lm_head", C.c_void_p)]
+
+
+class LLError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("ll error %d: %s" % (code, msg))
+        self.code = code
+
+
+_lib = None
+
+
+def load():
+    """Loads libll.so (built beforehand by ``paper_2604_23467_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("HIP library %s is missing: run `python -m paper_2604_23467_amd.build` "
+                           "(there is no CPU fallback)" % LIB_PATH)
+    L = C.CDLL(LIB_PATH)
+    L.ll_workspace_bytes.restype = C.c_size_t
+    L.ll_workspace_bytes.argtypes = [C.POINTER(LLConfig)]
+    L.ll_init.restype = C.c_int
+    L.ll_init.argtypes = [C.POINTER(LLConfig), C.POINTER(LLWeights), C.c_void_p, C.c_size_t, C.c_void_p]
+    L.ll_prefill.restype = C.c_int32
+    L.ll_prefill.argtypes = [C.POINTER(C.c_int32), C.c_int32]
+    L.ll_decode_step.restype = C.c_int32
+    L.ll_decode_step.argtypes = []
+    L.ll_decode_n.restype = C.c_int32
+    L.ll_decode_n.argtypes = [C.c_int32, C.POINTER(C.c_int32)]
+    for name in ("ll_reset", "ll_shutdown"):
+        getattr(L, name).restype = C.c_int
+        getattr(L, name).argtypes = []
+    for name in ("ll_max_prompt", "ll_position"):
+        getattr(L, name).restype = C.c_int32
+        getattr(L, name).argtypes = []
+    L.ll_last_error.restype = C.c_char_p
+    L.ll_last_error.argtypes = []
+    L.ll_dbg_get_logits.restype = C.c_int
+    L.ll_dbg_get_logits.argtypes = [C.POINTER(C.c_float)]
+    L.ll_dbg_get_hidden.restype = C.c_int
+    L.ll_dbg_get_hidden.argtypes = [C.POINTER(C.c_float)]
+    L.ll_dbg_force_next_token.restype = C.c_int
+    L.ll_dbg_force_next_token.argtypes = [C.c_int32]
+    L.ll_dbg_get_kv.restype = C.c_int
+    L.ll_dbg_get_kv.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float)]
+    L.ll_dbg_profile_decode.restype = C.c_int
+    L.ll_dbg_profile_decode.argtypes = [C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+    L.ll_dbg_time_decode.restype = C.c_int
+    L.ll_dbg_time_decode.argtypes = [C.c_int32, C.POINTER(C.c_float)]
+    _lib = L
+    return L
+
+
+def _check(rc):
+    if rc < 0:
+        raise LLError(rc, load().ll_last_error().decode())
+    return rc
+
+
+def make_config(cfg, flags=0):
+    return LLConfig(**{k: int(cfg[k]) for k in ("n_layers", "d_model", "n_heads", "head_dim",
+                                                  "ffn_hidden", "vocab", "max_seq")},
+                    rope_theta=float(cfg["rope_theta"]), rms_eps=float(cfg["rms_eps"]), flags=flags)
+
+
+def ll_workspace_bytes(cfg, flags=0):
+    c = make_config(cfg, flags)
+    return int(load().ll_workspace_bytes(C.byref(c)))
+
+
+def ll_last_error():
+    return load().ll_last_error().decode()
+
+
+class Session:
+    """Owns the torch tensors the library points into, for the life of one ll_init()."""
+
+    def __init__(self, cfg, weights, flags=0, stream=None, device="cuda:0"):
+        """``weights``: dict of fp16 torch tensors on ``device`` (see workloads.weight_shapes)."""
+        import torch
+        self.torch = torch
+        self.cfg = dict(cfg)
+        self.lib = load()
+        self.device = torch.device(device)
+        self.stream = stream if stream is not None else torch.cuda.Stream(device=self.device)
+        self._weights = weights
+        for name, t in self._iter_weights(weights):
+            if t.dtype != torch.float16 or not t.is_contiguous() or t.device.type != "cuda":
+                raise ValueError("weight %s must be a contiguous fp16 CUDA tensor" % name)
+        self._layers = (LLLayerWeights * cfg["n_layers"])()
+        for i, Lw in enumerate(weights["layers"]):
+            for k in LAYER_KEYS:
+                setattr(self._layers[i], k, Lw[k].data_ptr())
+        self._w = LLWeights(tok_emb=weights["tok_emb"].data_ptr(),
+                            layers=C.cast(self._layers, C.POINTER(LLLayerWeights)),
+                            final_norm=weights["final_norm"].data_ptr(),
+                            lm_head=weights["lm_head"].data_ptr())
+        self._cfg = make_config(cfg, flags)
+        nbytes = int(self.lib.ll_workspace_bytes(C.byref(self._cfg)))
+        if nbytes == 0:
+            raise LLError(LL_E_BAD_CONFIG, "ll_workspace_bytes rejected the configuration")
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        base = self.workspace.data_ptr()
+        self._ws_ptr = (base + 255) // 256 * 256
+        torch.cuda.synchronize(self.device)
+        _check(self.lib.ll_init(C.byref(self._cfg), C.byref(self._w), C.c_void_p(self._ws_ptr),
+                                C.c_size_t(nbytes), C.c_void_p(self.stream.cuda_stream)))
+        self.open = True
+
+    @staticmethod
+    def _iter_weights(w):
+        for k, v in w.items():
+            if k == "layers":
+                for i, Lw in enumerate(v):
+                    for kk, vv in Lw.items():
+                        yield "layers[%d].%s" % (i, kk), vv
+            else:
+                yield k, v
+
+    # ---- the four calls ------------------------------------------------
+    def ll_prefill(self, tokens):
+        arr = np.ascontiguousarray(tokens, dtype=np.int32)
+        return _check(self.lib.ll_prefill(arr.ctypes.data_as(C.POINTER(C.c_int32)), arr.shape[0]))
+
+    def ll_decode_step(self):
+        return _check(self.lib.ll_decode_step())
+
+    def ll_decode_n(self, k):
+        out = np.empty(k, dtype=np.int32)
+        _check(self.lib.ll_decode_n(k, out.ctypes.data_as(C.POINTER(C.c_int32))))
+        return out
+
+    def ll_reset(self):
+        return _check(self.lib.ll_reset())
+
+    def ll_shutdown(self):
+        if self.open:
+            self.open = False
+            return _check(self.lib.ll_shutdown())
+        return 0
+
+    close = ll_shutdown
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def ll_max_prompt(self):
+        return _check(self.lib.ll_max_prompt())
+
+    def ll_position(self):
+        return _check(self.lib.ll_position())
+
+    # ---- hooks ---------------------------------------------------------
+    def ll_dbg_get_logits(self):
+        out = np.empty(self.cfg["vocab"], dtype=np.float32)
+        _check(self.lib.ll_dbg_get_logits(out.ctypes.data_as(C.POINTER(C.c_float))))
+        return out
+
+    def ll_dbg_get_hidden(self):
+        out = np.empty(self.cfg["d_model"], dtype=np.float32)
+        _check(self.lib.ll_dbg_get_hidden(out.ctypes.data_as(C.POINTER(C.c_float))))
+        return out
+
+    def ll_dbg_force_next_token(self, tok):
+        return _check(self.lib.ll_dbg_force_next_token(int(tok)))
+
+    def ll_dbg_get_kv(self, layer, which, n_pos):
+        out = np.empty((n_pos, self.cfg["d_model"]), dtype=np.float32)
+        _check(self.lib.ll_dbg_get_kv(layer, which, n_pos, out.ctypes.data_as(C.POINTER(C.c_float))))
+        return out
+
+    def ll_dbg_profile_decode(self, steps):
+        us = np.zeros(len(KERNEL_CLASSES), dtype=np.float32)
+        n = np.zeros(len(KERNEL_CLASSES), dtype=np.int32)
+        _check(self.lib.ll_dbg_profile_decode(steps, us.ctypes.data_as(C.POINTER(C.c_float)),
+                                              n.ctypes.data_as(C.POINTER(C.c_int32))))
+        return {k: (float(us[i]), int(n[i])) for i, k in enumerate(KERNEL_CLASSES)}
+
+    def ll_dbg_time_decode(self, k):
+        ms = C.c_float(0.0)
+        _check(self.lib.ll_dbg_time_decode(k, C.byref(ms)))
+        return float(ms.value)

@@ -1,0 +1,70 @@
+// Device-side types and wave-level helpers shared by the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef _Float16 half_t;
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+// Per-step dynamic values.  They live in device memory so that one captured
+// graph serves every position: kernels read them, the last kernel of a step
+// advances them (the paper keeps these on the host, Sec. III-A "dynamic
+// operations"; here they never leave the GPU).
+struct DevState {
+  int32_t pos;         // cached positions = position of the token fed next
+  int32_t next_token;  // token the next decode step feeds
+  int32_t n_prompt;    // prompt length of the prefill in flight
+  int32_t steps;       // tokens produced since reset (index into the host ring)
+  int32_t pad[12];
+};
+
+#define LL_WAVE 64
+#define LL_WG 256
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over aligned groups of N lanes (N = 8 or 16) with DPP only: two quad
+// permutes, then a mirror inside each half row, then a mirror of the row.
+template <int N>
+__device__ __forceinline__ float group_sum(float v) {
+  v += dpp_mov<0xB1>(v);   // quad_perm [1,0,3,2]
+  v += dpp_mov<0x4E>(v);   // quad_perm [2,3,0,1]
+  v += dpp_mov<0x141>(v);  // row_half_mirror
+  if (N == 16) v += dpp_mov<0x140>(v);  // row_mirror
+  return v;
+}
+
+// Sum over the 64 lanes of a wave; the result is wave-uniform.
+__device__ __forceinline__ float wave_sum(float v) {
+  v = group_sum<16>(v);
+  int b = __builtin_bit_cast(int, v);
+  float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+  float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+  float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+  float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+  return (r0 + r1) + (r2 + r3);
+}
+
+// 16-byte streaming load of weights that are read exactly once per step.
+__device__ __forceinline__ h8 load_stream(const half_t* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const h8*>(p));
+}
+
+__device__ __forceinline__ float dot8(h8 w, f4 x0, f4 x1, float acc) {
+  acc += (float)w[0] * x0[0];
+  acc += (float)w[1] * x0[1];
+  acc += (float)w[2] * x0[2];
+  acc += (float)w[3] * x0[3];
+  acc += (float)w[4] * x1[0];
+  acc += (float)w[5] * x1[1];
+  acc += (float)w[6] * x1[2];
+  acc += (float)w[7] * x1[3];
+  return acc;
+}

@@ -1,0 +1,689 @@
+// C ABI of the decode / prefill path (see include/ll.h): workspace carving,
+// kernel chains, hipGraph capture and replay, device-resident step state.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/ll.h"
+#include "decode_kernels.h"
+#include "prefill_kernels.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define HIPCHK(expr)                                                                      \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess)                                                                 \
+      return fail(LL_E_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, \
+                  __LINE__);                                                              \
+  } while (0)
+
+constexpr int kGemvU = 4;          // 512-element chunks of a weight row in flight per lane and row
+constexpr int kAttnMaxSplits = 16;
+constexpr int kMaxPromptBucket = 512;
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+bool config_ok(const ll_config* c, const char** why) {
+  const char* w = nullptr;
+  if (!c) w = "null config";
+  else if (c->n_layers < 1 || c->vocab < 1) w = "n_layers and vocab must be >= 1";
+  else if (c->head_dim != 64 && c->head_dim != 128) w = "head_dim must be 64 or 128";
+  else if (c->n_heads < 1 || (int64_t)c->n_heads * c->head_dim != c->d_model) w = "n_heads * head_dim != d_model";
+  else if (c->d_model % 8 || c->ffn_hidden % 8 || c->ffn_hidden < 8) w = "d_model and ffn_hidden must be multiples of 8";
+  else if (c->max_seq < 2 || c->max_seq > (1 << 20)) w = "max_seq out of range";
+  else if (!(c->rope_theta > 0.f) || !(c->rms_eps >= 0.f)) w = "bad rope_theta / rms_eps";
+  if (why) *why = w;
+  return w == nullptr;
+}
+
+int prompt_bucket(int n) {   // smallest of {64,128,256,512} holding n rows
+  int b = 64;
+  while (b < n) b <<= 1;
+  return b;
+}
+
+struct Layout {
+  size_t kv, rope, x, q, o, m, attn_part, attn_cnt, logits, amax_val, amax_idx, state, tokens;
+  size_t pf_x, pf_xn, pf_qkv, pf_q, pf_o, pf_gu, pf_h;
+  size_t total;
+  int attn_splits, lm_wgs, max_prompt, mb_max;
+  size_t kv_layer_halves;   // halves per layer per K or V
+};
+
+int gemv_grid(int pairs) {
+  // ~3 workgroups per CU keep enough 16-byte loads in flight; never more waves than row pairs
+  const int want = 256 * 3;
+  const int need = (pairs + (LL_WG / 64) - 1) / (LL_WG / 64);
+  return need < want ? (need < 1 ? 1 : need) : want;
+}
+
+Layout make_layout(const ll_config& c) {
+  Layout L{};
+  const size_t d = c.d_model, F = c.ffn_hidden, V = c.vocab;
+  L.attn_splits = 256 / c.n_heads;
+  if (L.attn_splits < 1) L.attn_splits = 1;
+  if (L.attn_splits > kAttnMaxSplits) L.attn_splits = kAttnMaxSplits;
+  L.lm_wgs = gemv_grid((c.vocab + 1) / 2);
+  L.max_prompt = c.max_seq - 1 < kMaxPromptBucket ? c.max_seq - 1 : kMaxPromptBucket;
+  L.mb_max = prompt_bucket(L.max_prompt);
+  L.kv_layer_halves = (size_t)c.n_heads * c.max_seq * c.head_dim;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  L.kv = take((size_t)c.n_layers * 2 * L.kv_layer_halves * 2);
+  L.rope = take((size_t)c.max_seq * (c.head_dim / 2) * sizeof(float2));
+  L.x = take(d * 4);
+  L.q = take(d * 4);
+  L.o = take(d * 4);
+  L.m = take(F * 4);
+  L.attn_part = take((size_t)c.n_heads * L.attn_splits * (c.head_dim + 2) * 4);
+  L.attn_cnt = take((size_t)c.n_heads * 4);
+  L.logits = take(V * 4);
+  L.amax_val = take((size_t)L.lm_wgs * 4);
+  L.amax_idx = take((size_t)L.lm_wgs * 4);
+  L.state = take(sizeof(DevState));
+  L.tokens = take((size_t)L.mb_max * 4);
+  const size_t M = L.mb_max;
+  L.pf_x = take(M * d * 4);
+  L.pf_xn = take(M * d * 2);
+  L.pf_qkv = take(M * 3 * d * 4);
+  L.pf_q = take(M * d * 2);
+  L.pf_o = take(M * d * 2);
+  L.pf_gu = take(M * 2 * F * 4);
+  L.pf_h = take(M * F * 2);
+  L.total = off;
+  return L;
+}
+
+struct Instance {
+  ll_config cfg;
+  Layout L;
+  std::vector<ll_layer_weights> layers;
+  ll_weights w;
+  char* ws = nullptr;
+  hipStream_t stream = nullptr;
+  bool own_stream = false;
+  hipGraph_t dec_graph = nullptr;
+  hipGraphExec_t dec_exec = nullptr;
+  std::vector<int> pf_buckets;
+  std::vector<hipGraph_t> pf_graph;
+  std::vector<hipGraphExec_t> pf_exec;
+  int* host_ring = nullptr;      // pinned, device-visible; kernels write generated ids here
+  int* dev_ring = nullptr;       // device address of host_ring
+  int ring_size = 0;
+  int* host_stage = nullptr;     // pinned staging for the prompt ids + DevState
+  // host mirror of the device state (never read back from the GPU on the hot path)
+  int pos = 0, steps = 0;
+  bool last_was_prefill = false;
+  // profiling hook: when set, every decode launch is bracketed by events
+  std::vector<hipEvent_t>* prof_events = nullptr;
+  std::vector<int>* prof_class = nullptr;
+
+  template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+  half_t* kcache(int layer) const { return at<half_t>(L.kv) + (size_t)layer * 2 * L.kv_layer_halves; }
+  half_t* vcache(int layer) const { return kcache(layer) + L.kv_layer_halves; }
+  DevState* state() const { return at<DevState>(L.state); }
+};
+
+Instance* g = nullptr;
+
+size_t gemv_lds_bytes(int K) {
+  const int nch = (K + 511) / 512;
+  const int nchp = (nch + kGemvU - 1) / kGemvU * kGemvU;
+  return ((size_t)nchp * 512 + 8) * sizeof(float);
+}
+
+struct ProfScope {
+  Instance* I;
+  hipStream_t s;
+  ProfScope(Instance* inst, hipStream_t st, int klass) : I(inst), s(st) {
+    if (I->prof_events) {
+      hipEvent_t e;
+      (void)hipEventCreate(&e);
+      (void)hipEventRecord(e, s);
+      I->prof_events->push_back(e);
+      I->prof_class->push_back(klass);
+    }
+  }
+  ~ProfScope() {
+    if (I->prof_events) {
+      hipEvent_t e;
+      (void)hipEventCreate(&e);
+      (void)hipEventRecord(e, s);
+      I->prof_events->push_back(e);
+    }
+  }
+};
+
+template <int MODE>
+void launch_gemv(const GemvArgs& a, int pairs, int grid_override, hipStream_t s) {
+  const int grid = grid_override > 0 ? grid_override : gemv_grid(pairs);
+  hipLaunchKernelGGL((gemv_kernel<MODE, kGemvU>), dim3(grid), dim3(LL_WG), gemv_lds_bytes(a.K), s, a);
+}
+
+// final RMSNorm + LM head + argmax + state advance, shared by decode and prefill
+void enqueue_head(Instance* I, hipStream_t s, const float* xin, int from_prompt_row, int prefill) {
+  const ll_config& c = I->cfg;
+  {
+    ProfScope ps(I, s, LL_KC_LMHEAD);
+    GemvArgs a{};
+    a.w0 = (const half_t*)I->w.lm_head;
+    a.xin = xin;
+    a.gain = (const half_t*)I->w.final_norm;
+    a.out = I->at<float>(I->L.logits);
+    a.N = c.vocab;
+    a.K = c.d_model;
+    a.eps = c.rms_eps;
+    a.st = I->state();
+    a.amax_val = I->at<float>(I->L.amax_val);
+    a.amax_idx = I->at<int>(I->L.amax_idx);
+    a.x_row_from_prompt = from_prompt_row;
+    launch_gemv<GM_LMHEAD>(a, (c.vocab + 1) / 2, I->L.lm_wgs, s);
+  }
+  {
+    ProfScope ps(I, s, LL_KC_SAMPLE);
+    hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(LL_WG), 0, s, I->at<float>(I->L.amax_val),
+                       I->at<int>(I->L.amax_idx), I->L.lm_wgs, I->state(), I->dev_ring, I->ring_size,
+                       prefill);
+  }
+}
+
+void enqueue_decode(Instance* I, hipStream_t s) {
+  const ll_config& c = I->cfg;
+  const int d = c.d_model, F = c.ffn_hidden;
+  float* x = I->at<float>(I->L.x);
+  float* q = I->at<float>(I->L.q);
+  float* o = I->at<float>(I->L.o);
+  float* m = I->at<float>(I->L.m);
+  {
+    ProfScope ps(I, s, LL_KC_EMBED);
+    hipLaunchKernelGGL(embed_kernel, dim3((d + LL_WG * 8 - 1) / (LL_WG * 8)), dim3(LL_WG), 0, s,
+                       (const half_t*)I->w.tok_emb, I->state(), x, d);
+  }
+  for (int l = 0; l < c.n_layers; ++l) {
+    const ll_layer_weights& W = I->layers[l];
+    {
+      ProfScope ps(I, s, LL_KC_QKV);
+      GemvArgs a{};
+      a.w0 = (const half_t*)W.wq; a.w1 = (const half_t*)W.wk; a.w2 = (const half_t*)W.wv;
+      a.xin = x; a.gain = (const half_t*)W.attn_norm; a.out = q;
+      a.N = d; a.K = d; a.eps = c.rms_eps;
+      a.kcache = I->kcache(l); a.vcache = I->vcache(l);
+      a.rope = I->at<float2>(I->L.rope); a.st = I->state();
+      a.head_dim = c.head_dim; a.max_seq = c.max_seq;
+      launch_gemv<GM_QKV>(a, 3 * d / 2, 0, s);
+    }
+    {
+      ProfScope ps(I, s, LL_KC_ATTN);
+      dim3 grid(c.n_heads, I->L.attn_splits);
+      if (c.head_dim == 128)
+        hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(LL_WG), 0, s, q, I->kcache(l),
+                           I->vcache(l), I->state(), I->at<float>(I->L.attn_part),
+                           I->at<unsigned>(I->L.attn_cnt), o, c.max_seq);
+      else
+        hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(LL_WG), 0, s, q, I->kcache(l),
+                           I->vcache(l), I->state(), I->at<float>(I->L.attn_part),
+                           I->at<unsigned>(I->L.attn_cnt), o, c.max_seq);
+    }
+    {
+      ProfScope ps(I, s, LL_KC_OPROJ);
+      GemvArgs a{};
+      a.w0 = (const half_t*)W.wo; a.xin = o; a.out = x; a.N = d; a.K = d;
+      launch_gemv<GM_ORES>(a, d / 2, 0, s);
+    }
+    {
+      ProfScope ps(I, s, LL_KC_GATEUP);
+      GemvArgs a{};
+      a.w0 = (const half_t*)W.w_gate; a.w1 = (const half_t*)W.w_up;
+      a.xin = x; a.gain = (const half_t*)W.ffn_norm; a.out = m;
+      a.N = F; a.K = d; a.eps = c.rms_eps;
+      launch_gemv<GM_GATEUP>(a, F, 0, s);
+    }
+    {
+      ProfScope ps(I, s, LL_KC_DOWN);
+      GemvArgs a{};
+      a.w0 = (const half_t*)W.w_down; a.xin = m; a.out = x; a.N = d; a.K = F;
+      launch_gemv<GM_DOWN>(a, d / 2, 0, s);
+    }
+  }
+  enqueue_head(I, s, x, 0, 0);
+}
+
+void launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0, const void* w1,
+                 const void* w2, int nmat, float* C, int ldc, int N, int K, int Mb) {
+  GemmArgs ga{};
+  ga.A = A;
+  ga.W[0] = (const half_t*)w0; ga.W[1] = (const half_t*)w1; ga.W[2] = (const half_t*)w2;
+  ga.C = C; ga.st = I->state();
+  ga.N = N; ga.K = K; ga.ldc = ldc; ga.nmat = nmat;
+  ga.mtiles = Mb / PF_BM;
+  ga.ntiles = (N + PF_BN - 1) / PF_BN;
+  const int total_nt = ga.ntiles * nmat;
+  const int tiles = ga.mtiles * total_nt;
+  const int ktiles = (K + PF_BK - 1) / PF_BK;
+  int ks = (1024 + tiles - 1) / tiles;           // aim at >= ~1024 workgroups
+  if (ks > ktiles / 2) ks = ktiles / 2;
+  if (ks < 1) ks = 1;
+  ga.kt_per_split = (ktiles + ks - 1) / ks;
+  ks = (ktiles + ga.kt_per_split - 1) / ga.kt_per_split;
+  const int nt_rounds = (total_nt + 7) / 8;      // n-tiles are dealt to the 8 XCDs
+  dim3 grid(nt_rounds * ga.mtiles * 8, ks);
+  hipLaunchKernelGGL(pf_gemm_kernel, grid, dim3(LL_WG), 0, s, ga);
+}
+
+void enqueue_prefill(Instance* I, hipStream_t s, int Mb) {
+  const ll_config& c = I->cfg;
+  const int d = c.d_model, F = c.ffn_hidden;
+  float* X = I->at<float>(I->L.pf_x);
+  half_t* Xn = I->at<half_t>(I->L.pf_xn);
+  float* QKV = I->at<float>(I->L.pf_qkv);
+  half_t* Qh = I->at<half_t>(I->L.pf_q);
+  half_t* Oh = I->at<half_t>(I->L.pf_o);
+  float* GU = I->at<float>(I->L.pf_gu);
+  half_t* Hm = I->at<half_t>(I->L.pf_h);
+  hipLaunchKernelGGL(pf_embed_kernel, dim3(Mb, (d + LL_WG * 8 - 1) / (LL_WG * 8)), dim3(LL_WG), 0, s,
+                     (const half_t*)I->w.tok_emb, I->at<int>(I->L.tokens), I->state(), X, d);
+  for (int l = 0; l < c.n_layers; ++l) {
+    const ll_layer_weights& W = I->layers[l];
+    hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(LL_WG), 0, s, X, (const half_t*)W.attn_norm,
+                       Xn, d, c.rms_eps, QKV, 3 * d);
+    launch_gemm(I, s, Xn, W.wq, W.wk, W.wv, 3, QKV, 3 * d, d, d, Mb);
+    hipLaunchKernelGGL(pf_rope_kv_kernel, dim3(Mb), dim3(LL_WG), 0, s, QKV,
+                       I->at<float2>(I->L.rope), I->state(), Qh, I->kcache(l), I->vcache(l), d,
+                       c.head_dim, c.max_seq);
+    dim3 agrid(c.n_heads, Mb / 32);
+    if (c.head_dim == 128)
+      hipLaunchKernelGGL(pf_attn_kernel<128>, agrid, dim3(LL_WG), 0, s, Qh, I->kcache(l),
+                         I->vcache(l), I->state(), Oh, d, c.max_seq);
+    else
+      hipLaunchKernelGGL(pf_attn_kernel<64>, agrid, dim3(LL_WG), 0, s, Qh, I->kcache(l),
+                         I->vcache(l), I->state(), Oh, d, c.max_seq);
+    launch_gemm(I, s, Oh, W.wo, nullptr, nullptr, 1, X, d, d, d, Mb);
+    hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(LL_WG), 0, s, X, (const half_t*)W.ffn_norm,
+                       Xn, d, c.rms_eps, GU, 2 * F);
+    launch_gemm(I, s, Xn, W.w_gate, W.w_up, nullptr, 2, GU, 2 * F, F, d, Mb);
+    hipLaunchKernelGGL(pf_swiglu_kernel, dim3(Mb, (F + LL_WG * 4 - 1) / (LL_WG * 4)), dim3(LL_WG), 0,
+                       s, GU, I->state(), Hm, F);
+    launch_gemm(I, s, Hm, W.w_down, nullptr, nullptr, 1, X, d, d, F, Mb);
+  }
+  enqueue_head(I, s, X, 1, 1);
+}
+
+int capture(Instance* I, hipGraph_t* graph, hipGraphExec_t* exec, int prefill_bucket) {
+  HIPCHK(hipStreamBeginCapture(I->stream, hipStreamCaptureModeThreadLocal));
+  if (prefill_bucket) enqueue_prefill(I, I->stream, prefill_bucket);
+  else enqueue_decode(I, I->stream);
+  hipError_t e = hipStreamEndCapture(I->stream, graph);
+  if (e != hipSuccess) return fail(LL_E_HIP, "hipStreamEndCapture: %s", hipGetErrorString(e));
+  HIPCHK(hipGraphInstantiate(exec, *graph, nullptr, nullptr, 0));
+  return LL_OK;
+}
+
+int write_state(Instance* I, int pos, int next_token, int n_prompt, int steps) {
+  DevState* hs = reinterpret_cast<DevState*>(I->host_stage);
+  memset(hs, 0, sizeof(DevState));
+  hs->pos = pos; hs->next_token = next_token; hs->n_prompt = n_prompt; hs->steps = steps;
+  HIPCHK(hipMemcpyAsync(I->state(), hs, sizeof(DevState), hipMemcpyHostToDevice, I->stream));
+  return LL_OK;
+}
+
+void destroy(Instance* I) {
+  if (!I) return;
+  if (I->dec_exec) (void)hipGraphExecDestroy(I->dec_exec);
+  if (I->dec_graph) (void)hipGraphDestroy(I->dec_graph);
+  for (auto e : I->pf_exec) if (e) (void)hipGraphExecDestroy(e);
+  for (auto gr : I->pf_graph) if (gr) (void)hipGraphDestroy(gr);
+  if (I->host_ring) (void)hipHostFree(I->host_ring);
+  if (I->host_stage) (void)hipHostFree(I->host_stage);
+  if (I->own_stream && I->stream) (void)hipStreamDestroy(I->stream);
+  delete I;
+}
+
+bool eager(const Instance* I) { return (I->cfg.flags & LL_FLAG_EAGER) != 0; }
+
+int run_decode_steps(Instance* I, int k) {
+  for (int i = 0; i < k; ++i) {
+    if (eager(I)) enqueue_decode(I, I->stream);
+    else HIPCHK(hipGraphLaunch(I->dec_exec, I->stream));
+  }
+  if (eager(I)) HIPCHK(hipGetLastError());
+  return LL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ll_last_error(void) { return g_err.c_str(); }
+
+size_t ll_workspace_bytes(const ll_config* cfg) {
+  if (!config_ok(cfg, nullptr)) return 0;
+  return make_layout(*cfg).total;
+}
+
+int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t workspace_bytes,
+            void* hip_stream) {
+  if (g) return fail(LL_E_ALREADY_INIT, "ll_init: already initialised; call ll_shutdown first");
+  const char* why = nullptr;
+  if (!config_ok(cfg, &why)) return fail(LL_E_BAD_CONFIG, "ll_init: %s", why);
+  if (!w || !w->tok_emb || !w->layers || !w->final_norm || !w->lm_head)
+    return fail(LL_E_BAD_ARG, "ll_init: null weight pointer");
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const ll_layer_weights& lw = w->layers[l];
+    if (!lw.attn_norm || !lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.ffn_norm || !lw.w_gate ||
+        !lw.w_up || !lw.w_down)
+      return fail(LL_E_BAD_ARG, "ll_init: null weight pointer in layer %d", l);
+  }
+  if (!workspace) return fail(LL_E_BAD_ARG, "ll_init: null workspace");
+  Layout L = make_layout(*cfg);
+  if (workspace_bytes < L.total)
+    return fail(LL_E_WORKSPACE, "ll_init: workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign)
+    return fail(LL_E_WORKSPACE, "ll_init: workspace must be %zu-byte aligned", kAlign);
+  if (gemv_lds_bytes(cfg->ffn_hidden) > 64 * 1024 || gemv_lds_bytes(cfg->d_model) > 64 * 1024)
+    return fail(LL_E_BAD_CONFIG, "ll_init: d_model / ffn_hidden too large for the LDS-staged GEMV");
+
+  Instance* I = new Instance();
+  I->cfg = *cfg;
+  I->L = L;
+  I->layers.assign(w->layers, w->layers + cfg->n_layers);
+  I->w = *w;
+  I->w.layers = I->layers.data();
+  I->ws = static_cast<char*>(workspace);
+  int rc = LL_OK;
+  auto bail = [&](int code) { destroy(I); return code; };
+
+  if (hip_stream) {
+    I->stream = static_cast<hipStream_t>(hip_stream);
+  } else {
+    hipError_t e = hipStreamCreateWithFlags(&I->stream, hipStreamNonBlocking);
+    if (e != hipSuccess) return bail(fail(LL_E_HIP, "hipStreamCreate: %s", hipGetErrorString(e)));
+    I->own_stream = true;
+  }
+
+  I->ring_size = cfg->max_seq + 1;
+  auto hip_or_bail = [&](hipError_t e, const char* what) {
+    if (e != hipSuccess) { rc = fail(LL_E_HIP, "%s: %s", what, hipGetErrorString(e)); return false; }
+    return true;
+  };
+  if (!hip_or_bail(hipHostMalloc((void**)&I->host_ring, (size_t)I->ring_size * 4, hipHostMallocMapped),
+                   "hipHostMalloc(ring)")) return bail(rc);
+  if (!hip_or_bail(hipHostGetDevicePointer((void**)&I->dev_ring, I->host_ring, 0),
+                   "hipHostGetDevicePointer")) return bail(rc);
+  if (!hip_or_bail(hipHostMalloc((void**)&I->host_stage, sizeof(DevState) + (size_t)L.mb_max * 4 + 64,
+                                 hipHostMallocDefault), "hipHostMalloc(stage)")) return bail(rc);
+  memset(I->host_ring, 0, (size_t)I->ring_size * 4);
+
+  // RoPE table: angle pos * theta^(-2j/head_dim) and its cos/sin in double, stored as float
+  {
+    const int hh = cfg->head_dim / 2;
+    std::vector<float2> tab((size_t)cfg->max_seq * hh);
+    std::vector<double> inv_freq(hh);
+    for (int j = 0; j < hh; ++j)
+      inv_freq[j] = std::pow((double)cfg->rope_theta, -2.0 * (double)j / (double)cfg->head_dim);
+    for (int p = 0; p < cfg->max_seq; ++p)
+      for (int j = 0; j < hh; ++j) {
+        const double phi = (double)p * inv_freq[j];
+        tab[(size_t)p * hh + j] = make_float2((float)std::cos(phi), (float)std::sin(phi));
+      }
+    if (!hip_or_bail(hipMemcpy(I->at<float2>(L.rope), tab.data(), tab.size() * sizeof(float2),
+                               hipMemcpyHostToDevice), "hipMemcpy(rope)")) return bail(rc);
+  }
+  if (!hip_or_bail(hipMemset(I->at<unsigned>(L.attn_cnt), 0, (size_t)cfg->n_heads * 4), "hipMemset(cnt)"))
+    return bail(rc);
+  if (!hip_or_bail(hipMemset(I->state(), 0, sizeof(DevState)), "hipMemset(state)")) return bail(rc);
+  if (!hip_or_bail(hipMemset(I->at<int>(L.tokens), 0, (size_t)L.mb_max * 4), "hipMemset(tokens)"))
+    return bail(rc);
+  if (!hip_or_bail(hipDeviceSynchronize(), "hipDeviceSynchronize")) return bail(rc);
+
+  for (int b = 64; b <= L.mb_max; b <<= 1) I->pf_buckets.push_back(b);
+
+  // Warm-up: one eager pass of every kernel chain (loads the code objects, so
+  // nothing is compiled or loaded inside a capture), on state that is reset
+  // afterwards.  Token 0 at position 0 / a one-token prompt touch only valid memory.
+  if ((rc = write_state(I, 0, 0, 1, 0)) != LL_OK) return bail(rc);
+  enqueue_decode(I, I->stream);
+  for (int b : I->pf_buckets) {
+    if ((rc = write_state(I, 0, 0, 1, 0)) != LL_OK) return bail(rc);
+    enqueue_prefill(I, I->stream, b);
+  }
+  if (!hip_or_bail(hipStreamSynchronize(I->stream), "warm-up")) return bail(rc);
+  if (!hip_or_bail(hipGetLastError(), "warm-up launch")) return bail(rc);
+
+  if (!(cfg->flags & LL_FLAG_EAGER)) {
+    if ((rc = capture(I, &I->dec_graph, &I->dec_exec, 0)) != LL_OK) return bail(rc);
+    I->pf_graph.assign(I->pf_buckets.size(), nullptr);
+    I->pf_exec.assign(I->pf_buckets.size(), nullptr);
+    for (size_t i = 0; i < I->pf_buckets.size(); ++i)
+      if ((rc = capture(I, &I->pf_graph[i], &I->pf_exec[i], I->pf_buckets[i])) != LL_OK) return bail(rc);
+  }
+  if ((rc = write_state(I, 0, 0, 0, 0)) != LL_OK) return bail(rc);
+  if (!hip_or_bail(hipStreamSynchronize(I->stream), "init sync")) return bail(rc);
+  I->pos = 0;
+  I->steps = 0;
+  g = I;
+  g_err.clear();
+  return LL_OK;
+}
+
+int ll_shutdown(void) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_shutdown: not initialised");
+  (void)hipStreamSynchronize(g->stream);
+  destroy(g);
+  g = nullptr;
+  return LL_OK;
+}
+
+int ll_reset(void) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_reset: not initialised");
+  int rc = write_state(g, 0, 0, 0, 0);
+  if (rc != LL_OK) return rc;
+  HIPCHK(hipStreamSynchronize(g->stream));
+  g->pos = 0;
+  g->steps = 0;
+  return LL_OK;
+}
+
+int32_t ll_max_prompt(void) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_max_prompt: not initialised");
+  return g->L.max_prompt;
+}
+
+int32_t ll_position(void) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_position: not initialised");
+  return g->pos;
+}
+
+int32_t ll_prefill(const int32_t* tokens, int32_t n) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_prefill: not initialised");
+  Instance* I = g;
+  if (!tokens) return fail(LL_E_BAD_ARG, "ll_prefill: null tokens");
+  if (n < 1) return fail(LL_E_BAD_ARG, "ll_prefill: n = %d < 1", n);
+  if (I->pos != 0) return fail(LL_E_STATE, "ll_prefill: context holds %d positions; call ll_reset", I->pos);
+  if (n + 1 > I->cfg.max_seq) return fail(LL_E_CAPACITY, "ll_prefill: n + 1 = %d > max_seq = %d", n + 1, I->cfg.max_seq);
+  if (n > I->L.max_prompt) return fail(LL_E_CAPACITY, "ll_prefill: n = %d > ll_max_prompt() = %d", n, I->L.max_prompt);
+  for (int i = 0; i < n; ++i)
+    if (tokens[i] < 0 || tokens[i] >= I->cfg.vocab)
+      return fail(LL_E_BAD_ARG, "ll_prefill: tokens[%d] = %d outside [0, %d)", i, tokens[i], I->cfg.vocab);
+
+  const int Mb = prompt_bucket(n);
+  // prompt ids and the state block travel in one pinned staging buffer
+  DevState* hs = reinterpret_cast<DevState*>(I->host_stage);
+  int* htok = reinterpret_cast<int*>(reinterpret_cast<char*>(I->host_stage) + sizeof(DevState));
+  memset(hs, 0, sizeof(DevState));
+  hs->n_prompt = n;
+  memcpy(htok, tokens, (size_t)n * 4);
+  HIPCHK(hipMemcpyAsync(I->state(), hs, sizeof(DevState), hipMemcpyHostToDevice, I->stream));
+  HIPCHK(hipMemcpyAsync(I->at<int>(I->L.tokens), htok, (size_t)n * 4, hipMemcpyHostToDevice, I->stream));
+  if (eager(I)) {
+    enqueue_prefill(I, I->stream, Mb);
+    HIPCHK(hipGetLastError());
+  } else {
+    size_t bi = 0;
+    while (I->pf_buckets[bi] != Mb) ++bi;
+    HIPCHK(hipGraphLaunch(I->pf_exec[bi], I->stream));
+  }
+  HIPCHK(hipStreamSynchronize(I->stream));
+  I->pos = n;
+  I->steps = 1;
+  I->last_was_prefill = true;
+  return I->host_ring[0];
+}
+
+int32_t ll_decode_n(int32_t k, int32_t* out_tokens) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_decode_n: not initialised");
+  Instance* I = g;
+  if (k < 1) return fail(LL_E_BAD_ARG, "ll_decode_n: k = %d < 1", k);
+  if (I->pos == 0) return fail(LL_E_STATE, "ll_decode: empty context; call ll_prefill first");
+  if (I->pos + k > I->cfg.max_seq)
+    return fail(LL_E_CAPACITY, "ll_decode: %d cached + %d steps > max_seq = %d", I->pos, k, I->cfg.max_seq);
+  if (I->steps + k > I->ring_size)
+    return fail(LL_E_CAPACITY, "ll_decode: token ring full");
+  int rc = run_decode_steps(I, k);
+  if (rc != LL_OK) return rc;
+  HIPCHK(hipStreamSynchronize(I->stream));
+  if (out_tokens) memcpy(out_tokens, I->host_ring + I->steps, (size_t)k * 4);
+  I->pos += k;
+  I->steps += k;
+  I->last_was_prefill = false;
+  return I->host_ring[I->steps - 1];
+}
+
+int32_t ll_decode_step(void) { return ll_decode_n(1, nullptr); }
+
+int ll_dbg_get_logits(float* host_out) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_dbg_get_logits: not initialised");
+  if (!host_out) return fail(LL_E_BAD_ARG, "ll_dbg_get_logits: null output");
+  HIPCHK(hipStreamSynchronize(g->stream));
+  HIPCHK(hipMemcpy(host_out, g->at<float>(g->L.logits), (size_t)g->cfg.vocab * 4, hipMemcpyDeviceToHost));
+  return LL_OK;
+}
+
+int ll_dbg_get_hidden(float* host_out) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_dbg_get_hidden: not initialised");
+  if (!host_out) return fail(LL_E_BAD_ARG, "ll_dbg_get_hidden: null output");
+  if (g->pos == 0) return fail(LL_E_STATE, "ll_dbg_get_hidden: no step has run");
+  HIPCHK(hipStreamSynchronize(g->stream));
+  const float* src = g->last_was_prefill
+                         ? g->at<float>(g->L.pf_x) + (size_t)(g->pos - 1) * g->cfg.d_model
+                         : g->at<float>(g->L.x);
+  HIPCHK(hipMemcpy(host_out, src, (size_t)g->cfg.d_model * 4, hipMemcpyDeviceToHost));
+  return LL_OK;
+}
+
+int ll_dbg_force_next_token(int32_t tok) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_dbg_force_next_token: not initialised");
+  if (tok < 0 || tok >= g->cfg.vocab) return fail(LL_E_BAD_ARG, "ll_dbg_force_next_token: bad token %d", tok);
+  if (g->pos == 0) return fail(LL_E_STATE, "ll_dbg_force_next_token: empty context");
+  int* h = g->host_stage;
+  *h = tok;
+  HIPCHK(hipMemcpyAsync(&g->state()->next_token, h, 4, hipMemcpyHostToDevice, g->stream));
+  HIPCHK(hipStreamSynchronize(g->stream));
+  return LL_OK;
+}
+
+int ll_dbg_get_kv(int32_t layer, int32_t which, int32_t n_pos, float* host_out) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_dbg_get_kv: not initialised");
+  const ll_config& c = g->cfg;
+  if (layer < 0 || layer >= c.n_layers || (which != 0 && which != 1) || n_pos < 0 || n_pos > c.max_seq || !host_out)
+    return fail(LL_E_BAD_ARG, "ll_dbg_get_kv: bad argument");
+  HIPCHK(hipStreamSynchronize(g->stream));
+  std::vector<uint16_t> tmp(g->L.kv_layer_halves);
+  const half_t* src = which ? g->vcache(layer) : g->kcache(layer);
+  HIPCHK(hipMemcpy(tmp.data(), src, tmp.size() * 2, hipMemcpyDeviceToHost));
+  for (int h = 0; h < c.n_heads; ++h)
+    for (int p = 0; p < n_pos; ++p)
+      for (int e = 0; e < c.head_dim; ++e) {
+        uint16_t bits = tmp[((size_t)h * c.max_seq + p) * c.head_dim + e];
+        _Float16 v;
+        memcpy(&v, &bits, 2);
+        host_out[(size_t)p * c.d_model + h * c.head_dim + e] = (float)v;
+      }
+  return LL_OK;
+}
+
+int ll_dbg_profile_decode(int32_t steps, float* us_out, int32_t* launches_out) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_dbg_profile_decode: not initialised");
+  Instance* I = g;
+  if (steps < 1 || !us_out) return fail(LL_E_BAD_ARG, "ll_dbg_profile_decode: bad argument");
+  if (I->pos == 0) return fail(LL_E_STATE, "ll_dbg_profile_decode: empty context");
+  if (I->pos + steps > I->cfg.max_seq || I->steps + steps > I->ring_size)
+    return fail(LL_E_CAPACITY, "ll_dbg_profile_decode: would run past max_seq");
+  double sum[LL_KC_COUNT] = {0};
+  long cnt[LL_KC_COUNT] = {0};
+  for (int sidx = 0; sidx < steps; ++sidx) {
+    std::vector<hipEvent_t> ev;
+    std::vector<int> kc;
+    I->prof_events = &ev;
+    I->prof_class = &kc;
+    enqueue_decode(I, I->stream);
+    I->prof_events = nullptr;
+    I->prof_class = nullptr;
+    hipError_t e = hipStreamSynchronize(I->stream);
+    if (e == hipSuccess) {
+      for (size_t i = 0; i < kc.size(); ++i) {
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]);
+        sum[kc[i]] += ms * 1000.0;
+        cnt[kc[i]] += 1;
+      }
+    }
+    for (auto x : ev) (void)hipEventDestroy(x);
+    if (e != hipSuccess) return fail(LL_E_HIP, "profile: %s", hipGetErrorString(e));
+  }
+  I->pos += steps;
+  I->steps += steps;
+  I->last_was_prefill = false;
+  for (int i = 0; i < LL_KC_COUNT; ++i) {
+    us_out[i] = cnt[i] ? (float)(sum[i] / cnt[i]) : 0.f;
+    if (launches_out) launches_out[i] = (int32_t)(cnt[i] / steps);
+  }
+  return LL_OK;
+}
+
+int ll_dbg_time_decode(int32_t k, float* ms_out) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_dbg_time_decode: not initialised");
+  Instance* I = g;
+  if (k < 1 || !ms_out) return fail(LL_E_BAD_ARG, "ll_dbg_time_decode: bad argument");
+  if (I->pos == 0) return fail(LL_E_STATE, "ll_dbg_time_decode: empty context");
+  if (I->pos + k > I->cfg.max_seq || I->steps + k > I->ring_size)
+    return fail(LL_E_CAPACITY, "ll_dbg_time_decode: would run past max_seq");
+  hipEvent_t e0, e1;
+  HIPCHK(hipEventCreate(&e0));
+  HIPCHK(hipEventCreate(&e1));
+  HIPCHK(hipEventRecord(e0, I->stream));
+  int rc = run_decode_steps(I, k);
+  if (rc == LL_OK) {
+    (void)hipEventRecord(e1, I->stream);
+    hipError_t e = hipStreamSynchronize(I->stream);
+    if (e != hipSuccess) rc = fail(LL_E_HIP, "time_decode: %s", hipGetErrorString(e));
+    else (void)hipEventElapsedTime(ms_out, e0, e1);
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc != LL_OK) return rc;
+  I->pos += k;
+  I->steps += k;
+  I->last_was_prefill = false;
+  return LL_OK;
+}
+
+}  // extern "C"

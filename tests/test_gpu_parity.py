@@ -1,0 +1,265 @@
+"""Parity of the HIP path (called through the C ABI) against the CPU oracle on
+the same seeded inputs.  Needs a real MI355X: run with ``-m gpu``."""
+import numpy as np
+import pytest
+
+from paper_2604_23467_amd import workloads as wl
+from parity_utils import (check_logits, check_token, max_abs, rel_l2, run_teacher_forced,
+                          top2_margin)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need a GPU"
+    return torch
+
+
+def _session(cfg, w_np, flags=0):
+    import torch
+    from paper_2604_23467_amd import binding
+    w_t = wl.weights_to_torch(w_np, device="cuda:0", dtype=torch.float16)
+    return binding.Session(cfg, w_t, flags=flags)
+
+
+# ------------------------------------------------------------ config 1: tiny model
+@pytest.mark.parametrize("flags", [0, 1], ids=["graph", "eager"])
+def test_tiny_config_prefill_and_16_steps(torch_cuda, oracle32, flags):
+    """2 layers, d=256, 4x64 heads, FFN 688, vocab 1024, fp32 weights seed 0,
+    10-token prompt seed 0, prefill + 16 greedy steps.  The oracle keeps the
+    original fp32 weights; the GPU gets them rounded to fp16."""
+    cfg = wl.tiny_cfg(max_seq=64)
+    w = wl.make_weights_numpy(cfg, seed=0)
+    prompt = wl.make_tokens(10, cfg["vocab"], seed=0)
+    om = oracle32.model(cfg, w)
+    with _session(cfg, w, flags) as s:
+        stats = run_teacher_forced(s, om, prompt, 16, "tiny")
+        assert s.ll_position() == 26 and om.pos == 26
+        # K/V rows the GPU cached (fp16) against the oracle's, both layers
+        for layer in range(cfg["n_layers"]):
+            for which in (0, 1):
+                got = s.ll_dbg_get_kv(layer, which, 26)
+                ref = om.kv(layer, which)
+                assert rel_l2(got, ref) < 3e-3, (layer, which, rel_l2(got, ref))
+    om.close()
+    print("tiny worst max-abs %.2e rel-L2 %.2e" % (max(x[0] for x in stats), max(x[1] for x in stats)))
+
+
+def test_tiny_config_fp16_rounded_weights_isolate_kernel_error(torch_cuda, oracle32):
+    """Same run against the oracle on fp16-rounded weights: what is left is the
+    kernels' own error (fp16 KV cache / prefill activations, summation order)."""
+    cfg = wl.tiny_cfg(max_seq=64)
+    w = wl.make_weights_numpy(cfg, seed=0)
+    w16 = wl.weights_astype(w, np.float16)
+    prompt = wl.make_tokens(10, cfg["vocab"], seed=0)
+    om = oracle32.model(cfg, w16)
+    with _session(cfg, w) as s:
+        stats = run_teacher_forced(s, om, prompt, 16, "tiny-fp16w")
+    om.close()
+    assert max(x[1] for x in stats) < 5e-3
+
+
+# ------------------------------------------------------------ shapes, tails, buckets
+SHAPES = [
+    # (n_layers, n_heads, head_dim, ffn, vocab, max_seq, prompt_len, steps)
+    (1, 2, 128, 344, 777, 80, 1, 3),        # head_dim 128, odd vocab, single-token prompt
+    (2, 4, 64, 688, 1024, 200, 63, 2),      # just under a 64-row tile
+    (2, 4, 64, 688, 1024, 200, 64, 2),      # exactly one tile
+    (2, 4, 64, 688, 1024, 200, 65, 2),      # one row into the next bucket
+    (1, 3, 128, 1000, 501, 300, 150, 4),    # d=384 (K not a multiple of 512), ragged FFN
+    (2, 2, 64, 136, 33, 40, 7, 30),         # tiny everything, decode to near max_seq
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "L%d_H%dx%d_F%d_V%d_S%d_p%d" % s[:7])
+def test_shapes_tails_and_buckets(torch_cuda, oracle32, shape):
+    n_layers, H, dh, F, V, max_seq, n_prompt, steps = shape
+    cfg = wl.custom_cfg(n_layers, H, dh, F, V, max_seq)
+    w = wl.weights_astype(wl.make_weights_numpy(cfg, seed=21, gain_jitter=0.1), np.float16)
+    prompt = wl.make_tokens(n_prompt, V, seed=n_prompt)
+    om = oracle32.model(cfg, w)
+    with _session(cfg, w) as s:
+        run_teacher_forced(s, om, prompt, steps, "shape")
+        got = s.ll_dbg_get_kv(n_layers - 1, 0, n_prompt + steps)
+        assert rel_l2(got, om.kv(n_layers - 1, 0)) < 3e-3
+    om.close()
+
+
+def test_larger_activations_exercise_softmax_and_rope(torch_cuda, oracle32):
+    """Weights scaled up so attention is far from uniform and RoPE matters."""
+    cfg = wl.custom_cfg(2, 4, 64, 256, 300, 160)
+    w = wl.make_weights_numpy(cfg, seed=22, gain_jitter=0.2, emb_std=1.0)
+    for L in w["layers"]:
+        for k in ("wq", "wk"):
+            L[k] *= 6.0
+    w = wl.weights_astype(w, np.float16)
+    prompt = wl.make_tokens(90, cfg["vocab"], seed=5)
+    om = oracle32.model(cfg, w)
+    with _session(cfg, w) as s:
+        run_teacher_forced(s, om, prompt, 20, "sharp")
+    om.close()
+
+
+# ------------------------------------------------------------ runtime behaviour
+def test_graph_replay_equals_eager_and_decode_n(torch_cuda):
+    cfg = wl.tiny_cfg(max_seq=64)
+    w = wl.make_weights_numpy(cfg, seed=3)
+    prompt = wl.make_tokens(12, cfg["vocab"], seed=9)
+    runs = {}
+    for name, flags in (("graph", 0), ("eager", 1)):
+        with _session(cfg, w, flags) as s:
+            t1 = s.ll_prefill(prompt)
+            toks = [t1] + [s.ll_decode_step() for _ in range(10)]
+            logits = s.ll_dbg_get_logits()
+            s.ll_reset()
+            assert s.ll_position() == 0
+            t1b = s.ll_prefill(prompt)
+            toks_n = [t1b] + s.ll_decode_n(10).tolist()
+            logits_n = s.ll_dbg_get_logits()
+            runs[name] = (toks, logits, toks_n, logits_n)
+    g, e = runs["graph"], runs["eager"]
+    assert g[0] == g[2] and e[0] == e[2]              # decode_n == repeated decode_step, reset works
+    assert g[0] == e[0]                               # same kernels, same order
+    # decode kernels are deterministic; prefill accumulates split-K partials with atomics
+    assert max_abs(g[1], e[1]) < 1e-4 and max_abs(g[1], g[3]) < 1e-4
+
+
+def test_prefill_matches_token_by_token_decode(torch_cuda, oracle32):
+    """The MFMA prefill and the GEMV decode path are two implementations of the
+    same layer: feeding the prompt through decode steps must give the same
+    logits and cache as one prefill call."""
+    cfg = wl.custom_cfg(2, 4, 64, 688, 512, 128)
+    w = wl.weights_astype(wl.make_weights_numpy(cfg, seed=4, gain_jitter=0.1), np.float16)
+    prompt = wl.make_tokens(40, cfg["vocab"], seed=2)
+    with _session(cfg, w) as s:
+        s.ll_prefill(prompt)
+        lp = s.ll_dbg_get_logits()
+        kp = s.ll_dbg_get_kv(1, 0, 40)
+        s.ll_reset()
+        s.ll_prefill(prompt[:1])
+        for t in prompt[1:]:
+            s.ll_dbg_force_next_token(int(t))
+            s.ll_decode_step()
+        ld = s.ll_dbg_get_logits()
+        kd = s.ll_dbg_get_kv(1, 0, 40)
+    assert rel_l2(lp, ld) < 5e-3 and rel_l2(kp, kd) < 3e-3
+
+
+def test_error_paths_on_device(torch_cuda):
+    from paper_2604_23467_amd import binding as b
+    cfg = wl.custom_cfg(1, 2, 64, 136, 50, 12)
+    w = wl.make_weights_numpy(cfg, seed=5)
+    with _session(cfg, w) as s:
+        assert s.ll_max_prompt() == 11
+        with pytest.raises(b.LLError) as e:
+            s.ll_decode_step()                          # empty context
+        assert e.value.code == b.LL_E_STATE
+        with pytest.raises(b.LLError) as e:
+            s.ll_prefill(np.array([1, 50], dtype=np.int32))   # token out of range
+        assert e.value.code == b.LL_E_BAD_ARG
+        with pytest.raises(b.LLError) as e:
+            s.ll_prefill(np.arange(12, dtype=np.int32))       # n + 1 > max_seq
+        assert e.value.code == b.LL_E_CAPACITY
+        assert s.ll_position() == 0                           # failed calls left the state alone
+        s.ll_prefill(np.arange(5, dtype=np.int32))
+        with pytest.raises(b.LLError) as e:
+            s.ll_prefill(np.arange(5, dtype=np.int32))        # non-empty context
+        assert e.value.code == b.LL_E_STATE
+        s.ll_decode_n(7)                                      # fills the cache to max_seq = 12
+        assert s.ll_position() == 12
+        with pytest.raises(b.LLError) as e:
+            s.ll_decode_step()
+        assert e.value.code == b.LL_E_CAPACITY
+        # a second init while one is live is refused
+        lib = b.load()
+        assert lib.ll_init(s._cfg, s._w, None, 0, None) == b.LL_E_ALREADY_INIT
+        s.ll_reset()
+        assert s.ll_prefill(np.arange(3, dtype=np.int32)) >= 0
+
+
+# ------------------------------------------------------------ config 2: one 7B-shaped layer
+@pytest.mark.parametrize("kv_len", [10, 128, 500])
+def test_one_7b_layer_decode_step(torch_cuda, oracle32, kv_len):
+    """d=4096, 32x128 heads, FFN 11008, fp16 N(0,0.02) weights.  The cache is
+    filled by prefilling kv_len random hidden states (token i's embedding is an
+    N(0,1) row, vocab = kv_len + 1); the step under test feeds row kv_len at
+    position kv_len and attends kv_len + 1 keys.  Hidden state and logits
+    (through a random LM head) are compared."""
+    import torch
+    from paper_2604_23467_amd import binding
+    cfg = wl.llama7b_cfg(n_layers=1, vocab=kv_len + 1, max_seq=kv_len + 2)
+    w_t = wl.make_weights_torch(cfg, seed=0, device="cuda:0", emb_std=1.0)
+    w_np = wl.weights_to_numpy(w_t)
+    prompt = np.arange(kv_len, dtype=np.int32)
+    om = oracle32.model(cfg, w_np)
+    om.prefill(prompt)
+    _, l_ref, h_ref = om.step(kv_len)
+    with binding.Session(cfg, w_t) as s:
+        s.ll_prefill(prompt)
+        s.ll_dbg_force_next_token(kv_len)
+        s.ll_decode_step()
+        h = s.ll_dbg_get_hidden()
+        lg = s.ll_dbg_get_logits()
+        k_gpu = s.ll_dbg_get_kv(0, 0, kv_len + 1)
+    check_logits(h, h_ref, "7B layer kv=%d hidden" % kv_len,
+                 max_abs_tol=3e-2 * max(1.0, float(np.abs(h_ref).max())))
+    check_logits(lg, l_ref, "7B layer kv=%d logits" % kv_len)
+    assert rel_l2(k_gpu, om.kv(0, 0)) < 3e-3
+    om.close()
+
+
+def test_one_7b_layer_long_decode_to_kv_1000(torch_cuda, oracle32):
+    """Decode-path attention at the long end of the regime: prompt 500, then
+    500 teacher-forced decode steps (KV grows to 1000) on one 7B-shaped layer;
+    hidden state compared at a sample of steps including the last."""
+    import torch
+    from paper_2604_23467_amd import binding
+    n_prompt, n_steps = 500, 500
+    cfg = wl.llama7b_cfg(n_layers=1, vocab=1024, max_seq=n_prompt + n_steps + 1)
+    w_t = wl.make_weights_torch(cfg, seed=1, device="cuda:0", emb_std=1.0)
+    w_np = wl.weights_to_numpy(w_t)
+    toks = wl.make_tokens(n_prompt + n_steps, cfg["vocab"], seed=8)
+    om = oracle32.model(cfg, w_np)
+    om.prefill(toks[:n_prompt])
+    check_at = {0, 1, 63, 64, 255, 256, 498, 499}
+    with binding.Session(cfg, w_t) as s:
+        s.ll_prefill(toks[:n_prompt])
+        for i in range(n_steps):
+            t_in = int(toks[n_prompt + i])
+            s.ll_dbg_force_next_token(t_in)
+            s.ll_decode_step()
+            _, l_ref, h_ref = om.step(t_in)
+            if i in check_at:
+                check_logits(s.ll_dbg_get_hidden(), h_ref, "long decode step %d hidden" % i,
+                             max_abs_tol=3e-2 * max(1.0, float(np.abs(h_ref).max())))
+                check_logits(s.ll_dbg_get_logits(), l_ref, "long decode step %d logits" % i)
+        assert s.ll_position() == 1000
+    om.close()
+
+
+# ------------------------------------------------------------ config 3: full 7B-shaped model
+def test_full_7b_prompt10_teacher_forced(torch_cuda, oracle32):
+    """32 layers, vocab 32000, fp16 N(0,0.02) weights seed 0, 10-token prompt:
+    prefill + 6 teacher-forced decode steps against the oracle, graph replay."""
+    import torch
+    from paper_2604_23467_amd import binding
+    cfg = wl.llama7b_cfg(max_seq=1024)
+    w_t = wl.make_weights_torch(cfg, seed=0, device="cuda:0")
+    w_np = wl.weights_to_numpy(w_t)
+    prompt = wl.make_tokens(10, cfg["vocab"], seed=0)
+    om = oracle32.model(cfg, w_np)
+    with binding.Session(cfg, w_t) as s:
+        stats = run_teacher_forced(s, om, prompt, 6, "7B")
+        # full-size LM head, sampled rows recomputed one by one from the GPU's own hidden state
+        h = s.ll_dbg_get_hidden().astype(np.float64)
+        lg = s.ll_dbg_get_logits()
+    om.close()
+    a = h / np.sqrt(np.mean(h * h) + float(np.float32(cfg["rms_eps"])))
+    rows = np.random.default_rng(0).integers(0, cfg["vocab"], size=64)
+    ref = w_np["lm_head"][rows].astype(np.float64) @ a
+    assert np.abs(lg[rows] - ref).max() < 2e-3
+    print("7B worst max-abs %.2e rel-L2 %.2e" % (max(x[0] for x in stats), max(x[1] for x in stats)))
+    del w_t
+    torch.cuda.empty_cache()
