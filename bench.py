@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the batch-1 decode / prefill path on ONE MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Workload (benchmark configs[3], the long end of the paper's regime,
+Sec. IV-E: LLaMA-2-7B shape, fp16, batch 1): seeded random weights, a
+500-token random prompt through the MFMA prefill (TTFT), then K greedy decode
+steps as hipGraph replays (KV length 500 -> 500+K).  One "step" is one decode
+step = one generated token.  Prints ONE JSON line; progress goes to stderr.
+
+Reported: p50/p99 per-token latency (host wall clock around ll_decode_step),
+tokens/s, TTFT for prompts 10..500, device time per step and its HBM roofline
+fraction, the dominant kernel's roofline (gate/up GEMV, hipEvent-timed), graph
+replay vs eager launches, and the CPU oracle timed on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+PROMPT_LENGTHS = (10, 25, 50, 100, 250, 500)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def step_bytes(cfg, n_keys):
+    """Algorithmic HBM bytes of one decode step attending n_keys keys: every
+    fp16 weight once, the gain vectors, one embedding row, K and V rows read,
+    one K and one V row written."""
+    d, F, V, Lyr = cfg["d_model"], cfg["ffn_hidden"], cfg["vocab"], cfg["n_layers"]
+    weights = 2 * (Lyr * (4 * d * d + 3 * d * F) + V * d)
+    gains = 2 * (2 * Lyr + 1) * d
+    emb = 2 * d
+    kv_read = Lyr * 2 * d * 2 * n_keys
+    kv_write = Lyr * 2 * d * 2
+    return weights + gains + emb + kv_read + kv_write
+
+
+def gateup_bytes(cfg):
+    """Algorithmic bytes of one gate/up GEMV launch: both fp16 matrices, the gain, x in, m out."""
+    d, F = cfg["d_model"], cfg["ffn_hidden"]
+    return 2 * F * d * 2 + 2 * d + 4 * d + 4 * F
+
+
+def pct(v, p):
+    v = np.sort(np.asarray(v))
+    k = max(0, min(len(v) - 1, int(np.ceil(p / 100.0 * len(v))) - 1))   # nearest rank
+    return float(v[k])
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--prompt", type=int, default=500)
+    ap.add_argument("--ttft-reps", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-eager", action="store_true")
+    ap.add_argument("--cpu-tokens", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (batch-1 latency path, no sharding or "
+              "collectives); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2604_23467_amd import binding, workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    K, W, n_prompt = args.steps, args.warmup, args.prompt
+    cfg = wl.llama7b_cfg(max_seq=max(1024, n_prompt + max(K, W) + 64))
+    log("[bench] drawing 7B-shaped fp16 weights on the GPU ...")
+    w_t = wl.make_weights_torch(cfg, seed=0, device="cuda:0")
+    torch.cuda.synchronize()
+    prompt = wl.make_tokens(n_prompt, cfg["vocab"], seed=0)
+
+    sess = binding.Session(cfg, w_t)
+    log("[bench] init done; warm-up: prefill(%d) + %d steps" % (n_prompt, W))
+    sess.ll_prefill(prompt)
+    if W > 0:
+        sess.ll_decode_n(W)
+    sess.ll_reset()
+
+    # ---- TTFT per prompt length (host wall clock of ll_prefill, ids in host memory)
+    ttft = {}
+    for n in PROMPT_LENGTHS:
+        if n > sess.ll_max_prompt():
+            continue
+        ts = []
+        for r in range(args.ttft_reps + 1):
+            p = wl.make_tokens(n, cfg["vocab"], seed=wl.sweep_token_seed(n, r))
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            sess.ll_prefill(p)
+            ts.append((time.perf_counter() - t0) * 1e3)
+            sess.ll_reset()
+        ttft[n] = float(np.median(ts[1:]))
+        log("[bench] TTFT prompt %4d: %.3f ms" % (n, ttft[n]))
+
+    # ---- timed region: K decode steps after the prompt
+    sess.ll_prefill(prompt)
+    torch.cuda.synchronize()
+    lat = np.empty(K)
+    t_begin = time.perf_counter()
+    for i in range(K):
+        t0 = time.perf_counter()
+        sess.ll_decode_step()
+        lat[i] = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t_begin
+    ms_per_step = t_total * 1e3 / K
+    p50, p99 = pct(lat, 50) * 1e6, pct(lat, 99) * 1e6
+    log("[bench] %d steps: %.3f ms/step host wall, p50 %.1f us, p99 %.1f us" % (K, ms_per_step, p50, p99))
+
+    # ---- device time per step (one event pair around K replays, no host sync in between)
+    sess.ll_reset()
+    sess.ll_prefill(prompt)
+    dev_ms = sess.ll_dbg_time_decode(K) / K
+    mean_keys = n_prompt + 1 + (K - 1) / 2.0
+    bytes_step = step_bytes(cfg, mean_keys)
+    step_gbs = bytes_step / (dev_ms * 1e-3) / 1e9
+    log("[bench] device %.3f ms/step -> %.0f GB/s = %.1f%% of %.0f GB/s"
+        % (dev_ms, step_gbs, 100 * step_gbs / HBM_PEAK_GBS, HBM_PEAK_GBS))
+
+    # ---- per-kernel-class durations (eager launches bracketed by hipEvents on the library's stream)
+    sess.ll_reset()
+    sess.ll_prefill(prompt)
+    prof = sess.ll_dbg_profile_decode(8)
+    for k, (us, n) in prof.items():
+        log("[bench]   %-7s %8.2f us x %d" % (k, us, n))
+    gu_us = prof["gateup"][0]
+    gu_gbs = gateup_bytes(cfg) / (gu_us * 1e-6) / 1e9
+    kernel_sum_ms = sum(us * n for us, n in prof.values()) / 1e3
+    sess.close()
+
+    # ---- graph replay vs eager launches (same kernels, per-kernel dispatch from the host)
+    eager = None
+    if not args.no_eager:
+        es = binding.Session(cfg, w_t, flags=binding.LL_FLAG_EAGER)
+        es.ll_prefill(prompt[:10])
+        es.ll_decode_n(10)
+        el = np.empty(100)
+        for i in range(100):
+            t0 = time.perf_counter()
+            es.ll_decode_step()
+            el[i] = time.perf_counter() - t0
+        es.close()
+        gs = binding.Session(cfg, w_t)
+        gs.ll_prefill(prompt[:10])
+        gs.ll_decode_n(10)
+        gl = np.empty(100)
+        for i in range(100):
+            t0 = time.perf_counter()
+            gs.ll_decode_step()
+            gl[i] = time.perf_counter() - t0
+        gs.close()
+        eager = dict(prompt=10, steps=100, eager_p50_us=pct(el, 50) * 1e6, eager_p99_us=pct(el, 99) * 1e6,
+                     graph_p50_us=pct(gl, 50) * 1e6, graph_p99_us=pct(gl, 99) * 1e6)
+        log("[bench] prompt 10, 100 steps: graph p50 %.1f us p99 %.1f us | eager p50 %.1f us p99 %.1f us"
+            % (eager["graph_p50_us"], eager["graph_p99_us"], eager["eager_p50_us"], eager["eager_p99_us"]))
+
+    # ---- CPU oracle on this machine's host cores (bounded sample; a reported baseline, not the target)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle.cpu_oracle import Oracle
+        log("[bench] copying weights to the host for the CPU oracle ...")
+        w_np = wl.weights_to_numpy(w_t)
+        om = Oracle("f32").model(cfg, w_np)
+        om.step(int(prompt[0]))                      # first touch, untimed
+        n_tok = args.cpu_tokens
+        t0 = time.perf_counter()
+        for t in prompt[1:1 + n_tok]:
+            om.step(int(t))
+        cpu_s = (time.perf_counter() - t0) / n_tok
+        om.close()
+        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cpu = dict(value=cpu_s * 1e6, unit="us/token", cores=threads, kind="oracle",
+                   sample="%d token passes of the 7B-shaped fp32 oracle (positions 1..%d of the prompt, "
+                          "per-token cost is almost independent of KV length)" % (n_tok, n_tok))
+        log("[bench] CPU oracle: %.3f s/token on %d threads" % (cpu_s, threads))
+
+    out = {
+        "metric": "per-token decode latency p50/p99 (us) + % peak HBM BW; TTFT at 10-500 prompt",
+        "value": p50,
+        "unit": "us",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": "LLaMA-2-7B shape (32 layers, d 4096, 32x128 heads, FFN 11008, vocab 32000), "
+                               "fp16 N(0,0.02) weights seed 0, batch 1, %d-token random prompt, %d greedy "
+                               "decode steps as hipGraph replays (KV %d -> %d)"
+                               % (n_prompt, K, n_prompt, n_prompt + K),
+                   "prompt_len": n_prompt, "decode_steps": K},
+        "p50_us": p50,
+        "p99_us": p99,
+        "tokens_per_s": 1e3 / ms_per_step,
+        "ttft_ms": {str(k): v for k, v in ttft.items()},
+        "step": {"device_ms": dev_ms, "bytes": bytes_step, "achieved_GBps": step_gbs,
+                 "frac_of_peak_hbm": step_gbs / HBM_PEAK_GBS, "sum_of_kernels_ms": kernel_sum_ms},
+        "roofline": {"kernel": "gemv_kernel<GATEUP> (RMSNorm + gate/up GEMV + SwiGLU)", "bound": "hbm",
+                     "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gu_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": gateup_bytes(cfg), "avg_us": gu_us},
+        "kernels_us": {k: {"avg_us": us, "launches_per_step": n} for k, (us, n) in prof.items()},
+        "graph_vs_eager": eager,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -309,15 +309,22 @@ __global__ __launch_bounds__(LL_WG) void attn_decode_kernel(
     }
     __hip_atomic_store(mypart + 2 + tid, A, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  __threadfence();   // publish this workgroup's partial at device scope (L2s are per XCD)
+  // Publishing without a cache flush: the partial was written with device-scope
+  // atomic stores, which are coherent across the per-XCD L2s on their own, and
+  // the counter increment is issued only after every such store of this
+  // workgroup has completed (wait for the vector-memory counter, then the
+  // workgroup barrier).  The reader's loads below are device-scope atomics
+  // too and are issued after its own increment has returned.  A release fence
+  // here would write back the whole L2 in every workgroup, which costs far
+  // more than the attention itself.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (tid == 0) {
-    const unsigned t = __hip_atomic_fetch_add(cnt + h, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned t = __hip_atomic_fetch_add(cnt + h, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (t == (unsigned)(S - 1));
   }
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
   if (tid < HD) {
     const float* hp = part + (size_t)h * S * PS;
     float M = -INFINITY;
