@@ -68,6 +68,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=8)
+    ap.add_argument("--counters", action="store_true",
+                    help="short run for `rocprofv3 --pmc`: a 256 MiB device copy as the counter "
+                         "calibration, then prefill + the decode steps; no timing, no JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (batch-1 latency path, no sharding or "
@@ -85,6 +88,19 @@ def main():
     w_t = wl.make_weights_torch(cfg, seed=0, device="cuda:0")
     torch.cuda.synchronize()
     prompt = wl.make_tokens(n_prompt, cfg["vocab"], seed=0)
+
+    if args.counters:
+        sess = binding.Session(cfg, w_t, flags=binding.LL_FLAG_EAGER)
+        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        b = torch.empty_like(a)
+        b.copy_(a)                                   # known traffic: 256 MiB read + 256 MiB written
+        torch.cuda.synchronize()
+        binding.ll_dbg_stream_copy(b, a)             # same, through the GEMVs' 16-byte streaming loads
+        sess.ll_prefill(prompt)
+        sess.ll_decode_n(K)
+        sess.close()
+        log("[bench] counter run done (%d decode steps after a %d-token prompt)" % (K, n_prompt))
+        return 0
 
     sess = binding.Session(cfg, w_t)
     log("[bench] init done; warm-up: prefill(%d) + %d steps" % (n_prompt, W))
@@ -134,12 +150,18 @@ def main():
     log("[bench] device %.3f ms/step -> %.0f GB/s = %.1f%% of %.0f GB/s"
         % (dev_ms, step_gbs, 100 * step_gbs / HBM_PEAK_GBS, HBM_PEAK_GBS))
 
-    # ---- per-kernel-class durations (eager launches bracketed by hipEvents on the library's stream)
+    # ---- per-kernel-class durations: each class launched back to back over all layers
+    #      (every layer's own weights, nothing re-read from cache) between one hipEvent
+    #      pair on the library's stream
     sess.ll_reset()
     sess.ll_prefill(prompt)
-    prof = sess.ll_dbg_profile_decode(8)
-    for k, (us, n) in prof.items():
-        log("[bench]   %-7s %8.2f us x %d" % (k, us, n))
+    sess.ll_decode_n(max(1, min(K, 250)))            # KV length in the middle of the timed range
+    prof = {}
+    for name, per_step in (("qkv", cfg["n_layers"]), ("attn", cfg["n_layers"]), ("oproj", cfg["n_layers"]),
+                           ("gateup", cfg["n_layers"]), ("down", cfg["n_layers"]), ("lmhead", 1)):
+        prof[name] = (sess.ll_dbg_time_kernel_class(name, 4 if per_step > 1 else 32), per_step)
+        log("[bench]   %-7s %8.2f us x %d" % (name, prof[name][0], per_step))
+    sess.ll_reset()
     gu_us = prof["gateup"][0]
     gu_gbs = gateup_bytes(cfg) / (gu_us * 1e-6) / 1e9
     kernel_sum_ms = sum(us * n for us, n in prof.values()) / 1e3

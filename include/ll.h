@@ -155,6 +155,19 @@ enum {
 };
 int ll_dbg_profile_decode(int32_t steps, float *us_out, int32_t *launches_out);
 
+/* Mean device time of one launch of kernel class `klass` (LL_KC_QKV ..
+ * LL_KC_LMHEAD): `reps` passes over all layers, launching only that class back
+ * to back (each layer's own weights, so nothing is re-read from cache) between
+ * one hipEvent pair on the library's stream.  The position does not advance,
+ * but the activation buffers are left undefined: call ll_reset() afterwards. */
+int ll_dbg_time_kernel_class(int32_t klass, int32_t reps, float *us_out);
+
+/* Copies `bytes` (a multiple of 16; both DEVICE pointers 16-byte aligned) with
+ * the same 16-byte streaming loads the decode GEMVs use, and waits for it.  A
+ * calibration kernel of known traffic for hardware counters; works with or
+ * without an initialised instance. */
+int ll_dbg_stream_copy(void *dst, const void *src, size_t bytes);
+
 /* Device time of `k` decode-step replays measured with one hipEvent pair on
  * the library's stream (milliseconds for all k steps), tokens discarded. */
 int ll_dbg_time_decode(int32_t k, float *ms_out);

@@ -23,7 +23,7 @@ LAYER_KEYS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up",
 EXPORTS = ("ll_workspace_bytes", "ll_init", "ll_prefill", "ll_decode_step", "ll_decode_n", "ll_reset",
            "ll_shutdown", "ll_max_prompt", "ll_position", "ll_last_error", "ll_dbg_get_logits",
            "ll_dbg_get_hidden", "ll_dbg_force_next_token", "ll_dbg_get_kv", "ll_dbg_profile_decode",
-           "ll_dbg_time_decode")
+           "ll_dbg_time_decode", "ll_dbg_time_kernel_class", "ll_dbg_stream_copy")
 
 
 class LLConfig(C.Structure):
@@ -87,6 +87,10 @@ def load():
     L.ll_dbg_get_kv.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float)]
     L.ll_dbg_profile_decode.restype = C.c_int
     L.ll_dbg_profile_decode.argtypes = [C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+    L.ll_dbg_time_kernel_class.restype = C.c_int
+    L.ll_dbg_time_kernel_class.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_float)]
+    L.ll_dbg_stream_copy.restype = C.c_int
+    L.ll_dbg_stream_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
     L.ll_dbg_time_decode.restype = C.c_int
     L.ll_dbg_time_decode.argtypes = [C.c_int32, C.POINTER(C.c_float)]
     _lib = L
@@ -108,6 +112,14 @@ def make_config(cfg, flags=0):
 def ll_workspace_bytes(cfg, flags=0):
     c = make_config(cfg, flags)
     return int(load().ll_workspace_bytes(C.byref(c)))
+
+
+def ll_dbg_stream_copy(dst, src):
+    """Copies one contiguous CUDA tensor into another of the same byte size."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    return _check(load().ll_dbg_stream_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()),
+                                            C.c_size_t(nbytes)))
 
 
 def ll_last_error():
@@ -226,6 +238,11 @@ class Session:
         _check(self.lib.ll_dbg_profile_decode(steps, us.ctypes.data_as(C.POINTER(C.c_float)),
                                               n.ctypes.data_as(C.POINTER(C.c_int32))))
         return {k: (float(us[i]), int(n[i])) for i, k in enumerate(KERNEL_CLASSES)}
+
+    def ll_dbg_time_kernel_class(self, name, reps):
+        us = C.c_float(0.0)
+        _check(self.lib.ll_dbg_time_kernel_class(KERNEL_CLASSES.index(name), reps, C.byref(us)))
+        return float(us.value)
 
     def ll_dbg_time_decode(self, k):
         ms = C.c_float(0.0)

@@ -58,6 +58,61 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
   float* red = lds + nchp * 512;
   constexpr bool NORM = (MODE == GM_QKV || MODE == GM_GATEUP || MODE == GM_LMHEAD);
 
+  const int d_half = a.N >> 1;
+  int P;
+  if (MODE == GM_QKV) P = 3 * d_half;
+  else if (MODE == GM_GATEUP) P = a.N;
+  else P = (a.N + 1) >> 1;
+
+  // row pair p -> the two weight rows this wave streams
+  const half_t *pa = a.w0, *pb = a.w0;
+  int sec = 0, rowA = 0, rowB = 0;
+  auto select_rows = [&](int p) {
+    if (MODE == GM_QKV) {
+      sec = p / d_half;
+      const int pp = p - sec * d_half;
+      const half_t* base = sec == 0 ? a.w0 : (sec == 1 ? a.w1 : a.w2);
+      if (sec < 2) {
+        const int hh = a.head_dim >> 1;
+        const int head = pp / hh, j = pp - head * hh;
+        rowA = head * a.head_dim + j;
+        rowB = rowA + hh;
+      } else {
+        rowA = 2 * pp;
+        rowB = rowA + 1;
+      }
+      pa = base + (size_t)rowA * K;
+      pb = base + (size_t)rowB * K;
+    } else if (MODE == GM_GATEUP) {
+      rowA = rowB = p;
+      pa = a.w0 + (size_t)p * K;
+      pb = a.w1 + (size_t)p * K;
+    } else {
+      rowA = 2 * p;
+      rowB = min(rowA + 1, a.N - 1);
+      pa = a.w0 + (size_t)rowA * K;
+      pb = a.w0 + (size_t)rowB * K;
+    }
+  };
+  h8 wa[U], wb[U];
+  auto load_group = [&](int c0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int k = min((c0 + u) * 512 + lane * 8, K - 8);
+      wa[u] = load_stream(pa + k);
+      wb[u] = load_stream(pb + k);
+    }
+  };
+
+  // The weight stream does not depend on the input vector: put the first
+  // loads of this wave's first row pair in flight before staging x, so HBM is
+  // already busy while the prologue runs.
+  const int gw = blockIdx.x * (LL_WG / 64) + wave, GW = gridDim.x * (LL_WG / 64);
+  if (gw < P) {
+    select_rows(gw);
+    load_group(0);
+  }
+
   const float* xin = a.xin;
   if (MODE == GM_LMHEAD && a.x_row_from_prompt) xin += (size_t)(a.st->n_prompt - 1) * K;
 
@@ -84,54 +139,14 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
   float inv = 1.f;
   if (NORM) inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)K + a.eps);
 
-  const int d_half = a.N >> 1;
-  int P;
-  if (MODE == GM_QKV) P = 3 * d_half;
-  else if (MODE == GM_GATEUP) P = a.N;
-  else P = (a.N + 1) >> 1;
-
   float best_v = -INFINITY;
   int best_i = 0x7fffffff;
 
-  const int gw = blockIdx.x * (LL_WG / 64) + wave, GW = gridDim.x * (LL_WG / 64);
   for (int p = gw; p < P; p += GW) {
-    const half_t *pa, *pb;
-    int sec = 0, rowA = 0, rowB = 0;
-    if (MODE == GM_QKV) {
-      sec = p / d_half;
-      const int pp = p - sec * d_half;
-      const half_t* base = sec == 0 ? a.w0 : (sec == 1 ? a.w1 : a.w2);
-      if (sec < 2) {
-        const int hh = a.head_dim >> 1;
-        const int head = pp / hh, j = pp - head * hh;
-        rowA = head * a.head_dim + j;
-        rowB = rowA + hh;
-      } else {
-        rowA = 2 * pp;
-        rowB = rowA + 1;
-      }
-      pa = base + (size_t)rowA * K;
-      pb = base + (size_t)rowB * K;
-    } else if (MODE == GM_GATEUP) {
-      rowA = rowB = p;
-      pa = a.w0 + (size_t)p * K;
-      pb = a.w1 + (size_t)p * K;
-    } else {
-      rowA = 2 * p;
-      rowB = min(rowA + 1, a.N - 1);
-      pa = a.w0 + (size_t)rowA * K;
-      pb = a.w0 + (size_t)rowB * K;
-    }
-
+    if (p != gw) select_rows(p);
     float accA = 0.f, accB = 0.f;
     for (int c0 = 0; c0 < nch; c0 += U) {
-      h8 wa[U], wb[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int k = min((c0 + u) * 512 + lane * 8, K - 8);
-        wa[u] = load_stream(pa + k);
-        wb[u] = load_stream(pb + k);
-      }
+      if (p != gw || c0 != 0) load_group(c0);
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const float* xp = lds + (c0 + u) * 512 + lane * 4;
@@ -389,4 +404,14 @@ __global__ __launch_bounds__(LL_WG) void sample_kernel(const float* __restrict__
     st->next_token = tok;
     if (idx < ring_size) host_ring[idx] = tok;
   }
+}
+
+// Plain device-to-device copy with the same 16-byte streaming loads the GEMVs
+// use.  It exists to calibrate hardware traffic counters against a known byte
+// count; nothing on the decode path calls it.
+__global__ __launch_bounds__(LL_WG) void stream_copy_kernel(const h8* __restrict__ src,
+                                                            h8* __restrict__ dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * LL_WG;
+  for (size_t i = (size_t)blockIdx.x * LL_WG + threadIdx.x; i < n16; i += stride)
+    dst[i] = __builtin_nontemporal_load(src + i);
 }

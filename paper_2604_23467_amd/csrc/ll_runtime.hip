@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -35,7 +36,8 @@ int fail(int code, const char* fmt, ...) {
                   __LINE__);                                                              \
   } while (0)
 
-constexpr int kGemvU = 4;          // 512-element chunks of a weight row in flight per lane and row
+constexpr int kGemvU = 8;          // 512-element chunks of a weight row in flight per lane and row
+constexpr int kGemvWgsPerCu = 4;   // measured best of 2/3/4 on the 7B shapes
 constexpr int kAttnMaxSplits = 16;
 constexpr int kMaxPromptBucket = 512;
 constexpr size_t kAlign = 256;
@@ -70,8 +72,8 @@ struct Layout {
 };
 
 int gemv_grid(int pairs) {
-  // ~3 workgroups per CU keep enough 16-byte loads in flight; never more waves than row pairs
-  const int want = 256 * 3;
+  // a few workgroups per CU keep enough 16-byte loads in flight; never more waves than row pairs
+  const int want = 256 * kGemvWgsPerCu;
   const int need = (pairs + (LL_WG / 64) - 1) / (LL_WG / 64);
   return need < want ? (need < 1 ? 1 : need) : want;
 }
@@ -136,6 +138,8 @@ struct Instance {
   // profiling hook: when set, every decode launch is bracketed by events
   std::vector<hipEvent_t>* prof_events = nullptr;
   std::vector<int>* prof_class = nullptr;
+  int only_class = -1;           // timing hook: launch only this kernel class of the decode chain
+  bool runs(int klass) const { return only_class < 0 || only_class == klass; }
 
   template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
   half_t* kcache(int layer) const { return at<half_t>(L.kv) + (size_t)layer * 2 * L.kv_layer_halves; }
@@ -182,7 +186,7 @@ void launch_gemv(const GemvArgs& a, int pairs, int grid_override, hipStream_t s)
 // final RMSNorm + LM head + argmax + state advance, shared by decode and prefill
 void enqueue_head(Instance* I, hipStream_t s, const float* xin, int from_prompt_row, int prefill) {
   const ll_config& c = I->cfg;
-  {
+  if (I->runs(LL_KC_LMHEAD)) {
     ProfScope ps(I, s, LL_KC_LMHEAD);
     GemvArgs a{};
     a.w0 = (const half_t*)I->w.lm_head;
@@ -198,7 +202,7 @@ void enqueue_head(Instance* I, hipStream_t s, const float* xin, int from_prompt_
     a.x_row_from_prompt = from_prompt_row;
     launch_gemv<GM_LMHEAD>(a, (c.vocab + 1) / 2, I->L.lm_wgs, s);
   }
-  {
+  if (I->runs(LL_KC_SAMPLE)) {
     ProfScope ps(I, s, LL_KC_SAMPLE);
     hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(LL_WG), 0, s, I->at<float>(I->L.amax_val),
                        I->at<int>(I->L.amax_idx), I->L.lm_wgs, I->state(), I->dev_ring, I->ring_size,
@@ -213,14 +217,14 @@ void enqueue_decode(Instance* I, hipStream_t s) {
   float* q = I->at<float>(I->L.q);
   float* o = I->at<float>(I->L.o);
   float* m = I->at<float>(I->L.m);
-  {
+  if (I->runs(LL_KC_EMBED)) {
     ProfScope ps(I, s, LL_KC_EMBED);
     hipLaunchKernelGGL(embed_kernel, dim3((d + LL_WG * 8 - 1) / (LL_WG * 8)), dim3(LL_WG), 0, s,
                        (const half_t*)I->w.tok_emb, I->state(), x, d);
   }
   for (int l = 0; l < c.n_layers; ++l) {
     const ll_layer_weights& W = I->layers[l];
-    {
+    if (I->runs(LL_KC_QKV)) {
       ProfScope ps(I, s, LL_KC_QKV);
       GemvArgs a{};
       a.w0 = (const half_t*)W.wq; a.w1 = (const half_t*)W.wk; a.w2 = (const half_t*)W.wv;
@@ -231,7 +235,7 @@ void enqueue_decode(Instance* I, hipStream_t s) {
       a.head_dim = c.head_dim; a.max_seq = c.max_seq;
       launch_gemv<GM_QKV>(a, 3 * d / 2, 0, s);
     }
-    {
+    if (I->runs(LL_KC_ATTN)) {
       ProfScope ps(I, s, LL_KC_ATTN);
       dim3 grid(c.n_heads, I->L.attn_splits);
       if (c.head_dim == 128)
@@ -243,13 +247,13 @@ void enqueue_decode(Instance* I, hipStream_t s) {
                            I->vcache(l), I->state(), I->at<float>(I->L.attn_part),
                            I->at<unsigned>(I->L.attn_cnt), o, c.max_seq);
     }
-    {
+    if (I->runs(LL_KC_OPROJ)) {
       ProfScope ps(I, s, LL_KC_OPROJ);
       GemvArgs a{};
       a.w0 = (const half_t*)W.wo; a.xin = o; a.out = x; a.N = d; a.K = d;
       launch_gemv<GM_ORES>(a, d / 2, 0, s);
     }
-    {
+    if (I->runs(LL_KC_GATEUP)) {
       ProfScope ps(I, s, LL_KC_GATEUP);
       GemvArgs a{};
       a.w0 = (const half_t*)W.w_gate; a.w1 = (const half_t*)W.w_up;
@@ -257,7 +261,7 @@ void enqueue_decode(Instance* I, hipStream_t s) {
       a.N = F; a.K = d; a.eps = c.rms_eps;
       launch_gemv<GM_GATEUP>(a, F, 0, s);
     }
-    {
+    if (I->runs(LL_KC_DOWN)) {
       ProfScope ps(I, s, LL_KC_DOWN);
       GemvArgs a{};
       a.w0 = (const half_t*)W.w_down; a.xin = m; a.out = x; a.N = d; a.K = F;
@@ -656,6 +660,45 @@ int ll_dbg_profile_decode(int32_t steps, float* us_out, int32_t* launches_out) {
     us_out[i] = cnt[i] ? (float)(sum[i] / cnt[i]) : 0.f;
     if (launches_out) launches_out[i] = (int32_t)(cnt[i] / steps);
   }
+  return LL_OK;
+}
+
+int ll_dbg_stream_copy(void* dst, const void* src, size_t bytes) {
+  if (!dst || !src || bytes == 0 || bytes % 16 || reinterpret_cast<uintptr_t>(dst) % 16 ||
+      reinterpret_cast<uintptr_t>(src) % 16)
+    return fail(LL_E_BAD_ARG, "ll_dbg_stream_copy: pointers and size must be 16-byte multiples");
+  hipStream_t s = g ? g->stream : nullptr;
+  hipLaunchKernelGGL(stream_copy_kernel, dim3(256 * 8), dim3(LL_WG), 0, s, (const h8*)src, (h8*)dst,
+                     bytes / 16);
+  HIPCHK(hipGetLastError());
+  HIPCHK(hipStreamSynchronize(s));
+  return LL_OK;
+}
+
+int ll_dbg_time_kernel_class(int32_t klass, int32_t reps, float* us_out) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_dbg_time_kernel_class: not initialised");
+  Instance* I = g;
+  if (klass < LL_KC_QKV || klass > LL_KC_LMHEAD || reps < 1 || !us_out)
+    return fail(LL_E_BAD_ARG, "ll_dbg_time_kernel_class: bad argument");
+  if (I->pos == 0) return fail(LL_E_STATE, "ll_dbg_time_kernel_class: empty context");
+  if (I->pos >= I->cfg.max_seq) return fail(LL_E_CAPACITY, "ll_dbg_time_kernel_class: cache full");
+  hipEvent_t e0, e1;
+  HIPCHK(hipEventCreate(&e0));
+  HIPCHK(hipEventCreate(&e1));
+  I->only_class = klass;
+  enqueue_decode(I, I->stream);   // untimed pass
+  (void)hipEventRecord(e0, I->stream);
+  for (int r = 0; r < reps; ++r) enqueue_decode(I, I->stream);
+  (void)hipEventRecord(e1, I->stream);
+  I->only_class = -1;
+  hipError_t e = hipStreamSynchronize(I->stream);
+  float ms = 0.f;
+  if (e == hipSuccess) (void)hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (e != hipSuccess) return fail(LL_E_HIP, "time_kernel_class: %s", hipGetErrorString(e));
+  const int per_pass = klass == LL_KC_LMHEAD ? 1 : I->cfg.n_layers;
+  *us_out = ms * 1000.f / (float)(reps * per_pass);
   return LL_OK;
 }
 

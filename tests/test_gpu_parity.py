@@ -263,3 +263,30 @@ def test_full_7b_prompt10_teacher_forced(torch_cuda, oracle32):
     print("7B worst max-abs %.2e rel-L2 %.2e" % (max(x[0] for x in stats), max(x[1] for x in stats)))
     del w_t
     torch.cuda.empty_cache()
+
+
+def test_timing_hooks_leave_a_usable_context(torch_cuda, oracle32):
+    cfg = wl.tiny_cfg(max_seq=64)
+    w = wl.make_weights_numpy(cfg, seed=0)
+    prompt = wl.make_tokens(10, cfg["vocab"], seed=0)
+    om = oracle32.model(cfg, w)
+    with _session(cfg, w) as s:
+        s.ll_prefill(prompt)
+        for name in ("qkv", "attn", "oproj", "gateup", "down", "lmhead"):
+            assert s.ll_dbg_time_kernel_class(name, 2) > 0.0
+        assert s.ll_position() == 10
+        prof = s.ll_dbg_profile_decode(2)
+        assert prof["gateup"][1] == cfg["n_layers"] and s.ll_position() == 12
+        assert s.ll_dbg_time_decode(3) > 0.0 and s.ll_position() == 15
+        s.ll_reset()                                   # required after the class timing hook
+        run_teacher_forced(s, om, prompt, 3, "after-hooks")
+    om.close()
+
+
+def test_stream_copy_calibration_kernel(torch_cuda):
+    import torch
+    from paper_2604_23467_amd import binding
+    a = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device="cuda:0")
+    b = torch.zeros_like(a)
+    binding.ll_dbg_stream_copy(b, a)
+    assert torch.equal(a, b)
