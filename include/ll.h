@@ -50,9 +50,22 @@ enum {
 
 /* ll_config.flags */
 enum {
-  LL_FLAG_EAGER = 1 /* launch every kernel individually instead of replaying graphs
-                       (same kernels, same order: isolates the dispatch cost the
-                       paper's Sec. I-B / III-B attribute to per-kernel launches) */
+  LL_FLAG_EAGER = 1,       /* launch every kernel individually instead of replaying graphs
+                              (same kernels, same order: isolates the dispatch cost the
+                              paper's Sec. I-B / III-B attribute to per-kernel launches) */
+  LL_FLAG_MULTIKERNEL = 2, /* decode step = graph of one kernel per fused operator (~160 nodes) */
+  LL_FLAG_PERSISTENT = 4   /* decode step = graph of ONE persistent kernel with in-kernel grid
+                              barriers (needs d_model <= 4096 and one resident workgroup per
+                              CU; ll_init fails with LL_E_BAD_CONFIG otherwise).  With neither
+                              of the two flags the library picks the faster one it has measured
+                              for the 7B shape, currently the multi-kernel graph. */
+};
+
+/* what ll_decode_step() replays, see ll_decode_mode() */
+enum {
+  LL_MODE_PERSISTENT_GRAPH = 0,   /* graph of ONE persistent kernel with in-kernel grid barriers */
+  LL_MODE_MULTIKERNEL_GRAPH = 1,  /* graph of one kernel per fused operator */
+  LL_MODE_EAGER = 2               /* the multi-kernel chain launched kernel by kernel */
 };
 
 /* Model shape.  Constraints: n_heads * head_dim == d_model; head_dim is 64 or
@@ -123,6 +136,9 @@ int32_t ll_max_prompt(void);
 /* Number of cached positions (0 when empty), or LL_E_NOT_INIT. */
 int32_t ll_position(void);
 
+/* LL_MODE_* of the current instance. */
+int ll_decode_mode(void);
+
 /* Text of the most recent failure on this thread ("" if none). */
 const char *ll_last_error(void);
 
@@ -161,6 +177,16 @@ int ll_dbg_profile_decode(int32_t steps, float *us_out, int32_t *launches_out);
  * one hipEvent pair on the library's stream.  The position does not advance,
  * but the activation buffers are left undefined: call ll_reset() afterwards. */
 int ll_dbg_time_kernel_class(int32_t klass, int32_t reps, float *us_out);
+
+/* One decode step of the persistent kernel with phase tracing: for each of its
+ * 5 * n_layers + 1 phases (QKV, attention, O, gate/up, down per layer, then the
+ * LM head) workgroup 0 records 100 MHz timestamps, 8 slots per phase: [0] phase
+ * entry, [1] input staged, [2] dot products done, [3] results stored, [4] grid
+ * barrier passed (service wave); [5] first dot product starts, [6] ends, [7] its
+ * next loads issued (compute wave 0); slots a phase does not use stay 0.
+ * ticks_out (host) receives [phases][8] values (at most 162 phases are traced);
+ * returns the phase count.  The context advances by one token. */
+int ll_dbg_trace_decode(uint64_t *ticks_out, int32_t max_phases);
 
 /* Copies `bytes` (a multiple of 16; both DEVICE pointers 16-byte aligned) with
  * the same 16-byte streaming loads the decode GEMVs use, and waits for it.  A

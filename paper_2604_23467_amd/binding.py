@@ -17,13 +17,16 @@ LL_OK = 0
 LL_E_NOT_INIT, LL_E_BAD_CONFIG, LL_E_BAD_ARG, LL_E_CAPACITY = -1, -2, -3, -4
 LL_E_WORKSPACE, LL_E_STATE, LL_E_HIP, LL_E_ALREADY_INIT = -5, -6, -7, -8
 LL_FLAG_EAGER = 1
+LL_FLAG_MULTIKERNEL = 2
+LL_FLAG_PERSISTENT = 4
+LL_MODE_PERSISTENT_GRAPH, LL_MODE_MULTIKERNEL_GRAPH, LL_MODE_EAGER = 0, 1, 2
 KERNEL_CLASSES = ("embed", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "sample")
 LAYER_KEYS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
 
 EXPORTS = ("ll_workspace_bytes", "ll_init", "ll_prefill", "ll_decode_step", "ll_decode_n", "ll_reset",
-           "ll_shutdown", "ll_max_prompt", "ll_position", "ll_last_error", "ll_dbg_get_logits",
+           "ll_shutdown", "ll_max_prompt", "ll_position", "ll_decode_mode", "ll_last_error", "ll_dbg_get_logits",
            "ll_dbg_get_hidden", "ll_dbg_force_next_token", "ll_dbg_get_kv", "ll_dbg_profile_decode",
-           "ll_dbg_time_decode", "ll_dbg_time_kernel_class", "ll_dbg_stream_copy")
+           "ll_dbg_time_decode", "ll_dbg_time_kernel_class", "ll_dbg_stream_copy", "ll_dbg_trace_decode")
 
 
 class LLConfig(C.Structure):
@@ -72,7 +75,7 @@ def load():
     for name in ("ll_reset", "ll_shutdown"):
         getattr(L, name).restype = C.c_int
         getattr(L, name).argtypes = []
-    for name in ("ll_max_prompt", "ll_position"):
+    for name in ("ll_max_prompt", "ll_position", "ll_decode_mode"):
         getattr(L, name).restype = C.c_int32
         getattr(L, name).argtypes = []
     L.ll_last_error.restype = C.c_char_p
@@ -89,6 +92,8 @@ def load():
     L.ll_dbg_profile_decode.argtypes = [C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     L.ll_dbg_time_kernel_class.restype = C.c_int
     L.ll_dbg_time_kernel_class.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_float)]
+    L.ll_dbg_trace_decode.restype = C.c_int
+    L.ll_dbg_trace_decode.argtypes = [C.POINTER(C.c_uint64), C.c_int32]
     L.ll_dbg_stream_copy.restype = C.c_int
     L.ll_dbg_stream_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
     L.ll_dbg_time_decode.restype = C.c_int
@@ -210,6 +215,9 @@ class Session:
     def ll_max_prompt(self):
         return _check(self.lib.ll_max_prompt())
 
+    def ll_decode_mode(self):
+        return _check(self.lib.ll_decode_mode())
+
     def ll_position(self):
         return _check(self.lib.ll_position())
 
@@ -243,6 +251,13 @@ class Session:
         us = C.c_float(0.0)
         _check(self.lib.ll_dbg_time_kernel_class(KERNEL_CLASSES.index(name), reps, C.byref(us)))
         return float(us.value)
+
+    def ll_dbg_trace_decode(self):
+        """[phases][5] timestamps in microseconds relative to the first one."""
+        n = 5 * self.cfg["n_layers"] + 1
+        buf = np.zeros((n, 8), dtype=np.uint64)
+        _check(self.lib.ll_dbg_trace_decode(buf.ctypes.data_as(C.POINTER(C.c_uint64)), n))
+        return (buf.astype(np.int64) - np.int64(buf[0, 0])) / 100.0
 
     def ll_dbg_time_decode(self, k):
         ms = C.c_float(0.0)

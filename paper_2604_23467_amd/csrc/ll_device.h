@@ -52,9 +52,28 @@ __device__ __forceinline__ float wave_sum(float v) {
   return (r0 + r1) + (r2 + r3);
 }
 
+// Pointers that were themselves loaded from memory (e.g. a per-layer pointer
+// table) are "generic" to the compiler, which then emits FLAT loads; those count
+// against the LDS counter as well, so every LDS wait and every workgroup
+// barrier would also wait for weight loads still in flight.  All device
+// buffers here live in global memory: say so.
+#define LL_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ const LL_GLOBAL T* as_global(const T* p) {
+  return (const LL_GLOBAL T*)p;
+}
+template <class T>
+__device__ __forceinline__ LL_GLOBAL T* as_global(T* p) {
+  return (LL_GLOBAL T*)p;
+}
+
 // 16-byte streaming load of weights that are read exactly once per step.
 __device__ __forceinline__ h8 load_stream(const half_t* p) {
-  return __builtin_nontemporal_load(reinterpret_cast<const h8*>(p));
+  return __builtin_nontemporal_load(as_global(reinterpret_cast<const h8*>(p)));
+}
+// plain 16-byte load from global memory
+__device__ __forceinline__ h8 load_h8(const half_t* p) {
+  return *as_global(reinterpret_cast<const h8*>(p));
 }
 
 __device__ __forceinline__ float dot8(h8 w, f4 x0, f4 x1, float acc) {

@@ -7,11 +7,13 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <algorithm>
 #include <string>
 #include <vector>
 
 #include "../../include/ll.h"
 #include "decode_kernels.h"
+#include "decode_mega.h"
 #include "prefill_kernels.h"
 
 namespace {
@@ -66,6 +68,7 @@ int prompt_bucket(int n) {   // smallest of {64,128,256,512} holding n rows
 struct Layout {
   size_t kv, rope, x, q, o, m, attn_part, attn_cnt, logits, amax_val, amax_idx, state, tokens;
   size_t pf_x, pf_xn, pf_qkv, pf_q, pf_o, pf_gu, pf_h;
+  size_t mk_layers, mk_bar, mk_amax_val, mk_amax_idx, mk_trace;
   size_t total;
   int attn_splits, lm_wgs, max_prompt, mb_max;
   size_t kv_layer_halves;   // halves per layer per K or V
@@ -96,7 +99,7 @@ Layout make_layout(const ll_config& c) {
   L.q = take(d * 4);
   L.o = take(d * 4);
   L.m = take(F * 4);
-  L.attn_part = take((size_t)c.n_heads * L.attn_splits * (c.head_dim + 2) * 4);
+  L.attn_part = take((size_t)c.n_heads * kAttnMaxSplits * (c.head_dim + 2) * 4);
   L.attn_cnt = take((size_t)c.n_heads * 4);
   L.logits = take(V * 4);
   L.amax_val = take((size_t)L.lm_wgs * 4);
@@ -111,6 +114,11 @@ Layout make_layout(const ll_config& c) {
   L.pf_o = take(M * d * 2);
   L.pf_gu = take(M * 2 * F * 4);
   L.pf_h = take(M * F * 2);
+  L.mk_layers = take((size_t)c.n_layers * sizeof(MkLayer));
+  L.mk_bar = take((size_t)MK_BAR_WORDS * 4);
+  L.mk_amax_val = take(1024 * 4);   // one candidate per workgroup of the persistent kernel
+  L.mk_amax_idx = take(1024 * 4);
+  L.mk_trace = take((size_t)(5 * c.n_layers + 2) * 8 * 8);
   L.total = off;
   return L;
 }
@@ -138,6 +146,10 @@ struct Instance {
   // profiling hook: when set, every decode launch is bracketed by events
   std::vector<hipEvent_t>* prof_events = nullptr;
   std::vector<int>* prof_class = nullptr;
+  bool use_mega = false;         // decode step = one persistent kernel
+  int mega_grid = 0;
+  size_t mega_lds = 0;
+  int mega_splits = 1;
   int only_class = -1;           // timing hook: launch only this kernel class of the decode chain
   bool runs(int klass) const { return only_class < 0 || only_class == klass; }
 
@@ -210,7 +222,7 @@ void enqueue_head(Instance* I, hipStream_t s, const float* xin, int from_prompt_
   }
 }
 
-void enqueue_decode(Instance* I, hipStream_t s) {
+void enqueue_decode_multi(Instance* I, hipStream_t s) {
   const ll_config& c = I->cfg;
   const int d = c.d_model, F = c.ffn_hidden;
   float* x = I->at<float>(I->L.x);
@@ -269,6 +281,73 @@ void enqueue_decode(Instance* I, hipStream_t s) {
     }
   }
   enqueue_head(I, s, x, 0, 0);
+}
+
+// Can the whole step run as one persistent kernel on this device / shape?
+bool mega_plan(Instance* I, std::string* why) {
+  const ll_config& c = I->cfg;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
+    *why = "cannot query the CU count";
+    return false;
+  }
+  if (cus > 1024) cus = 1024;
+  const int nch_d = (c.d_model + 511) / 512, nch_f = (c.ffn_hidden + 511) / 512;
+  if (nch_d > MK_U) { *why = "d_model > 4096"; return false; }
+  if (c.n_heads > cus) { *why = "more heads than CUs"; return false; }
+  auto items = [&](int npairs, int nch) { return ((npairs + cus - 1) / cus) * ((nch + MK_U - 1) / MK_U); };
+  int worst = items(3 * c.d_model / 2, nch_d);
+  worst = std::max(worst, items(c.ffn_hidden, nch_d));
+  worst = std::max(worst, items(c.d_model / 2, nch_f));
+  worst = std::max(worst, items((c.vocab + 1) / 2, nch_d));
+  if (worst > MK_MAX_ITEMS) { *why = "too many row pairs per workgroup"; return false; }
+  const int gpw = 64 / (c.head_dim / 8), ng = MK_WAVES * gpw;
+  const size_t stage = (size_t)(std::max(nch_d, nch_f) + 1) * 512;
+  const size_t attn = (size_t)2 * ng + (size_t)ng * c.head_dim + c.head_dim + 2;
+  I->mega_lds = std::max(stage, attn) * sizeof(float);
+  if (I->mega_lds > 64 * 1024) { *why = "input vector does not fit the LDS staging area"; return false; }
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mega_kernel, MK_THREADS, I->mega_lds) !=
+          hipSuccess || per_cu < 1) {
+    *why = "persistent workgroup does not fit a CU";
+    return false;
+  }
+  I->mega_grid = cus;   // one workgroup per CU: all co-resident, which the grid barrier needs
+  int splits = cus / c.n_heads;
+  I->mega_splits = splits > kAttnMaxSplits ? kAttnMaxSplits : splits;
+  return true;
+}
+
+void enqueue_decode_mega(Instance* I, hipStream_t s, bool trace = false) {
+  const ll_config& c = I->cfg;
+  MkArgs a{};
+  a.layers = I->at<MkLayer>(I->L.mk_layers);
+  a.tok_emb = (const half_t*)I->w.tok_emb;
+  a.final_norm = (const half_t*)I->w.final_norm;
+  a.lm_head = (const half_t*)I->w.lm_head;
+  a.x = I->at<float>(I->L.x); a.q = I->at<float>(I->L.q); a.o = I->at<float>(I->L.o);
+  a.m = I->at<float>(I->L.m); a.logits = I->at<float>(I->L.logits);
+  a.attn_part = I->at<float>(I->L.attn_part);
+  a.attn_cnt = I->at<unsigned>(I->L.attn_cnt);
+  a.amax_val = I->at<float>(I->L.mk_amax_val);
+  a.amax_idx = I->at<int>(I->L.mk_amax_idx);
+  a.rope = I->at<float2>(I->L.rope);
+  a.st = I->state();
+  a.host_ring = I->dev_ring;
+  a.bar = I->at<unsigned>(I->L.mk_bar);
+  a.ring_size = I->ring_size;
+  a.n_layers = c.n_layers; a.d = c.d_model; a.n_heads = c.n_heads; a.head_dim = c.head_dim;
+  a.F = c.ffn_hidden; a.vocab = c.vocab; a.max_seq = c.max_seq; a.attn_splits = I->mega_splits;
+  a.eps = c.rms_eps;
+  a.trace = trace ? I->at<unsigned long long>(I->L.mk_trace) : nullptr;
+  a.spin_limit = 4000000;   // a few seconds, then the step reports an error instead of hanging
+  hipLaunchKernelGGL(decode_mega_kernel, dim3(I->mega_grid), dim3(MK_THREADS), I->mega_lds, s, a);
+}
+
+void enqueue_decode(Instance* I, hipStream_t s) {
+  if (I->use_mega && I->only_class < 0 && !I->prof_events) enqueue_decode_mega(I, s);
+  else enqueue_decode_multi(I, s);
 }
 
 void launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0, const void* w1,
@@ -456,6 +535,25 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipMemset(I->state(), 0, sizeof(DevState)), "hipMemset(state)")) return bail(rc);
   if (!hip_or_bail(hipMemset(I->at<int>(L.tokens), 0, (size_t)L.mb_max * 4), "hipMemset(tokens)"))
     return bail(rc);
+  if (!hip_or_bail(hipMemset(I->at<unsigned>(L.mk_bar), 0, (size_t)MK_BAR_WORDS * 4), "hipMemset(bar)"))
+    return bail(rc);
+  {
+    std::vector<MkLayer> tab(cfg->n_layers);
+    for (int l = 0; l < cfg->n_layers; ++l) {
+      const ll_layer_weights& lw = I->layers[l];
+      tab[l] = MkLayer{(const half_t*)lw.attn_norm, (const half_t*)lw.wq, (const half_t*)lw.wk,
+                       (const half_t*)lw.wv, (const half_t*)lw.wo, (const half_t*)lw.ffn_norm,
+                       (const half_t*)lw.w_gate, (const half_t*)lw.w_up, (const half_t*)lw.w_down,
+                       I->kcache(l), I->vcache(l)};
+    }
+    if (!hip_or_bail(hipMemcpy(I->at<MkLayer>(L.mk_layers), tab.data(), tab.size() * sizeof(MkLayer),
+                               hipMemcpyHostToDevice), "hipMemcpy(layer table)")) return bail(rc);
+  }
+  if ((cfg->flags & LL_FLAG_PERSISTENT) && !(cfg->flags & (LL_FLAG_EAGER | LL_FLAG_MULTIKERNEL))) {
+    std::string why;
+    I->use_mega = mega_plan(I, &why);
+    if (!I->use_mega) return bail(fail(LL_E_BAD_CONFIG, "ll_init: persistent kernel unavailable: %s", why.c_str()));
+  }
   if (!hip_or_bail(hipDeviceSynchronize(), "hipDeviceSynchronize")) return bail(rc);
 
   for (int b = 64; b <= L.mb_max; b <<= 1) I->pf_buckets.push_back(b);
@@ -500,6 +598,9 @@ int ll_reset(void) {
   if (!g) return fail(LL_E_NOT_INIT, "ll_reset: not initialised");
   int rc = write_state(g, 0, 0, 0, 0);
   if (rc != LL_OK) return rc;
+  // also clears a barrier time-out left behind by a failed step
+  HIPCHK(hipMemsetAsync(g->at<unsigned>(g->L.mk_bar), 0, (size_t)MK_BAR_WORDS * 4, g->stream));
+  HIPCHK(hipMemsetAsync(g->at<unsigned>(g->L.attn_cnt), 0, (size_t)g->cfg.n_heads * 4, g->stream));
   HIPCHK(hipStreamSynchronize(g->stream));
   g->pos = 0;
   g->steps = 0;
@@ -564,6 +665,10 @@ int32_t ll_decode_n(int32_t k, int32_t* out_tokens) {
   int rc = run_decode_steps(I, k);
   if (rc != LL_OK) return rc;
   HIPCHK(hipStreamSynchronize(I->stream));
+  for (int i = 0; i < k; ++i)
+    if (I->host_ring[I->steps + i] < 0)
+      return fail(LL_E_HIP, "ll_decode: the persistent kernel's grid barrier timed out (are other "
+                            "kernels occupying the GPU?); call ll_reset");
   if (out_tokens) memcpy(out_tokens, I->host_ring + I->steps, (size_t)k * 4);
   I->pos += k;
   I->steps += k;
@@ -572,6 +677,12 @@ int32_t ll_decode_n(int32_t k, int32_t* out_tokens) {
 }
 
 int32_t ll_decode_step(void) { return ll_decode_n(1, nullptr); }
+
+int ll_decode_mode(void) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_decode_mode: not initialised");
+  if (g->cfg.flags & LL_FLAG_EAGER) return LL_MODE_EAGER;
+  return g->use_mega ? LL_MODE_PERSISTENT_GRAPH : LL_MODE_MULTIKERNEL_GRAPH;
+}
 
 int ll_dbg_get_logits(float* host_out) {
   if (!g) return fail(LL_E_NOT_INIT, "ll_dbg_get_logits: not initialised");
@@ -661,6 +772,26 @@ int ll_dbg_profile_decode(int32_t steps, float* us_out, int32_t* launches_out) {
     if (launches_out) launches_out[i] = (int32_t)(cnt[i] / steps);
   }
   return LL_OK;
+}
+
+int ll_dbg_trace_decode(uint64_t* ticks_out, int32_t max_phases) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_dbg_trace_decode: not initialised");
+  Instance* I = g;
+  if (!I->use_mega) return fail(LL_E_STATE, "ll_dbg_trace_decode: persistent kernel not in use");
+  const int phases = 5 * I->cfg.n_layers + 1;
+  if (!ticks_out || max_phases < phases) return fail(LL_E_BAD_ARG, "ll_dbg_trace_decode: need room for %d phases", phases);
+  if (I->pos == 0) return fail(LL_E_STATE, "ll_dbg_trace_decode: empty context");
+  if (I->pos + 1 > I->cfg.max_seq || I->steps + 1 > I->ring_size)
+    return fail(LL_E_CAPACITY, "ll_dbg_trace_decode: cache full");
+  HIPCHK(hipMemsetAsync(I->at<char>(I->L.mk_trace), 0, (size_t)phases * 8 * 8, I->stream));
+  enqueue_decode_mega(I, I->stream, true);
+  HIPCHK(hipGetLastError());
+  HIPCHK(hipStreamSynchronize(I->stream));
+  HIPCHK(hipMemcpy(ticks_out, I->at<char>(I->L.mk_trace), (size_t)phases * 8 * 8, hipMemcpyDeviceToHost));
+  I->pos += 1;
+  I->steps += 1;
+  I->last_was_prefill = false;
+  return phases;
 }
 
 int ll_dbg_stream_copy(void* dst, const void* src, size_t bytes) {

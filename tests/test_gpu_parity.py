@@ -8,6 +8,7 @@ from parity_utils import (check_logits, check_token, max_abs, rel_l2, run_teache
                           top2_margin)
 
 pytestmark = pytest.mark.gpu
+DEFAULT_MODE = 1      # what ll_init picks without LL_FLAG_PERSISTENT / LL_FLAG_MULTIKERNEL
 
 
 @pytest.fixture(scope="module")
@@ -25,7 +26,7 @@ def _session(cfg, w_np, flags=0):
 
 
 # ------------------------------------------------------------ config 1: tiny model
-@pytest.mark.parametrize("flags", [0, 1], ids=["graph", "eager"])
+@pytest.mark.parametrize("flags", [4, 2, 1, 0], ids=["persistent", "multikernel", "eager", "default"])
 def test_tiny_config_prefill_and_16_steps(torch_cuda, oracle32, flags):
     """2 layers, d=256, 4x64 heads, FFN 688, vocab 1024, fp32 weights seed 0,
     10-token prompt seed 0, prefill + 16 greedy steps.  The oracle keeps the
@@ -35,6 +36,7 @@ def test_tiny_config_prefill_and_16_steps(torch_cuda, oracle32, flags):
     prompt = wl.make_tokens(10, cfg["vocab"], seed=0)
     om = oracle32.model(cfg, w)
     with _session(cfg, w, flags) as s:
+        assert s.ll_decode_mode() == {4: 0, 2: 1, 1: 2, 0: DEFAULT_MODE}[flags]
         stats = run_teacher_forced(s, om, prompt, 16, "tiny")
         assert s.ll_position() == 26 and om.pos == 26
         # K/V rows the GPU cached (fp16) against the oracle's, both layers
@@ -73,14 +75,15 @@ SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("flags", [4, 2], ids=["persistent", "multikernel"])
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "L%d_H%dx%d_F%d_V%d_S%d_p%d" % s[:7])
-def test_shapes_tails_and_buckets(torch_cuda, oracle32, shape):
+def test_shapes_tails_and_buckets(torch_cuda, oracle32, shape, flags):
     n_layers, H, dh, F, V, max_seq, n_prompt, steps = shape
     cfg = wl.custom_cfg(n_layers, H, dh, F, V, max_seq)
     w = wl.weights_astype(wl.make_weights_numpy(cfg, seed=21, gain_jitter=0.1), np.float16)
     prompt = wl.make_tokens(n_prompt, V, seed=n_prompt)
     om = oracle32.model(cfg, w)
-    with _session(cfg, w) as s:
+    with _session(cfg, w, flags) as s:
         run_teacher_forced(s, om, prompt, steps, "shape")
         got = s.ll_dbg_get_kv(n_layers - 1, 0, n_prompt + steps)
         assert rel_l2(got, om.kv(n_layers - 1, 0)) < 3e-3
@@ -108,7 +111,7 @@ def test_graph_replay_equals_eager_and_decode_n(torch_cuda):
     w = wl.make_weights_numpy(cfg, seed=3)
     prompt = wl.make_tokens(12, cfg["vocab"], seed=9)
     runs = {}
-    for name, flags in (("graph", 0), ("eager", 1)):
+    for name, flags in (("graph", 4), ("multi", 2), ("eager", 1)):
         with _session(cfg, w, flags) as s:
             t1 = s.ll_prefill(prompt)
             toks = [t1] + [s.ll_decode_step() for _ in range(10)]
@@ -119,11 +122,12 @@ def test_graph_replay_equals_eager_and_decode_n(torch_cuda):
             toks_n = [t1b] + s.ll_decode_n(10).tolist()
             logits_n = s.ll_dbg_get_logits()
             runs[name] = (toks, logits, toks_n, logits_n)
-    g, e = runs["graph"], runs["eager"]
-    assert g[0] == g[2] and e[0] == e[2]              # decode_n == repeated decode_step, reset works
-    assert g[0] == e[0]                               # same kernels, same order
+    g, m, e = runs["graph"], runs["multi"], runs["eager"]
+    for r in (g, m, e):
+        assert r[0] == r[2]                           # decode_n == repeated decode_step, reset works
+    assert g[0] == e[0] == m[0]
     # decode kernels are deterministic; prefill accumulates split-K partials with atomics
-    assert max_abs(g[1], e[1]) < 1e-4 and max_abs(g[1], g[3]) < 1e-4
+    assert max_abs(m[1], e[1]) < 1e-4 and max_abs(g[1], e[1]) < 1e-4 and max_abs(g[1], g[3]) < 1e-4
 
 
 def test_prefill_matches_token_by_token_decode(torch_cuda, oracle32):
@@ -210,7 +214,8 @@ def test_one_7b_layer_decode_step(torch_cuda, oracle32, kv_len):
     om.close()
 
 
-def test_one_7b_layer_long_decode_to_kv_1000(torch_cuda, oracle32):
+@pytest.mark.parametrize("flags", [2, 4], ids=["multikernel", "persistent"])
+def test_one_7b_layer_long_decode_to_kv_1000(torch_cuda, oracle32, flags):
     """Decode-path attention at the long end of the regime: prompt 500, then
     500 teacher-forced decode steps (KV grows to 1000) on one 7B-shaped layer;
     hidden state compared at a sample of steps including the last."""
@@ -224,7 +229,7 @@ def test_one_7b_layer_long_decode_to_kv_1000(torch_cuda, oracle32):
     om = oracle32.model(cfg, w_np)
     om.prefill(toks[:n_prompt])
     check_at = {0, 1, 63, 64, 255, 256, 498, 499}
-    with binding.Session(cfg, w_t) as s:
+    with binding.Session(cfg, w_t, flags=flags) as s:
         s.ll_prefill(toks[:n_prompt])
         for i in range(n_steps):
             t_in = int(toks[n_prompt + i])
@@ -249,18 +254,19 @@ def test_full_7b_prompt10_teacher_forced(torch_cuda, oracle32):
     w_t = wl.make_weights_torch(cfg, seed=0, device="cuda:0")
     w_np = wl.weights_to_numpy(w_t)
     prompt = wl.make_tokens(10, cfg["vocab"], seed=0)
-    om = oracle32.model(cfg, w_np)
-    with binding.Session(cfg, w_t) as s:
-        stats = run_teacher_forced(s, om, prompt, 6, "7B")
-        # full-size LM head, sampled rows recomputed one by one from the GPU's own hidden state
-        h = s.ll_dbg_get_hidden().astype(np.float64)
-        lg = s.ll_dbg_get_logits()
-    om.close()
+    for flags, label in ((binding.LL_FLAG_MULTIKERNEL, "7B multikernel"), (binding.LL_FLAG_PERSISTENT, "7B persistent")):
+        om = oracle32.model(cfg, w_np)
+        with binding.Session(cfg, w_t, flags=flags) as s:
+            stats = run_teacher_forced(s, om, prompt, 6, label)
+            # full-size LM head, sampled rows recomputed one by one from the GPU's own hidden state
+            h = s.ll_dbg_get_hidden().astype(np.float64)
+            lg = s.ll_dbg_get_logits()
+        om.close()
+        print("%s worst max-abs %.2e rel-L2 %.2e" % (label, max(x[0] for x in stats), max(x[1] for x in stats)))
     a = h / np.sqrt(np.mean(h * h) + float(np.float32(cfg["rms_eps"])))
     rows = np.random.default_rng(0).integers(0, cfg["vocab"], size=64)
     ref = w_np["lm_head"][rows].astype(np.float64) @ a
     assert np.abs(lg[rows] - ref).max() < 2e-3
-    print("7B worst max-abs %.2e rel-L2 %.2e" % (max(x[0] for x in stats), max(x[1] for x in stats)))
     del w_t
     torch.cuda.empty_cache()
 
@@ -281,6 +287,16 @@ def test_timing_hooks_leave_a_usable_context(torch_cuda, oracle32):
         s.ll_reset()                                   # required after the class timing hook
         run_teacher_forced(s, om, prompt, 3, "after-hooks")
     om.close()
+    from paper_2604_23467_amd import binding
+    with _session(cfg, w, binding.LL_FLAG_PERSISTENT) as s:
+        s.ll_prefill(prompt)
+        t = s.ll_dbg_trace_decode()
+        assert t.shape == (5 * cfg["n_layers"] + 1, 8) and s.ll_position() == 11
+        assert (np.diff(t[:, 4]) > 0).all()            # barrier-passed stamps are ordered
+    with _session(cfg, w, binding.LL_FLAG_MULTIKERNEL) as s:
+        s.ll_prefill(prompt)
+        with pytest.raises(binding.LLError):
+            s.ll_dbg_trace_decode()
 
 
 def test_stream_copy_calibration_kernel(torch_cuda):
