@@ -11,6 +11,9 @@
 #pragma once
 #include "ll_device.h"
 
+#define ATTN_THREADS 1024
+#define ATTN_PART_STRIDE(HD) ((HD) + 4)   // floats per attention partial: m, l, 2 pad, acc[HD] (16-byte aligned)
+
 enum GemvMode { GM_QKV = 0, GM_ORES = 1, GM_GATEUP = 2, GM_DOWN = 3, GM_LMHEAD = 4 };
 
 struct GemvArgs {
@@ -33,6 +36,9 @@ struct GemvArgs {
   float* amax_val;     // [gridDim.x] best logit seen by each workgroup
   int* amax_idx;
   int x_row_from_prompt;  // 1: input vector is row (st->n_prompt - 1) of a [rows][K] matrix
+  // O projection prologue: the input vector is the merge of attn_splits split-K partials per head
+  const float* attn_part;
+  int attn_splits;
 };
 
 // The input vector is staged in LDS as fp32 in a lane-major layout: for the
@@ -116,20 +122,78 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
   const float* xin = a.xin;
   if (MODE == GM_LMHEAD && a.x_row_from_prompt) xin += (size_t)(a.st->n_prompt - 1) * K;
 
+  // O projection: its input is the merge of the attention kernel's S partials per
+  // head.  First the per-partial weights exp(m_s - M) / sum_s l_s exp(m_s - M) ...
+  float* wn = red + 8;
+  if (MODE == GM_ORES && a.attn_part) {
+    const int PS = ATTN_PART_STRIDE(a.head_dim), S = a.attn_splits;
+    for (int head = tid; head < K / a.head_dim; head += LL_WG) {
+      const float* hp = a.attn_part + (size_t)head * S * PS;
+      float M = -INFINITY, L = 0.f;
+      for (int sp = 0; sp < S; ++sp) M = fmaxf(M, hp[sp * PS]);
+      for (int sp = 0; sp < S; ++sp) {
+        const float mi = hp[sp * PS];
+        const float w = (mi > -INFINITY) ? __expf(mi - M) : 0.f;
+        wn[head * S + sp] = w;
+        L += hp[sp * PS + 1] * w;
+      }
+      const float rl = 1.0f / L;
+      for (int sp = 0; sp < S; ++sp) wn[head * S + sp] *= rl;
+    }
+    __syncthreads();
+  }
+
+  // ... then the staging proper, four float4 per thread and pass with all of a
+  // pass's loads issued before any is used (one L2 round trip, not four).
   float ss = 0.f;
-  for (int i = tid; i < nchp * 128; i += LL_WG) {
-    const int k = i * 4;
-    f4 v = {0.f, 0.f, 0.f, 0.f};
-    if (k < K) {
-      v = *reinterpret_cast<const f4*>(xin + k);
-      if (NORM) {
-        ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-        h4 g = *reinterpret_cast<const h4*>(a.gain + k);
-        v[0] *= (float)g[0]; v[1] *= (float)g[1]; v[2] *= (float)g[2]; v[3] *= (float)g[3];
+  constexpr int SU = 4;
+  for (int i0 = tid; i0 < nchp * 128; i0 += LL_WG * SU) {
+    f4 v[SU], v2[SU];
+    h4 g[SU];
+    float w0[SU], w1[SU];
+#pragma unroll
+    for (int j = 0; j < SU; ++j) {
+      const int k = (i0 + j * LL_WG) * 4;
+      v[j] = f4{0.f, 0.f, 0.f, 0.f};
+      v2[j] = v[j];
+      g[j] = h4{0, 0, 0, 0};
+      w0[j] = w1[j] = 0.f;
+      if (k < K) {
+        if (MODE == GM_ORES && a.attn_part) {
+          // o[k..k+3] of head k / head_dim: the (at most two) partial accumulators weighted by wn
+          const int HD = a.head_dim, PS = ATTN_PART_STRIDE(HD);
+          const int head = k / HD, dcol = k - head * HD;
+          const float* hp = a.attn_part + (size_t)head * a.attn_splits * PS + 4 + dcol;
+          v[j] = *reinterpret_cast<const f4*>(hp);
+          w0[j] = wn[head * a.attn_splits];
+          if (a.attn_splits > 1) {
+            v2[j] = *reinterpret_cast<const f4*>(hp + PS);
+            w1[j] = wn[head * a.attn_splits + 1];
+          }
+        } else {
+          v[j] = *reinterpret_cast<const f4*>(xin + k);
+        }
+        if (NORM) g[j] = *reinterpret_cast<const h4*>(a.gain + k);
       }
     }
-    const int c = k >> 9, r = k & 511;
-    *reinterpret_cast<f4*>(lds + c * 512 + ((r >> 2) & 1) * 256 + (r >> 3) * 4) = v;
+#pragma unroll
+    for (int j = 0; j < SU; ++j) {
+      const int k = (i0 + j * LL_WG) * 4;
+      if (k >= nchp * 512) continue;
+      f4 t = v[j];
+      if (MODE == GM_ORES && a.attn_part) {
+        t[0] = v[j][0] * w0[j] + v2[j][0] * w1[j];
+        t[1] = v[j][1] * w0[j] + v2[j][1] * w1[j];
+        t[2] = v[j][2] * w0[j] + v2[j][2] * w1[j];
+        t[3] = v[j][3] * w0[j] + v2[j][3] * w1[j];
+      }
+      if (NORM) {
+        ss += t[0] * t[0] + t[1] * t[1] + t[2] * t[2] + t[3] * t[3];
+        t[0] *= (float)g[j][0]; t[1] *= (float)g[j][1]; t[2] *= (float)g[j][2]; t[3] *= (float)g[j][3];
+      }
+      const int c = k >> 9, r = k & 511;
+      *reinterpret_cast<f4*>(lds + c * 512 + ((r >> 2) & 1) * 256 + (r >> 3) * 4) = t;
+    }
   }
   if (NORM) {
     ss = wave_sum(ss);
@@ -216,6 +280,70 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
   }
 }
 
+// Residual GEMV for long rows (K > 4096, i.e. the down projection): x += W m.
+// A 22 KB row pair handled by one wave is a serial chain of three load groups;
+// here every wave takes one K segment of at most 8 chunks instead, so ALL loads
+// of the kernel are issued up front.  Workgroup = 4 row pairs x NSEG segments
+// (NSEG waves per pair, adjacent), the NSEG partial sums meet in LDS.  grid =
+// ceil(pairs / 4), one pass, no loop.
+template <int NSEG>
+__global__ __launch_bounds__(NSEG * 256, 2) void gemv_ksplit_kernel(GemvArgs a) {
+  extern __shared__ float lds[];
+  constexpr int NT = NSEG * 256;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int K = a.K;
+  const int nch = (K + 511) >> 9;
+  const int cps = (nch + NSEG - 1) / NSEG;      // chunks per segment, <= 8
+  float* part = lds + (nch + 1) * 512;          // [4 * NSEG][2]
+  const int P = a.N >> 1;
+  const int pl = wave / NSEG, seg = wave - pl * NSEG;
+  const int p = blockIdx.x * 4 + pl;
+  const bool valid = p < P;
+  const int rowA = 2 * min(p, P - 1), rowB = rowA + 1;
+  const half_t* pa = a.w0 + (size_t)rowA * K;
+  const half_t* pb = a.w0 + (size_t)rowB * K;
+  const int gc0 = seg * cps;
+
+  h8 wa[8], wb[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {   // in flight before the input vector is staged
+    const int k = min((gc0 + u) * 512 + lane * 8, K - 8);
+    wa[u] = load_stream(pa + k);
+    wb[u] = load_stream(pb + k);
+  }
+
+  for (int i = tid; i < (nch + 1) * 128; i += NT) {   // chunk nch stays zero
+    const int k = i * 4;
+    f4 v = {0.f, 0.f, 0.f, 0.f};
+    if (k < K) v = *reinterpret_cast<const f4*>(a.xin + k);
+    const int c = k >> 9, r = k & 511;
+    *reinterpret_cast<f4*>(lds + c * 512 + ((r >> 2) & 1) * 256 + (r >> 3) * 4) = v;
+  }
+  __syncthreads();
+
+  float accA = 0.f, accB = 0.f;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const int gc = gc0 + u;
+    const int xc = (u < cps && gc < nch) ? gc : nch;
+    const float* xp = lds + xc * 512 + lane * 4;
+    const f4 x0 = *reinterpret_cast<const f4*>(xp);
+    const f4 x1 = *reinterpret_cast<const f4*>(xp + 256);
+    accA = dot8(wa[u], x0, x1, accA);
+    accB = dot8(wb[u], x0, x1, accB);
+  }
+  accA = wave_sum(accA);
+  accB = wave_sum(accB);
+  if (lane == 0) { part[wave * 2] = accA; part[wave * 2 + 1] = accB; }
+  __syncthreads();
+  if (valid && seg == 0 && lane == 0) {
+    for (int sg = 1; sg < NSEG; ++sg) { accA += part[(wave + sg) * 2]; accB += part[(wave + sg) * 2 + 1]; }
+    a.out[rowA] += accA;
+    a.out[rowB] += accB;
+  }
+}
+
 // x = float(E[next_token])
 __global__ __launch_bounds__(LL_WG) void embed_kernel(const half_t* __restrict__ emb,
                                                       const DevState* __restrict__ st,
@@ -231,27 +359,29 @@ __global__ __launch_bounds__(LL_WG) void embed_kernel(const half_t* __restrict__
 
 // Split-K attention of the one new query against keys 0..pos of one head.
 //
-// grid = (heads, S).  A key row (HD halves) is read by HD/8 adjacent lanes with
-// one 16-byte load each, so a wave covers 64/(HD/8) consecutive keys per load.
-// Every such lane group keeps its own online-softmax state (running max m,
-// denominator l, 8 output columns per lane) over the keys it is dealt, round
-// robin over all groups of all S workgroups of the head -- the grid is fixed
-// and the key range comes from DevState, so the same captured launch serves
-// every KV length.  Groups are merged through LDS, workgroups through a
-// partial buffer; the last workgroup of a head to arrive (device-scope counter)
-// merges the S partials and writes o.
+// grid = (heads, S), 1024 threads.  A key row (HD halves) is read by HD/8
+// adjacent lanes with one 16-byte load each, so a wave covers 64/(HD/8)
+// consecutive keys per load.  Every such lane group keeps its own
+// online-softmax state (running max m, denominator l, 8 output columns per
+// lane) over the keys it is dealt, round robin over all groups of all S
+// workgroups of the head -- the grid is fixed and the key range comes from
+// DevState, so the same captured launch serves every KV length.  With S = 2
+// and 8 keys in flight per group one pass covers 1024 keys.  Groups merge
+// inside the wave by shuffles, waves through LDS; the S partials (m, l,
+// acc[HD]) of a head are merged by the consumer, the O-projection's prologue,
+// which costs it 2 x 130 floats per head and saves this kernel a cross-
+// workgroup hand-off (stores -> counter -> reload: about 5 us of pure latency).
+
 template <int HD>
-__global__ __launch_bounds__(LL_WG) void attn_decode_kernel(
+__global__ __launch_bounds__(ATTN_THREADS) void attn_decode_kernel(
     const float* __restrict__ q, const half_t* __restrict__ kc, const half_t* __restrict__ vc,
-    const DevState* __restrict__ st, float* part, unsigned* cnt, float* __restrict__ o,
-    int max_seq) {
+    const DevState* __restrict__ st, float* __restrict__ part, int max_seq) {
   constexpr int LPR = HD / 8;      // lanes per key row
   constexpr int GPW = 64 / LPR;    // lane groups per wave
-  constexpr int NG = (LL_WG / 64) * GPW;
-  constexpr int UK = 4;            // keys in flight per group
-  constexpr int PS = HD + 2;       // floats per partial: m, l, acc[HD]
-  __shared__ float s_m[NG], s_l[NG], s_acc[NG][HD];
-  __shared__ int s_last;
+  constexpr int NW = ATTN_THREADS / 64;
+  constexpr int UK = 8;            // keys in flight per group
+  constexpr int PS = ATTN_PART_STRIDE(HD);
+  __shared__ float s_m[NW], s_l[NW], s_acc[NW][HD];
 
   const int h = blockIdx.x, s = blockIdx.y, S = gridDim.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -273,14 +403,14 @@ __global__ __launch_bounds__(LL_WG) void attn_decode_kernel(
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
 
-  const int stride = S * (LL_WG / 64) * GPW;
-  for (int base = (s * (LL_WG / 64) + wave) * GPW; base < n_keys; base += stride * UK) {
+  const int stride = S * NW * GPW;
+  for (int base = (s * NW + wave) * GPW; base < n_keys; base += stride * UK) {
     h8 kk[UK], vv[UK];
 #pragma unroll
     for (int j = 0; j < UK; ++j) {
       const int u = min(base + j * stride + gi, n_keys - 1);
-      kk[j] = *reinterpret_cast<const h8*>(kh + (size_t)u * HD);
-      vv[j] = *reinterpret_cast<const h8*>(vh + (size_t)u * HD);
+      kk[j] = load_h8(kh + (size_t)u * HD);
+      vv[j] = load_h8(vh + (size_t)u * HD);
     }
 #pragma unroll
     for (int j = 0; j < UK; ++j) {
@@ -300,61 +430,46 @@ __global__ __launch_bounds__(LL_WG) void attn_decode_kernel(
     }
   }
 
-  const int g = wave * GPW + gi;
-  if (li == 0) { s_m[g] = m; s_l[g] = l; }
+  // merge the lane groups of this wave: lanes with equal li hold the same columns
+  {
+    float M = m;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) s_acc[g][li * 8 + e] = acc[e];
+    for (int off = LPR; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
+    const float w = (M > -INFINITY) ? __expf(m - M) : 0.f;   // empty groups (m = -inf) weigh 0
+    l *= w;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] *= w;
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+      l += __shfl_xor(l, off);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += __shfl_xor(acc[e], off);
+    }
+    if (gi == 0) {
+      if (li == 0) { s_m[wave] = M; s_l[wave] = l; }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s_acc[wave][li * 8 + e] = acc[e];
+    }
+  }
   __syncthreads();
 
-  float* mypart = part + ((size_t)h * S + s) * PS;
-  if (tid < HD) {
+  if (tid < HD) {   // merge the waves, publish this workgroup's partial
     float M = -INFINITY;
-    for (int i = 0; i < NG; ++i) M = fmaxf(M, s_m[i]);
+#pragma unroll
+    for (int i = 0; i < NW; ++i) M = fmaxf(M, s_m[i]);
     float L = 0.f, A = 0.f;
     if (M > -INFINITY) {
-      for (int i = 0; i < NG; ++i) {
-        const float w = __expf(s_m[i] - M);   // empty groups: exp(-inf) = 0
+#pragma unroll
+      for (int i = 0; i < NW; ++i) {
+        const float w = (s_m[i] > -INFINITY) ? __expf(s_m[i] - M) : 0.f;
         L += s_l[i] * w;
         A += s_acc[i][tid] * w;
       }
     }
-    if (tid == 0) {
-      __hip_atomic_store(mypart + 0, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(mypart + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __hip_atomic_store(mypart + 2 + tid, A, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    float* mypart = part + ((size_t)h * S + s) * PS;
+    if (tid == 0) { mypart[0] = M; mypart[1] = L; }
+    mypart[4 + tid] = A;
   }
-  // Publishing without a cache flush: the partial was written with device-scope
-  // atomic stores, which are coherent across the per-XCD L2s on their own, and
-  // the counter increment is issued only after every such store of this
-  // workgroup has completed (wait for the vector-memory counter, then the
-  // workgroup barrier).  The reader's loads below are device-scope atomics
-  // too and are issued after its own increment has returned.  A release fence
-  // here would write back the whole L2 in every workgroup, which costs far
-  // more than the attention itself.
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  if (tid == 0) {
-    const unsigned t = __hip_atomic_fetch_add(cnt + h, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    s_last = (t == (unsigned)(S - 1));
-  }
-  __syncthreads();
-  if (!s_last) return;
-  if (tid < HD) {
-    const float* hp = part + (size_t)h * S * PS;
-    float M = -INFINITY;
-    for (int i = 0; i < S; ++i)
-      M = fmaxf(M, __hip_atomic_load(hp + i * PS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    float L = 0.f, A = 0.f;
-    for (int i = 0; i < S; ++i) {
-      const float mi = __hip_atomic_load(hp + i * PS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const float w = (mi > -INFINITY) ? __expf(mi - M) : 0.f;
-      L += __hip_atomic_load(hp + i * PS + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * w;
-      A += __hip_atomic_load(hp + i * PS + 2 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * w;
-    }
-    o[h * HD + tid] = A / L;
-  }
-  if (tid == 0) __hip_atomic_store(cnt + h, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Final argmax over the per-workgroup candidates of the LM head (ties: lowest

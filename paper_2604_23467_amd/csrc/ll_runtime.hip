@@ -84,9 +84,7 @@ int gemv_grid(int pairs) {
 Layout make_layout(const ll_config& c) {
   Layout L{};
   const size_t d = c.d_model, F = c.ffn_hidden, V = c.vocab;
-  L.attn_splits = 256 / c.n_heads;
-  if (L.attn_splits < 1) L.attn_splits = 1;
-  if (L.attn_splits > kAttnMaxSplits) L.attn_splits = kAttnMaxSplits;
+  L.attn_splits = (c.n_heads * 2 <= 512) ? 2 : 1;   // two 1024-thread workgroups per head
   L.lm_wgs = gemv_grid((c.vocab + 1) / 2);
   L.max_prompt = c.max_seq - 1 < kMaxPromptBucket ? c.max_seq - 1 : kMaxPromptBucket;
   L.mb_max = prompt_bucket(L.max_prompt);
@@ -99,7 +97,7 @@ Layout make_layout(const ll_config& c) {
   L.q = take(d * 4);
   L.o = take(d * 4);
   L.m = take(F * 4);
-  L.attn_part = take((size_t)c.n_heads * kAttnMaxSplits * (c.head_dim + 2) * 4);
+  L.attn_part = take((size_t)c.n_heads * kAttnMaxSplits * (c.head_dim + 4) * 4);
   L.attn_cnt = take((size_t)c.n_heads * 4);
   L.logits = take(V * 4);
   L.amax_val = take((size_t)L.lm_wgs * 4);
@@ -164,7 +162,7 @@ Instance* g = nullptr;
 size_t gemv_lds_bytes(int K) {
   const int nch = (K + 511) / 512;
   const int nchp = (nch + kGemvU - 1) / kGemvU * kGemvU;
-  return ((size_t)nchp * 512 + 8) * sizeof(float);
+  return ((size_t)nchp * 512 + 8 + 512) * sizeof(float);   // input vector, reduction scratch, attention merge weights
 }
 
 struct ProfScope {
@@ -251,18 +249,17 @@ void enqueue_decode_multi(Instance* I, hipStream_t s) {
       ProfScope ps(I, s, LL_KC_ATTN);
       dim3 grid(c.n_heads, I->L.attn_splits);
       if (c.head_dim == 128)
-        hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(LL_WG), 0, s, q, I->kcache(l),
-                           I->vcache(l), I->state(), I->at<float>(I->L.attn_part),
-                           I->at<unsigned>(I->L.attn_cnt), o, c.max_seq);
+        hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(ATTN_THREADS), 0, s, q, I->kcache(l),
+                           I->vcache(l), I->state(), I->at<float>(I->L.attn_part), c.max_seq);
       else
-        hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(LL_WG), 0, s, q, I->kcache(l),
-                           I->vcache(l), I->state(), I->at<float>(I->L.attn_part),
-                           I->at<unsigned>(I->L.attn_cnt), o, c.max_seq);
+        hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(ATTN_THREADS), 0, s, q, I->kcache(l),
+                           I->vcache(l), I->state(), I->at<float>(I->L.attn_part), c.max_seq);
     }
     if (I->runs(LL_KC_OPROJ)) {
       ProfScope ps(I, s, LL_KC_OPROJ);
       GemvArgs a{};
       a.w0 = (const half_t*)W.wo; a.xin = o; a.out = x; a.N = d; a.K = d;
+      a.attn_part = I->at<float>(I->L.attn_part); a.attn_splits = I->L.attn_splits; a.head_dim = c.head_dim;
       launch_gemv<GM_ORES>(a, d / 2, 0, s);
     }
     if (I->runs(LL_KC_GATEUP)) {
@@ -277,7 +274,13 @@ void enqueue_decode_multi(Instance* I, hipStream_t s) {
       ProfScope ps(I, s, LL_KC_DOWN);
       GemvArgs a{};
       a.w0 = (const half_t*)W.w_down; a.xin = m; a.out = x; a.N = d; a.K = F;
-      launch_gemv<GM_DOWN>(a, d / 2, 0, s);
+      const int nch = (F + 511) / 512, nseg = (nch + 7) / 8;
+      const size_t lds = ((size_t)(nch + 1) * 512 + 4 * 4 * 2) * sizeof(float);
+      const int grid = (d / 2 + 3) / 4;
+      if (nseg == 2) hipLaunchKernelGGL(gemv_ksplit_kernel<2>, dim3(grid), dim3(512), lds, s, a);
+      else if (nseg == 3) hipLaunchKernelGGL(gemv_ksplit_kernel<3>, dim3(grid), dim3(768), lds, s, a);
+      else if (nseg == 4) hipLaunchKernelGGL(gemv_ksplit_kernel<4>, dim3(grid), dim3(1024), lds, s, a);
+      else launch_gemv<GM_DOWN>(a, d / 2, 0, s);   // short rows, or too long to split over one workgroup
     }
   }
   enqueue_head(I, s, x, 0, 0);
@@ -481,7 +484,8 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
     return fail(LL_E_WORKSPACE, "ll_init: workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign)
     return fail(LL_E_WORKSPACE, "ll_init: workspace must be %zu-byte aligned", kAlign);
-  if (gemv_lds_bytes(cfg->ffn_hidden) > 64 * 1024 || gemv_lds_bytes(cfg->d_model) > 64 * 1024)
+  if (gemv_lds_bytes(cfg->ffn_hidden) > 64 * 1024 || gemv_lds_bytes(cfg->d_model) > 64 * 1024 ||
+      cfg->n_heads * 2 > 512)
     return fail(LL_E_BAD_CONFIG, "ll_init: d_model / ffn_hidden too large for the LDS-staged GEMV");
 
   Instance* I = new Instance();

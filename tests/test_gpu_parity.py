@@ -72,6 +72,8 @@ SHAPES = [
     (2, 4, 64, 688, 1024, 200, 65, 2),      # one row into the next bucket
     (1, 3, 128, 1000, 501, 300, 150, 4),    # d=384 (K not a multiple of 512), ragged FFN
     (2, 2, 64, 136, 33, 40, 7, 30),         # tiny everything, decode to near max_seq
+    (1, 2, 64, 4616, 100, 48, 5, 3),        # FFN rows of 10 chunks: down projection split in 2 K segments
+    (1, 2, 64, 8712, 100, 48, 5, 3),        # 18 chunks: 3 K segments, ragged last one
 ]
 
 
