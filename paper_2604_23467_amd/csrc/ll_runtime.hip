@@ -68,7 +68,7 @@ int prompt_bucket(int n) {   // smallest of {64,128,256,512} holding n rows
 struct Layout {
   size_t kv, rope, x, q, o, m, attn_part, attn_cnt, logits, amax_val, amax_idx, state, tokens;
   size_t pf_x, pf_xn, pf_qkv, pf_q, pf_o, pf_gu, pf_h;
-  size_t mk_layers, mk_bar, mk_amax_val, mk_amax_idx, mk_trace;
+  size_t mk_layers, mk_bar, mk_amax_val, mk_amax_idx, mk_trace, zeros;
   size_t total;
   int attn_splits, lm_wgs, max_prompt, mb_max;
   size_t kv_layer_halves;   // halves per layer per K or V
@@ -112,6 +112,7 @@ Layout make_layout(const ll_config& c) {
   L.pf_o = take(M * d * 2);
   L.pf_gu = take(M * 2 * F * 4);
   L.pf_h = take(M * F * 2);
+  L.zeros = take(256);
   L.mk_layers = take((size_t)c.n_layers * sizeof(MkLayer));
   L.mk_bar = take((size_t)MK_BAR_WORDS * 4);
   L.mk_amax_val = take(1024 * 4);   // one candidate per workgroup of the persistent kernel
@@ -359,20 +360,24 @@ void launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0, co
   ga.A = A;
   ga.W[0] = (const half_t*)w0; ga.W[1] = (const half_t*)w1; ga.W[2] = (const half_t*)w2;
   ga.C = C; ga.st = I->state();
+  ga.zeros = I->at<half_t>(I->L.zeros);
   ga.N = N; ga.K = K; ga.ldc = ldc; ga.nmat = nmat;
-  ga.mtiles = Mb / PF_BM;
+  const int bm = Mb >= 128 ? 128 : 64;
+  ga.mtiles = Mb / bm;
   ga.ntiles = (N + PF_BN - 1) / PF_BN;
   const int total_nt = ga.ntiles * nmat;
   const int tiles = ga.mtiles * total_nt;
   const int ktiles = (K + PF_BK - 1) / PF_BK;
-  int ks = (1024 + tiles - 1) / tiles;           // aim at >= ~1024 workgroups
-  if (ks > ktiles / 2) ks = ktiles / 2;
+  int ks = (256 + tiles - 1) / tiles;            // at least one workgroup per CU (measured best of 1..3)
+  if (ks > ktiles / 4) ks = ktiles / 4;          // at least 4 slabs per workgroup
   if (ks < 1) ks = 1;
   ga.kt_per_split = (ktiles + ks - 1) / ks;
   ks = (ktiles + ga.kt_per_split - 1) / ga.kt_per_split;
+  ga.atomic = ks > 1;
   const int nt_rounds = (total_nt + 7) / 8;      // n-tiles are dealt to the 8 XCDs
   dim3 grid(nt_rounds * ga.mtiles * 8, ks);
-  hipLaunchKernelGGL(pf_gemm_kernel, grid, dim3(LL_WG), 0, s, ga);
+  if (bm == 128) hipLaunchKernelGGL(pf_gemm_kernel<128>, grid, dim3(LL_WG), PF_GEMM_LDS_BYTES(128), s, ga);
+  else hipLaunchKernelGGL(pf_gemm_kernel<64>, grid, dim3(LL_WG), PF_GEMM_LDS_BYTES(64), s, ga);
 }
 
 void enqueue_prefill(Instance* I, hipStream_t s, int Mb) {
@@ -395,12 +400,12 @@ void enqueue_prefill(Instance* I, hipStream_t s, int Mb) {
     hipLaunchKernelGGL(pf_rope_kv_kernel, dim3(Mb), dim3(LL_WG), 0, s, QKV,
                        I->at<float2>(I->L.rope), I->state(), Qh, I->kcache(l), I->vcache(l), d,
                        c.head_dim, c.max_seq);
-    dim3 agrid(c.n_heads, Mb / 32);
+    dim3 agrid(c.n_heads, Mb / 64);
     if (c.head_dim == 128)
-      hipLaunchKernelGGL(pf_attn_kernel<128>, agrid, dim3(LL_WG), 0, s, Qh, I->kcache(l),
+      hipLaunchKernelGGL(pf_attn_kernel<128>, agrid, dim3(128), 0, s, Qh, I->kcache(l),
                          I->vcache(l), I->state(), Oh, d, c.max_seq);
     else
-      hipLaunchKernelGGL(pf_attn_kernel<64>, agrid, dim3(LL_WG), 0, s, Qh, I->kcache(l),
+      hipLaunchKernelGGL(pf_attn_kernel<64>, agrid, dim3(128), 0, s, Qh, I->kcache(l),
                          I->vcache(l), I->state(), Oh, d, c.max_seq);
     launch_gemm(I, s, Oh, W.wo, nullptr, nullptr, 1, X, d, d, d, Mb);
     hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(LL_WG), 0, s, X, (const half_t*)W.ffn_norm,
@@ -539,6 +544,13 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipMemset(I->state(), 0, sizeof(DevState)), "hipMemset(state)")) return bail(rc);
   if (!hip_or_bail(hipMemset(I->at<int>(L.tokens), 0, (size_t)L.mb_max * 4), "hipMemset(tokens)"))
     return bail(rc);
+  if (!hip_or_bail(hipMemset(I->at<char>(L.zeros), 0, 256), "hipMemset(zeros)")) return bail(rc);
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128)),
+                   "hipFuncSetAttribute(gemm 128)")) return bail(rc);
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<64>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(64)),
+                   "hipFuncSetAttribute(gemm 64)")) return bail(rc);
   if (!hip_or_bail(hipMemset(I->at<unsigned>(L.mk_bar), 0, (size_t)MK_BAR_WORDS * 4), "hipMemset(bar)"))
     return bail(rc);
   {
