@@ -52,6 +52,17 @@ def gateup_bytes(cfg):
     return 2 * F * d * 2 + 2 * d + 4 * d + 4 * F
 
 
+def counter_traffic():
+    """HBM bytes per gate/up launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE runs of `bench.py --counters`, each scaled by a copy kernel of known size), or None."""
+    path = os.path.join(ROOT, "profiles", "counters_gateup_7b.json")
+    try:
+        with open(path) as f:
+            return json.load(f)["traffic_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def pct(v, p):
     v = np.sort(np.asarray(v))
     k = max(0, min(len(v) - 1, int(np.ceil(p / 100.0 * len(v))) - 1))   # nearest rank
@@ -103,6 +114,7 @@ def main():
         return 0
 
     sess = binding.Session(cfg, w_t)
+    decode_mode = ("persistent-kernel graph", "multi-kernel graph", "eager")[sess.ll_decode_mode()]
     log("[bench] init done; warm-up: prefill(%d) + %d steps" % (n_prompt, W))
     sess.ll_prefill(prompt)
     if W > 0:
@@ -188,10 +200,22 @@ def main():
             gs.ll_decode_step()
             gl[i] = time.perf_counter() - t0
         gs.close()
+        ps = binding.Session(cfg, w_t, flags=binding.LL_FLAG_PERSISTENT)
+        ps.ll_prefill(prompt[:10])
+        ps.ll_decode_n(10)
+        pl = np.empty(100)
+        for i in range(100):
+            t0 = time.perf_counter()
+            ps.ll_decode_step()
+            pl[i] = time.perf_counter() - t0
+        ps.close()
         eager = dict(prompt=10, steps=100, eager_p50_us=pct(el, 50) * 1e6, eager_p99_us=pct(el, 99) * 1e6,
-                     graph_p50_us=pct(gl, 50) * 1e6, graph_p99_us=pct(gl, 99) * 1e6)
-        log("[bench] prompt 10, 100 steps: graph p50 %.1f us p99 %.1f us | eager p50 %.1f us p99 %.1f us"
-            % (eager["graph_p50_us"], eager["graph_p99_us"], eager["eager_p50_us"], eager["eager_p99_us"]))
+                     graph_p50_us=pct(gl, 50) * 1e6, graph_p99_us=pct(gl, 99) * 1e6,
+                     persistent_kernel_p50_us=pct(pl, 50) * 1e6, persistent_kernel_p99_us=pct(pl, 99) * 1e6)
+        log("[bench] prompt 10, 100 steps: graph p50 %.1f us p99 %.1f us | eager p50 %.1f us p99 %.1f us | "
+            "one persistent kernel p50 %.1f us p99 %.1f us"
+            % (eager["graph_p50_us"], eager["graph_p99_us"], eager["eager_p50_us"], eager["eager_p99_us"],
+               eager["persistent_kernel_p50_us"], eager["persistent_kernel_p99_us"]))
 
     # ---- CPU oracle on this machine's host cores (bounded sample; a reported baseline, not the target)
     cpu = None
@@ -231,6 +255,7 @@ def main():
                                "decode steps as hipGraph replays (KV %d -> %d)"
                                % (n_prompt, K, n_prompt, n_prompt + K),
                    "prompt_len": n_prompt, "decode_steps": K},
+        "decode_mode": decode_mode,
         "p50_us": p50,
         "p99_us": p99,
         "tokens_per_s": 1e3 / ms_per_step,
@@ -239,7 +264,7 @@ def main():
                  "frac_of_peak_hbm": step_gbs / HBM_PEAK_GBS, "sum_of_kernels_ms": kernel_sum_ms},
         "roofline": {"kernel": "gemv_kernel<GATEUP> (RMSNorm + gate/up GEMV + SwiGLU)", "bound": "hbm",
                      "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gu_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "frac": gu_gbs / HBM_PEAK_GBS, "traffic": counter_traffic(),
                      "bytes_per_launch": gateup_bytes(cfg), "avg_us": gu_us},
         "kernels_us": {k: {"avg_us": us, "launches_per_step": n} for k, (us, n) in prof.items()},
         "graph_vs_eager": eager,

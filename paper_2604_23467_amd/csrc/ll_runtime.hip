@@ -368,7 +368,10 @@ void launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0, co
   const int total_nt = ga.ntiles * nmat;
   const int tiles = ga.mtiles * total_nt;
   const int ktiles = (K + PF_BK - 1) / PF_BK;
-  int ks = (256 + tiles - 1) / tiles;            // at least one workgroup per CU (measured best of 1..3)
+  // 128-row tiles: one workgroup per CU (measured best of 1..3); 64-row tiles are weight-stream
+  // bound and want two resident workgroups per CU with their slabs in flight
+  const int want_wgs = bm == 128 ? 256 : 512;
+  int ks = (want_wgs + tiles - 1) / tiles;
   if (ks > ktiles / 4) ks = ktiles / 4;          // at least 4 slabs per workgroup
   if (ks < 1) ks = 1;
   ga.kt_per_split = (ktiles + ks - 1) / ks;
@@ -376,8 +379,8 @@ void launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0, co
   ga.atomic = ks > 1;
   const int nt_rounds = (total_nt + 7) / 8;      // n-tiles are dealt to the 8 XCDs
   dim3 grid(nt_rounds * ga.mtiles * 8, ks);
-  if (bm == 128) hipLaunchKernelGGL(pf_gemm_kernel<128>, grid, dim3(LL_WG), PF_GEMM_LDS_BYTES(128), s, ga);
-  else hipLaunchKernelGGL(pf_gemm_kernel<64>, grid, dim3(LL_WG), PF_GEMM_LDS_BYTES(64), s, ga);
+  if (bm == 128) hipLaunchKernelGGL((pf_gemm_kernel<128, 2>), grid, dim3(LL_WG), PF_GEMM_LDS_BYTES(128, 2), s, ga);
+  else hipLaunchKernelGGL((pf_gemm_kernel<64, 3>), grid, dim3(LL_WG), PF_GEMM_LDS_BYTES(64, 3), s, ga);
 }
 
 void enqueue_prefill(Instance* I, hipStream_t s, int Mb) {
@@ -545,11 +548,11 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipMemset(I->at<int>(L.tokens), 0, (size_t)L.mb_max * 4), "hipMemset(tokens)"))
     return bail(rc);
   if (!hip_or_bail(hipMemset(I->at<char>(L.zeros), 0, 256), "hipMemset(zeros)")) return bail(rc);
-  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128)),
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128, 2>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128, 2)),
                    "hipFuncSetAttribute(gemm 128)")) return bail(rc);
-  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<64>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(64)),
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<64, 3>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(64, 3)),
                    "hipFuncSetAttribute(gemm 64)")) return bail(rc);
   if (!hip_or_bail(hipMemset(I->at<unsigned>(L.mk_bar), 0, (size_t)MK_BAR_WORDS * 4), "hipMemset(bar)"))
     return bail(rc);

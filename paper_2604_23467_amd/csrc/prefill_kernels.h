@@ -74,7 +74,9 @@ __global__ __launch_bounds__(LL_WG) void pf_rmsnorm_kernel(const float* __restri
 // both operands in LDS a 64 x 64 wave tile moves 1 KB of LDS per MFMA, which
 // is what bounds this kernel (measured: dropping the MFMAs changes nothing,
 // dropping the loads gains 25 %), so LDS capacity is better spent on a second
-// resident workgroup than on deeper prefetch.  A direct load writes the 64 lanes' 16-byte pieces to consecutive LDS addresses, so
+// resident workgroup than on deeper prefetch: 2 stages for the 128-row tile
+// (measured against 3 and 4).  The 64-row tile of the short-prompt bucket is
+// bound by the weight stream instead and gets 3 stages.  A direct load writes the 64 lanes' 16-byte pieces to consecutive LDS addresses, so
 // rows are stored unpadded (128 bytes) and bank conflicts are avoided by an XOR
 // swizzle instead: 16-byte chunk c of row r lives at chunk position c ^ (r & 7).
 // Pieces outside the matrices (K tail, rows >= N) are fetched from a block of
@@ -99,15 +101,14 @@ struct GemmArgs {
 
 #define PF_BN 128
 #define PF_BK 64
-#define PF_STAGES 2   // measured: 2 stages and two resident workgroups per CU beat 3 or 4 stages and one
-#define PF_GEMM_LDS_BYTES(BM) (PF_STAGES * ((BM) + PF_BN) * PF_BK * 2)
+#define PF_GEMM_LDS_BYTES(BM, STAGES) ((STAGES) * ((BM) + PF_BN) * PF_BK * 2)
 
 template <int N>
 __device__ __forceinline__ void wait_vm_at_most() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int BM>
+template <int BM, int PF_STAGES>
 __global__ __launch_bounds__(LL_WG) void pf_gemm_kernel(GemmArgs g) {
   constexpr int MT = BM / 64;             // 32-row MFMA tiles per wave
   constexpr int A_LD = BM / 32;           // 1 KB direct loads per wave and slab for A (8 rows each)
