@@ -16,6 +16,7 @@ replay vs eager launches, and the CPU oracle timed on this machine's host cores.
 """
 import argparse
 import json
+import re
 import os
 import sys
 import time
@@ -55,11 +56,12 @@ def gateup_bytes(cfg):
 def counter_traffic():
     """HBM bytes per gate/up launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and
     WRITE_SIZE runs of `bench.py --counters`, each scaled by a copy kernel of known size), or None."""
-    path = os.path.join(ROOT, "profiles", "counters_gateup_7b.json")
+    path = os.path.join(ROOT, "profiles", "counters_decode_gemv_7b.md")
     try:
         with open(path) as f:
-            return json.load(f)["traffic_bytes_per_launch"]
-    except (OSError, KeyError, ValueError):
+            m = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", f.read(), re.M)
+        return int(m.group(1)) if m else None
+    except OSError:
         return None
 
 
