@@ -84,6 +84,10 @@ def main():
     ap.add_argument("--counters", action="store_true",
                     help="short run for `rocprofv3 --pmc`: a 256 MiB device copy as the counter "
                          "calibration, then prefill + the decode steps; no timing, no JSON")
+    ap.add_argument("--sweep", type=int, default=0, metavar="REPS",
+                    help="latency sweep instead of the default run: for every prompt length in "
+                         "{10,25,50,100,250,500}, REPS repetitions (token seed 1000*len + rep) of reset + "
+                         "prefill + --steps decode steps; prints TTFT and per-token p50/p99 per length")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (batch-1 latency path, no sharding or "
@@ -122,6 +126,36 @@ def main():
     if W > 0:
         sess.ll_decode_n(W)
     sess.ll_reset()
+
+    if args.sweep > 0:
+        out = {"metric": "latency sweep: TTFT and per-token latency p50/p99 per prompt length", "unit": "us",
+               "n_gpus": 1, "reps": args.sweep, "decode_steps": K, "decode_mode": decode_mode,
+               "dtype": "f16", "data": "synthetic", "lengths": {}}
+        for n in PROMPT_LENGTHS:
+            tt, lat = np.empty(args.sweep), np.empty((args.sweep, K))
+            for r in range(args.sweep):
+                p = wl.make_tokens(n, cfg["vocab"], seed=wl.sweep_token_seed(n, r))
+                sess.ll_reset()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                sess.ll_prefill(p)
+                tt[r] = time.perf_counter() - t0
+                for i in range(K):
+                    t0 = time.perf_counter()
+                    sess.ll_decode_step()
+                    lat[r, i] = time.perf_counter() - t0
+            dec = [pct(lat[:, K * j // 10:K * (j + 1) // 10].ravel(), 99) * 1e6 for j in range(10)]
+            out["lengths"][str(n)] = {
+                "ttft_p50_ms": pct(tt, 50) * 1e3, "ttft_p99_ms": pct(tt, 99) * 1e3,
+                "token_p50_us": pct(lat.ravel(), 50) * 1e6, "token_p99_us": pct(lat.ravel(), 99) * 1e6,
+                "token_max_us": float(lat.max()) * 1e6, "samples": int(lat.size),
+                "token_p99_us_by_generation_decile": dec}
+            log("[bench] sweep prompt %4d: TTFT p50 %.3f ms p99 %.3f ms | token p50 %.1f us p99 %.1f us (%d samples)"
+                % (n, pct(tt, 50) * 1e3, pct(tt, 99) * 1e3, pct(lat.ravel(), 50) * 1e6,
+                   pct(lat.ravel(), 99) * 1e6, lat.size))
+        sess.close()
+        print(json.dumps(out), flush=True)
+        return 0
 
     # ---- TTFT per prompt length (host wall clock of ll_prefill, ids in host memory)
     ttft = {}

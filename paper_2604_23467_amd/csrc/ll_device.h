@@ -87,3 +87,13 @@ __device__ __forceinline__ float dot8(h8 w, f4 x0, f4 x1, float acc) {
   acc += (float)w[7] * x1[3];
   return acc;
 }
+
+// "Fragment-major" layout of an fp16 activation matrix of 16*TB token rows that feeds the
+// short-prompt kernels' MFMA B operand: the 16 bytes lane (16 g + r) needs for K step s and
+// token block t (token 16 t + r, k = 32 s + 8 g .. + 8) are stored at lane-consecutive
+// addresses, so a wave's fragment is one contiguous 1 KB load.  Offset in halves of element
+// (tok, k); tb = 0 selects plain row-major with row length K.
+__host__ __device__ __forceinline__ size_t act_offset(int tok, int k, int K, int tb) {
+  if (tb == 0) return (size_t)tok * K + k;
+  return ((size_t)((k >> 5) * tb + (tok >> 4)) * 64 + ((k >> 3) & 3) * 16 + (tok & 15)) * 8 + (k & 7);
+}

@@ -15,6 +15,7 @@
 #include "decode_kernels.h"
 #include "decode_mega.h"
 #include "prefill_kernels.h"
+#include "prefill_skinny.h"
 
 namespace {
 
@@ -65,9 +66,14 @@ int prompt_bucket(int n) {   // smallest of {64,128,256,512} holding n rows
   return b;
 }
 
+// Shapes the short-prompt kernels accept: 16-row blocks that keep RoPE pairs / gate-up pairs together
+bool skinny_ok(const ll_config& c) {
+  return c.d_model % 16 == 0 && c.head_dim % 16 == 0 && c.ffn_hidden % 8 == 0;
+}
+
 struct Layout {
   size_t kv, rope, x, q, o, m, attn_part, attn_cnt, logits, amax_val, amax_idx, state, tokens;
-  size_t pf_x, pf_xn, pf_qkv, pf_q, pf_o, pf_gu, pf_h;
+  size_t pf_x, pf_xn, pf_qkv, pf_q, pf_o, pf_gu, pf_h, pf_ss;
   size_t mk_layers, mk_bar, mk_amax_val, mk_amax_idx, mk_trace, zeros;
   size_t total;
   int attn_splits, lm_wgs, max_prompt, mb_max;
@@ -106,12 +112,13 @@ Layout make_layout(const ll_config& c) {
   L.tokens = take((size_t)L.mb_max * 4);
   const size_t M = L.mb_max;
   L.pf_x = take(M * d * 4);
-  L.pf_xn = take(M * d * 2);
+  L.pf_xn = take(M * ((d + 31) / 32 * 32) * 2);          // K rounded up: fragment-major layout
   L.pf_qkv = take(M * 3 * d * 4);
   L.pf_q = take(M * d * 2);
-  L.pf_o = take(M * d * 2);
+  L.pf_o = take(M * ((d + 31) / 32 * 32) * 2);
   L.pf_gu = take(M * 2 * F * 4);
-  L.pf_h = take(M * F * 2);
+  L.pf_h = take(M * ((F + 31) / 32 * 32) * 2);
+  L.pf_ss = take(2 * 64 * SK_SS_STRIDE * 4);
   L.zeros = take(256);
   L.mk_layers = take((size_t)c.n_layers * sizeof(MkLayer));
   L.mk_bar = take((size_t)MK_BAR_WORDS * 4);
@@ -132,6 +139,7 @@ struct Instance {
   bool own_stream = false;
   hipGraph_t dec_graph = nullptr;
   hipGraphExec_t dec_exec = nullptr;
+  bool skinny = false;          // prompts of <= 64 tokens take the short-prompt kernels
   std::vector<int> pf_buckets;
   std::vector<hipGraph_t> pf_graph;
   std::vector<hipGraphExec_t> pf_exec;
@@ -383,7 +391,86 @@ void launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0, co
   else hipLaunchKernelGGL((pf_gemm_kernel<64, 3>), grid, dim3(LL_WG), PF_GEMM_LDS_BYTES(64, 3), s, ga);
 }
 
+int g_skinny_rb[3] = {2, 1, 4};   // row blocks per workgroup for SK_QKV, SK_RES, SK_GATEUP
+
+template <int MODE, int RB>
+void launch_skinny_rb(hipStream_t s, const SkinnyArgs& a, int Mb) {
+  const int units = skinny_units(MODE, a.N);
+  dim3 grid((units + RB - 1) / RB), block(SK_THREADS);
+  if (Mb == 16) hipLaunchKernelGGL((pf_skinny_kernel<MODE, 1, RB>), grid, block, 0, s, a);
+  else if (Mb == 32) hipLaunchKernelGGL((pf_skinny_kernel<MODE, 2, RB>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((pf_skinny_kernel<MODE, 4, RB>), grid, block, 0, s, a);
+}
+
+int g_skinny_persist = 1;
+int g_num_cus = 256;
+
+template <int MODE>
+void launch_skinny(hipStream_t s, const SkinnyArgs& a, int Mb) {
+  if constexpr (MODE != SK_RES) {
+    const int per_wave = (((a.K + 31) >> 5) + SK_WAVES - 1) / SK_WAVES;
+    if (g_skinny_persist && Mb <= 32 && per_wave <= SKP_KSTEPS) {
+      const int units = skinny_units(MODE, a.N);
+      dim3 grid(units < g_num_cus ? units : g_num_cus), block(SK_THREADS);
+      if (Mb == 16) hipLaunchKernelGGL((pf_skinny_persist_kernel<MODE, 1>), grid, block, 0, s, a);
+      else hipLaunchKernelGGL((pf_skinny_persist_kernel<MODE, 2>), grid, block, 0, s, a);
+      return;
+    }
+  }
+  switch (g_skinny_rb[MODE]) {
+    case 4: return launch_skinny_rb<MODE, 4>(s, a, Mb);
+    case 2: return launch_skinny_rb<MODE, 2>(s, a, Mb);
+    default: return launch_skinny_rb<MODE, 1>(s, a, Mb);
+  }
+}
+
+// Prompts of at most 64 tokens: five kernels per layer, every projection streams its weights
+// once and finishes its own epilogue; the norms ride on the projections around them.
+void enqueue_prefill_skinny(Instance* I, hipStream_t s, int Mb) {
+  const ll_config& c = I->cfg;
+  const int d = c.d_model, F = c.ffn_hidden;
+  float* X = I->at<float>(I->L.pf_x);
+  half_t* Xn = I->at<half_t>(I->L.pf_xn);
+  half_t* Qh = I->at<half_t>(I->L.pf_q);
+  half_t* Oh = I->at<half_t>(I->L.pf_o);
+  half_t* Hm = I->at<half_t>(I->L.pf_h);
+  float* ss_attn = I->at<float>(I->L.pf_ss);      // sum of squares in front of the attention block
+  float* ss_ffn = ss_attn + 64 * SK_SS_STRIDE;                  // ... and in front of the FFN
+  const int tb = Mb / 16;       // token blocks: the activations' fragment-major layout depends on it
+  hipLaunchKernelGGL(pf_embed_norm_kernel, dim3(Mb), dim3(LL_WG), 0, s, (const half_t*)I->w.tok_emb,
+                     I->at<int>(I->L.tokens), I->state(), (const half_t*)I->layers[0].attn_norm, X, Xn,
+                     ss_attn, ss_ffn, d, tb);
+  for (int l = 0; l < c.n_layers; ++l) {
+    const ll_layer_weights& W = I->layers[l];
+    SkinnyArgs a{};
+    a.st = I->state(); a.head_dim = c.head_dim; a.max_seq = c.max_seq; a.eps = c.rms_eps;
+    a.X = Xn; a.W[0] = (const half_t*)W.wq; a.W[1] = (const half_t*)W.wk; a.W[2] = (const half_t*)W.wv;
+    a.N = d; a.K = d; a.Q = Qh; a.kc = I->kcache(l); a.vc = I->vcache(l); a.rope = I->at<float2>(I->L.rope);
+    a.ss_in = ss_attn;
+    launch_skinny<SK_QKV>(s, a, Mb);
+    dim3 agrid(c.n_heads, 1);
+    if (c.head_dim == 128)
+      hipLaunchKernelGGL(pf_attn_kernel<128>, agrid, dim3(128), 0, s, Qh, I->kcache(l),
+                         I->vcache(l), I->state(), Oh, d, c.max_seq, tb);
+    else
+      hipLaunchKernelGGL(pf_attn_kernel<64>, agrid, dim3(128), 0, s, Qh, I->kcache(l),
+                         I->vcache(l), I->state(), Oh, d, c.max_seq, tb);
+    a.X = Oh; a.W[0] = (const half_t*)W.wo; a.W[1] = a.W[2] = nullptr; a.N = d; a.K = d; a.Xres = X;
+    a.gain_next = (const half_t*)W.ffn_norm; a.Xh_next = Xn; a.ss_out = ss_ffn; a.ss_zero = ss_attn;
+    launch_skinny<SK_RES>(s, a, Mb);
+    a.X = Xn; a.W[0] = (const half_t*)W.w_gate; a.W[1] = (const half_t*)W.w_up; a.N = F; a.K = d; a.Hout = Hm;
+    a.ss_in = ss_ffn;
+    launch_skinny<SK_GATEUP>(s, a, Mb);
+    a.X = Hm; a.W[0] = (const half_t*)W.w_down; a.W[1] = nullptr; a.N = d; a.K = F; a.Xres = X;
+    a.gain_next = l + 1 < c.n_layers ? (const half_t*)I->layers[l + 1].attn_norm : nullptr;
+    a.Xh_next = Xn; a.ss_out = ss_attn; a.ss_zero = ss_ffn;
+    launch_skinny<SK_RES>(s, a, Mb);
+  }
+  enqueue_head(I, s, X, 1, 1);
+}
+
 void enqueue_prefill(Instance* I, hipStream_t s, int Mb) {
+  if (Mb <= 64 && I->skinny) return enqueue_prefill_skinny(I, s, Mb);
   const ll_config& c = I->cfg;
   const int d = c.d_model, F = c.ffn_hidden;
   float* X = I->at<float>(I->L.pf_x);
@@ -398,7 +485,7 @@ void enqueue_prefill(Instance* I, hipStream_t s, int Mb) {
   for (int l = 0; l < c.n_layers; ++l) {
     const ll_layer_weights& W = I->layers[l];
     hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(LL_WG), 0, s, X, (const half_t*)W.attn_norm,
-                       Xn, d, c.rms_eps, QKV, 3 * d);
+                       Xn, d, c.rms_eps, QKV, 3 * d, 0);
     launch_gemm(I, s, Xn, W.wq, W.wk, W.wv, 3, QKV, 3 * d, d, d, Mb);
     hipLaunchKernelGGL(pf_rope_kv_kernel, dim3(Mb), dim3(LL_WG), 0, s, QKV,
                        I->at<float2>(I->L.rope), I->state(), Qh, I->kcache(l), I->vcache(l), d,
@@ -406,13 +493,13 @@ void enqueue_prefill(Instance* I, hipStream_t s, int Mb) {
     dim3 agrid(c.n_heads, Mb / 64);
     if (c.head_dim == 128)
       hipLaunchKernelGGL(pf_attn_kernel<128>, agrid, dim3(128), 0, s, Qh, I->kcache(l),
-                         I->vcache(l), I->state(), Oh, d, c.max_seq);
+                         I->vcache(l), I->state(), Oh, d, c.max_seq, 0);
     else
       hipLaunchKernelGGL(pf_attn_kernel<64>, agrid, dim3(128), 0, s, Qh, I->kcache(l),
-                         I->vcache(l), I->state(), Oh, d, c.max_seq);
+                         I->vcache(l), I->state(), Oh, d, c.max_seq, 0);
     launch_gemm(I, s, Oh, W.wo, nullptr, nullptr, 1, X, d, d, d, Mb);
     hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(LL_WG), 0, s, X, (const half_t*)W.ffn_norm,
-                       Xn, d, c.rms_eps, GU, 2 * F);
+                       Xn, d, c.rms_eps, GU, 2 * F, 0);
     launch_gemm(I, s, Xn, W.w_gate, W.w_up, nullptr, 2, GU, 2 * F, F, d, Mb);
     hipLaunchKernelGGL(pf_swiglu_kernel, dim3(Mb, (F + LL_WG * 4 - 1) / (LL_WG * 4)), dim3(LL_WG), 0,
                        s, GU, I->state(), Hm, F);
@@ -575,7 +662,18 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   }
   if (!hip_or_bail(hipDeviceSynchronize(), "hipDeviceSynchronize")) return bail(rc);
 
-  for (int b = 64; b <= L.mb_max; b <<= 1) I->pf_buckets.push_back(b);
+  I->skinny = skinny_ok(*cfg);
+  if (const char* e = getenv("LL_SKINNY")) I->skinny = I->skinny && atoi(e) != 0;
+  if (const char* e = getenv("LL_SKINNY_PERSIST")) g_skinny_persist = atoi(e);
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      g_num_cus = cus;
+  }
+  if (const char* e = getenv("LL_SKINNY_RB"))
+    for (int i = 0; i < 3 && e[i]; ++i) g_skinny_rb[i] = e[i] - '0';
+  for (int b = I->skinny ? 16 : 64; b <= L.mb_max; b <<= 1) I->pf_buckets.push_back(b);
 
   // Warm-up: one eager pass of every kernel chain (loads the code objects, so
   // nothing is compiled or loaded inside a capture), on state that is reset
@@ -648,7 +746,7 @@ int32_t ll_prefill(const int32_t* tokens, int32_t n) {
     if (tokens[i] < 0 || tokens[i] >= I->cfg.vocab)
       return fail(LL_E_BAD_ARG, "ll_prefill: tokens[%d] = %d outside [0, %d)", i, tokens[i], I->cfg.vocab);
 
-  const int Mb = prompt_bucket(n);
+  const int Mb = (I->skinny && n <= 32) ? (n <= 16 ? 16 : 32) : prompt_bucket(n);
   // prompt ids and the state block travel in one pinned staging buffer
   DevState* hs = reinterpret_cast<DevState*>(I->host_stage);
   int* htok = reinterpret_cast<int*>(reinterpret_cast<char*>(I->host_stage) + sizeof(DevState));

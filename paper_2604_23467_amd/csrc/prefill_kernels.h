@@ -32,12 +32,13 @@ __global__ __launch_bounds__(LL_WG) void pf_embed_kernel(const half_t* __restric
 
 // Row-wise RMSNorm of the fp32 residual stream into fp16 GEMM operands, one
 // workgroup per row.  As a side job each workgroup clears its row of the fp32
-// buffer the following split-K GEMM accumulates into.
+// buffer the following split-K GEMM accumulates into.  frag_tb != 0 writes the
+// operands in the short-prompt kernels' fragment-major layout.
 __global__ __launch_bounds__(LL_WG) void pf_rmsnorm_kernel(const float* __restrict__ X,
                                                            const half_t* __restrict__ gain,
                                                            half_t* __restrict__ Xn, int d, float eps,
                                                            float* __restrict__ zero_buf,
-                                                           int zero_row_floats) {
+                                                           int zero_row_floats, int frag_tb) {
   __shared__ float red[LL_WG / 64];
   const int r = blockIdx.x, tid = threadIdx.x;
   const float* xr = X + (size_t)r * d;
@@ -56,7 +57,7 @@ __global__ __launch_bounds__(LL_WG) void pf_rmsnorm_kernel(const float* __restri
     h4 o;
 #pragma unroll
     for (int j = 0; j < 4; ++j) o[j] = (half_t)(v[j] * inv * (float)g[j]);
-    *reinterpret_cast<h4*>(Xn + (size_t)r * d + i) = o;
+    *reinterpret_cast<h4*>(Xn + act_offset(r, i, d, frag_tb)) = o;
   }
   float* z = zero_buf + (size_t)r * zero_row_floats;
   const f4 zero = {0.f, 0.f, 0.f, 0.f};
@@ -287,7 +288,8 @@ __global__ __launch_bounds__(128) void pf_attn_kernel(const half_t* __restrict__
                                                       const half_t* __restrict__ kc,
                                                       const half_t* __restrict__ vc,
                                                       const DevState* __restrict__ st,
-                                                      half_t* __restrict__ O, int d, int max_seq) {
+                                                      half_t* __restrict__ O, int d, int max_seq,
+                                                      int frag_tb) {
   constexpr int QB = 64, TK = 32, KS = HD / 16, DT = HD / 32, CPR = HD / 8;
   constexpr int K_STRIDE = HD + 8;   // halves: 16-byte fragment reads of 8 rows hit 8 distinct bank groups
   constexpr int V_STRIDE = 40;       // halves per d row of V^T (32 keys + pad)
@@ -378,7 +380,6 @@ __global__ __launch_bounds__(128) void pf_attn_kernel(const half_t* __restrict__
 
   if (qi < n) {
     const float rl = 1.0f / l;
-    half_t* op = O + (size_t)qi * d + h * HD;
 #pragma unroll
     for (int t = 0; t < DT; ++t)
 #pragma unroll
@@ -386,7 +387,7 @@ __global__ __launch_bounds__(128) void pf_attn_kernel(const half_t* __restrict__
         h4 o;
 #pragma unroll
         for (int j = 0; j < 4; ++j) o[j] = (half_t)(acc[t][g4 * 4 + j] * rl);
-        *reinterpret_cast<h4*>(op + t * 32 + g4 * 8 + hf * 4) = o;
+        *reinterpret_cast<h4*>(O + act_offset(qi, h * HD + t * 32 + g4 * 8 + hf * 4, d, frag_tb)) = o;
       }
   }
 }

@@ -1,0 +1,418 @@
+// Projections of a SHORT prompt (at most 64 rows) for gfx950: the TTFT regime's
+// low end (10-50 tokens, Sec. IV-E / Table I), where the layer is bound by
+// streaming its weights once, exactly like a decode step, and a square-tiled
+// GEMM wastes most of its tile.
+//
+// One workgroup of 8 waves owns RB blocks of 16 output rows over the WHOLE of K,
+// so nothing is accumulated across workgroups: no split-K atomics, no zeroing,
+// and the epilogue of the layer (RoPE + KV-cache write, SwiGLU, residual add)
+// runs on the finished sums inside the same kernel, as in the decode GEMVs.
+//
+//  * The weights never touch LDS.  v_mfma_f32_16x16x32_f16 takes, per lane, 8
+//    consecutive k of one row (row = lane % 16, k = 8 * (lane / 16) ..), which is
+//    exactly a 16-byte streaming load from that weight row: a wave's load
+//    covers 16 rows x 64 contiguous bytes and goes straight into the A operand.
+//  * The activations (B operand, 16 tokens per block, TB blocks) are at most
+//    64 x K and stay in L2.  Their producers store them fragment-major
+//    (act_offset), so a B fragment is one contiguous 1 KB load; read row-major
+//    with the weights' addressing, the 16 rows of a fragment sit a power of two
+//    apart and pile onto one L2 channel (measured: 53 us per layer and token block).
+//  * The 8 waves split K into 8 contiguous ranges; their partial 16 x 16 tiles
+//    meet in LDS, and the epilogue threads sum the 8 partials.
+//
+// Row blocks are chosen so that the epilogue's partners share a block: a
+// q/k block holds rows j..j+7 and j+hd/2..j+hd/2+7 of one head (the RoPE
+// pairs), a gate/up block holds gate rows r..r+7 and up rows r..r+7.
+//
+// RMSNorm costs no kernel of its own.  The kernel that finishes a residual
+// update (SK_RES, or the embedding gather for layer 0) also stores the fp16
+// operand x * gain of the NEXT projection and adds each token's sum of squares
+// into a small buffer; the consuming projection (SK_QKV / SK_GATEUP) multiplies
+// its finished sums by rsqrt(mean x^2 + eps), which commutes with the
+// contraction: W (x g) s = s W (x g).
+#pragma once
+#include "ll_device.h"
+
+enum SkinnyMode { SK_QKV = 0, SK_RES = 1, SK_GATEUP = 2 };
+
+struct SkinnyArgs {
+  const half_t* X;        // 16 TB token rows x K fp16 activations, fragment-major; rows >= n hold anything
+  const half_t* W[3];     // [N][K] fp16 each (QKV: q, k, v; GATEUP: gate, up; RES: one matrix)
+  const DevState* st;
+  int N, K;
+  float* Xres;            // RES: residual stream [rows][N] fp32, updated in place for rows < n
+  const half_t* gain_next;// RES: gain of the norm in front of the next projection (null: none follows)
+  half_t* Xh_next;        // RES: fp16 x * gain_next, fragment-major, operand of the next projection
+  float* ss_out;          // RES: [16 TB] per-token sum of squares of the updated residual (atomic adds)
+  float* ss_zero;         // RES: [16 TB] buffer to clear for the projection after the next
+  const float* ss_in;     // QKV / GATEUP: per-token sum of squares of the operand's source
+  float eps;
+  half_t* Hout;           // GATEUP: 16 TB rows x N fp16, fragment-major
+  half_t* Q;              // QKV: [rows][N] fp16 rotated queries
+  half_t* kc;             // QKV: this layer's K cache [head][max_seq][head_dim]
+  half_t* vc;
+  const float2* rope;     // [max_seq][head_dim / 2] (cos, sin)
+  int head_dim, max_seq;
+};
+
+#define SK_WAVES 8
+#define SK_THREADS (SK_WAVES * 64)
+#define SK_PSTRIDE 20      // floats per (wave, token) row of partials: 16 + pad, keeps 16-byte alignment
+#define SK_SS_STRIDE 64    // floats between two tokens' sums of squares: one L2 channel each for the atomics
+
+// number of 16-row blocks the kernel's grid has to cover
+__host__ __device__ inline int skinny_units(int mode, int N) {
+  return mode == SK_QKV ? 3 * (N / 16) : mode == SK_GATEUP ? N / 8 : N / 16;
+}
+
+template <int MODE, int TB, int RB>
+__global__ __launch_bounds__(SK_THREADS) void pf_skinny_kernel(SkinnyArgs a) {
+  __shared__ __attribute__((aligned(16))) float part[SK_WAVES * RB * TB * 16 * SK_PSTRIDE];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r = lane & 15, g = lane >> 4;
+  const int K = a.K, N = a.N;
+  const int n = a.st->n_prompt;
+  const int units = skinny_units(MODE, N);
+  const int hh = a.head_dim >> 1;
+
+  // weight row this lane streams for each of the workgroup's row blocks
+  const half_t* wrow[RB];
+#pragma unroll
+  for (int b = 0; b < RB; ++b) {
+    const int u = min((int)blockIdx.x * RB + b, units - 1);   // a block past the end repeats the last one, unwritten
+    if (MODE == SK_RES) {
+      wrow[b] = a.W[0] + (size_t)(u * 16 + r) * K;
+    } else if (MODE == SK_GATEUP) {
+      wrow[b] = a.W[r >> 3] + (size_t)(u * 8 + (r & 7)) * K;
+    } else {
+      const int per = N / 16, z = u / per, v = u - z * per;
+      int row;
+      if (z == 2) {
+        row = v * 16 + r;
+      } else {
+        const int bph = hh / 8, head = v / bph, j0 = (v - head * bph) * 8;
+        row = head * a.head_dim + j0 + (r & 7) + (r >> 3) * hh;
+      }
+      wrow[b] = a.W[z] + (size_t)row * K;
+    }
+  }
+  const half_t* xfrag = a.X + lane * 8;   // fragment (s, t) starts at ((s * TB + t) * 64 + lane) * 8
+
+  f4 acc[RB][TB];
+#pragma unroll
+  for (int b = 0; b < RB; ++b)
+#pragma unroll
+    for (int t = 0; t < TB; ++t) acc[b][t] = f4{0.f, 0.f, 0.f, 0.f};
+
+  // K range of this wave, in 32-wide MFMA steps
+  const int ksteps = (K + 31) >> 5;
+  const int per_wave = (ksteps + SK_WAVES - 1) / SK_WAVES;
+  const int s_begin = wave * per_wave, s_end = min(s_begin + per_wave, ksteps);
+  constexpr int U = (RB * TB >= 4) ? 4 : 8;      // k-steps whose loads are issued together
+  const h8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int s0 = s_begin; s0 < s_end; s0 += U) {
+    h8 fa[U][RB], fb[U][TB];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int k = (s0 + u) * 32 + g * 8;
+      const bool in = (s0 + u < s_end) && (k < K);   // K % 8 == 0: 8 halves are all in or all out
+#pragma unroll
+      for (int b = 0; b < RB; ++b) fa[u][b] = in ? load_stream(wrow[b] + k) : zero;
+#pragma unroll
+      for (int t = 0; t < TB; ++t) fb[u][t] = in ? load_h8(xfrag + (size_t)((s0 + u) * TB + t) * 512) : zero;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int b = 0; b < RB; ++b)
+#pragma unroll
+        for (int t = 0; t < TB; ++t)
+          acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[u][b], fb[u][t], acc[b][t], 0, 0, 0);
+  }
+
+  // accumulator layout of the 16x16 MFMA: lane holds token column (lane % 16) and weight
+  // rows 4 * (lane / 16) + 0..3; partials are stored as part[wave][block][token][row]
+#pragma unroll
+  for (int b = 0; b < RB; ++b)
+#pragma unroll
+    for (int t = 0; t < TB; ++t)
+      *reinterpret_cast<f4*>(part + (((wave * RB + b) * TB + t) * 16 + r) * SK_PSTRIDE + g * 4) = acc[b][t];
+  __syncthreads();
+
+  // Epilogue: one thread finishes 8 consecutive rows of one token (16-byte stores throughout).
+  // sum8(b, tok, h): rows 8h..8h+7 of block b for token tok, summed over the 8 waves' partials
+  auto sum8 = [&](int b, int tok, int h, float (&v)[8]) {
+    f4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0;
+#pragma unroll
+    for (int w = 0; w < SK_WAVES; ++w) {
+      const float* pp = part + (((w * RB + b) * TB) * 16 + tok) * SK_PSTRIDE + h * 8;
+      s0 += *reinterpret_cast<const f4*>(pp);
+      s1 += *reinterpret_cast<const f4*>(pp + 4);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { v[j] = s0[j]; v[4 + j] = s1[j]; }
+  };
+
+  if (MODE == SK_RES) {
+    for (int o = tid; o < RB * TB * 32; o += SK_THREADS) {
+      const int h = o & 1, tok = (o >> 1) % (TB * 16), b = o / (TB * 32);
+      const int u = blockIdx.x * RB + b;
+      const bool live = u < units && tok < n;      // the same for both halves of a token
+      float ss = 0.f;
+      if (live) {
+        float v[8];
+        sum8(b, tok, h, v);
+        const int c0 = u * 16 + h * 8;
+        float* xp = a.Xres + (size_t)tok * N + c0;
+        const f4 x0 = *reinterpret_cast<const f4*>(xp), x1 = *reinterpret_cast<const f4*>(xp + 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { v[j] += x0[j]; v[4 + j] += x1[j]; }
+        *reinterpret_cast<f4*>(xp) = f4{v[0], v[1], v[2], v[3]};
+        *reinterpret_cast<f4*>(xp + 4) = f4{v[4], v[5], v[6], v[7]};
+        if (a.gain_next) {
+          const h8 gn = load_h8(a.gain_next + c0);
+          h8 xh;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            xh[j] = (half_t)(v[j] * (float)gn[j]);
+            ss += v[j] * v[j];
+          }
+          *reinterpret_cast<h8*>(a.Xh_next + act_offset(tok, c0, N, TB)) = xh;
+        }
+      }
+      ss += dpp_mov<0xB1>(ss);                     // the token's other half sits in the neighbouring lane
+      if (live && h == 0 && a.gain_next) unsafeAtomicAdd(a.ss_out + tok * SK_SS_STRIDE, ss);
+    }
+    if (blockIdx.x == 0 && tid < TB * 16 && a.ss_zero) a.ss_zero[tid * SK_SS_STRIDE] = 0.f;
+  } else {
+    for (int o = tid; o < RB * TB * 16; o += SK_THREADS) {
+      const int tok = o % (TB * 16), b = o / (TB * 16);
+      const int u = blockIdx.x * RB + b;
+      if (u >= units || tok >= n) continue;
+      const float rs = 1.0f / sqrtf(a.ss_in[tok * SK_SS_STRIDE] / (float)K + a.eps);
+      float lo[8], hi[8];
+      sum8(b, tok, 0, lo);
+      sum8(b, tok, 1, hi);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { lo[j] *= rs; hi[j] *= rs; }
+      h8 o0, o1;
+      if (MODE == SK_GATEUP) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o0[j] = (half_t)(lo[j] / (1.0f + expf(-lo[j])) * hi[j]);
+        *reinterpret_cast<h8*>(a.Hout + act_offset(tok, u * 8, N, TB)) = o0;
+      } else {
+        const int per = N / 16, z = u / per, v = u - z * per;
+        if (z == 2) {
+          const int c0 = v * 16, head = c0 / a.head_dim, e = c0 - head * a.head_dim;   // 16 rows of one head
+#pragma unroll
+          for (int j = 0; j < 8; ++j) { o0[j] = (half_t)lo[j]; o1[j] = (half_t)hi[j]; }
+          half_t* vr = a.vc + ((size_t)head * a.max_seq + tok) * a.head_dim + e;
+          *reinterpret_cast<h8*>(vr) = o0;
+          *reinterpret_cast<h8*>(vr + 8) = o1;
+        } else {
+          const int bph = hh / 8, head = v / bph, j0 = (v - head * bph) * 8;
+          const float2* cs = a.rope + (size_t)tok * hh + j0;   // prompt row tok sits at position tok
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float2 t2 = cs[j];
+            o0[j] = (half_t)(lo[j] * t2.x - hi[j] * t2.y);
+            o1[j] = (half_t)(hi[j] * t2.x + lo[j] * t2.y);
+          }
+          half_t* dst = z == 0 ? a.Q + (size_t)tok * N + head * a.head_dim
+                               : a.kc + ((size_t)head * a.max_seq + tok) * a.head_dim;
+          *reinterpret_cast<h8*>(dst + j0) = o0;
+          *reinterpret_cast<h8*>(dst + j0 + hh) = o1;
+        }
+      }
+    }
+  }
+}
+
+// Persistent form of the two wide projections (SK_QKV, SK_GATEUP) for K <= 4096 and at most 32
+// tokens: one workgroup per CU walks row blocks u = blockIdx.x, + gridDim.x, ...  A wave keeps
+// the same K range for every block, so its B fragments (16 K steps x TB) are loaded ONCE into
+// registers and the activations cause no further traffic; and the first half of the next
+// block's weights is requested before the current block's partials are exchanged, so the
+// weight stream never drains while a block is being finished.  The finishing (8 partials ->
+// epilogue) rotates over the waves, one block each; partials are double-buffered in LDS so a
+// single barrier per block orders writers and the finishing wave.
+#define SKP_KSTEPS 16     // K steps per wave held in registers: K <= 8 waves * 16 * 32
+template <int MODE, int TB>
+__global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(SkinnyArgs a) {
+  static_assert(MODE != SK_RES, "wide projections only");
+  __shared__ __attribute__((aligned(16))) float part[2][SK_WAVES * TB * 16 * SK_PSTRIDE];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r = lane & 15, g = lane >> 4;
+  const int K = a.K, N = a.N;
+  const int n = a.st->n_prompt;
+  const int units = skinny_units(MODE, N);
+  const int hh = a.head_dim >> 1;
+  const int ksteps = (K + 31) >> 5;
+  const int per_wave = (ksteps + SK_WAVES - 1) / SK_WAVES;      // <= SKP_KSTEPS (host checked)
+  const int s_begin = wave * per_wave, s_end = min(s_begin + per_wave, ksteps);
+  const h8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+  constexpr int HALF = SKP_KSTEPS / 2;
+
+  bool in[SKP_KSTEPS];
+#pragma unroll
+  for (int i = 0; i < SKP_KSTEPS; ++i) in[i] = (s_begin + i < s_end) && ((s_begin + i) * 32 + g * 8 < K);
+
+  h8 fb[SKP_KSTEPS][TB];
+#pragma unroll
+  for (int i = 0; i < SKP_KSTEPS; ++i)
+#pragma unroll
+    for (int t = 0; t < TB; ++t)
+      fb[i][t] = in[i] ? load_h8(a.X + ((size_t)((s_begin + i) * TB + t) * 64 + lane) * 8) : zero;
+
+  // weight row of this lane in row block u
+  auto row_ptr = [&](int u) -> const half_t* {
+    if (MODE == SK_GATEUP) return a.W[r >> 3] + (size_t)(u * 8 + (r & 7)) * K;
+    const int per = N / 16, z = u / per, v = u - z * per;
+    int row;
+    if (z == 2) {
+      row = v * 16 + r;
+    } else {
+      const int bph = hh / 8, head = v / bph, j0 = (v - head * bph) * 8;
+      row = head * a.head_dim + j0 + (r & 7) + (r >> 3) * hh;
+    }
+    return a.W[z] + (size_t)row * K;
+  };
+  // element offset of K step i in a weight row; steps outside the wave's range re-read the row
+  // start instead (always valid memory) and meet a zero B fragment
+  int koff[SKP_KSTEPS];
+#pragma unroll
+  for (int i = 0; i < SKP_KSTEPS; ++i) koff[i] = in[i] ? (s_begin + i) * 32 + g * 8 : 0;
+
+  float rs = 0.f;                                   // the finishing lanes' token scale
+  if (lane < TB * 16 && lane < n) rs = 1.0f / sqrtf(a.ss_in[lane * SK_SS_STRIDE] / (float)K + a.eps);
+
+  int u = blockIdx.x;
+  h8 fa0[HALF], fa1[HALF];
+  if (u < units) {
+    const half_t* wp = row_ptr(u);
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) fa0[i] = load_h8(wp + koff[i]);
+  }
+  int round = 0;
+  for (; u < units; u += gridDim.x, ++round) {
+    {
+      const half_t* wp = row_ptr(u);
+#pragma unroll
+      for (int i = 0; i < HALF; ++i) fa1[i] = load_h8(wp + koff[HALF + i]);
+    }
+    f4 acc[TB];
+#pragma unroll
+    for (int t = 0; t < TB; ++t) acc[t] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < HALF; ++i)
+#pragma unroll
+      for (int t = 0; t < TB; ++t)
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa0[i], fb[i][t], acc[t], 0, 0, 0);
+    const int un = u + gridDim.x;
+    if (un < units) {
+      const half_t* wp = row_ptr(un);
+#pragma unroll
+      for (int i = 0; i < HALF; ++i) fa0[i] = load_h8(wp + koff[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < HALF; ++i)
+#pragma unroll
+      for (int t = 0; t < TB; ++t)
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa1[i], fb[HALF + i][t], acc[t], 0, 0, 0);
+
+    float* pb = part[round & 1];
+#pragma unroll
+    for (int t = 0; t < TB; ++t)
+      *reinterpret_cast<f4*>(pb + ((wave * TB + t) * 16 + r) * SK_PSTRIDE + g * 4) = acc[t];
+    // LDS writes done, then a bare barrier: a full __syncthreads() would also drain the weight loads in flight
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    if (wave == (round & (SK_WAVES - 1)) && lane < TB * 16 && lane < n) {
+      const int tok = lane;
+      const float scale = rs;                 // token = lane in every wave
+      f4 s[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+      for (int w = 0; w < SK_WAVES; ++w) {
+        const float* pp = pb + ((w * TB) * 16 + tok) * SK_PSTRIDE;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) s[q] += *reinterpret_cast<const f4*>(pp + q * 4);
+      }
+      float lo[8], hi[8];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        lo[j] = s[0][j] * scale; lo[4 + j] = s[1][j] * scale;
+        hi[j] = s[2][j] * scale; hi[4 + j] = s[3][j] * scale;
+      }
+      h8 o0, o1;
+      if (MODE == SK_GATEUP) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o0[j] = (half_t)(lo[j] / (1.0f + expf(-lo[j])) * hi[j]);
+        *reinterpret_cast<h8*>(a.Hout + act_offset(tok, u * 8, N, TB)) = o0;
+      } else {
+        const int per = N / 16, z = u / per, v = u - z * per;
+        if (z == 2) {
+          const int c0 = v * 16, head = c0 / a.head_dim, e = c0 - head * a.head_dim;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) { o0[j] = (half_t)lo[j]; o1[j] = (half_t)hi[j]; }
+          half_t* vr = a.vc + ((size_t)head * a.max_seq + tok) * a.head_dim + e;
+          *reinterpret_cast<h8*>(vr) = o0;
+          *reinterpret_cast<h8*>(vr + 8) = o1;
+        } else {
+          const int bph = hh / 8, head = v / bph, j0 = (v - head * bph) * 8;
+          const float2* cs = a.rope + (size_t)tok * hh + j0;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float2 t2 = cs[j];
+            o0[j] = (half_t)(lo[j] * t2.x - hi[j] * t2.y);
+            o1[j] = (half_t)(hi[j] * t2.x + lo[j] * t2.y);
+          }
+          half_t* dst = z == 0 ? a.Q + (size_t)tok * N + head * a.head_dim
+                               : a.kc + ((size_t)head * a.max_seq + tok) * a.head_dim;
+          *reinterpret_cast<h8*>(dst + j0) = o0;
+          *reinterpret_cast<h8*>(dst + j0 + hh) = o1;
+        }
+      }
+    }
+  }
+}
+
+// Layer-0 front end of the short-prompt path: X[r] = float(E[tokens[r]]) (zero for r >= n),
+// Xh = fp16 (x * gain) fragment-major, ss[r] = sum x^2; also clears the other sum buffer.
+// grid = 16 TB rows, one workgroup per row.
+__global__ __launch_bounds__(LL_WG) void pf_embed_norm_kernel(const half_t* __restrict__ emb,
+                                                              const int* __restrict__ tokens,
+                                                              const DevState* __restrict__ st,
+                                                              const half_t* __restrict__ gain,
+                                                              float* __restrict__ X, half_t* __restrict__ Xh,
+                                                              float* __restrict__ ss, float* __restrict__ ss_other,
+                                                              int d, int tb) {
+  __shared__ float red[LL_WG / 64];
+  const int r = blockIdx.x, tid = threadIdx.x;
+  const bool live = r < st->n_prompt;
+  const half_t* e = emb + (size_t)(live ? tokens[r] : 0) * d;
+  float acc = 0.f;
+  for (int i = tid * 8; i < d; i += LL_WG * 8) {
+    h8 v = load_h8(e + i);
+    const h8 gn = load_h8(gain + i);
+    h8 o;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float x = live ? (float)v[j] : 0.f;
+      X[(size_t)r * d + i + j] = x;
+      o[j] = (half_t)(x * (float)gn[j]);
+      acc += x * x;
+    }
+    *reinterpret_cast<h8*>(Xh + act_offset(r, i, d, tb)) = o;
+  }
+  acc = wave_sum(acc);
+  if ((tid & 63) == 0) red[tid >> 6] = acc;
+  __syncthreads();
+  if (tid == 0) {
+    ss[r * SK_SS_STRIDE] = red[0] + red[1] + red[2] + red[3];
+    ss_other[r * SK_SS_STRIDE] = 0.f;
+  }
+}

@@ -92,6 +92,24 @@ def test_shapes_tails_and_buckets(torch_cuda, oracle32, shape, flags):
     om.close()
 
 
+@pytest.mark.parametrize("flags", [0, 1], ids=["graph", "eager"])
+@pytest.mark.parametrize("n_prompt", [2, 15, 16, 17, 31, 32, 33, 50])
+def test_short_prompt_row_blocks(torch_cuda, oracle32, n_prompt, flags):
+    """Prompts around the 16 / 32 / 64-row boundaries of the short-prompt kernels, head_dim 128
+    and an FFN width whose K range ends inside an MFMA step; every K and V cache row is compared."""
+    cfg = wl.custom_cfg(2, 2, 128, 344, 300, 100)
+    w = wl.weights_astype(wl.make_weights_numpy(cfg, seed=31, gain_jitter=0.1), np.float16)
+    prompt = wl.make_tokens(n_prompt, cfg["vocab"], seed=100 + n_prompt)
+    om = oracle32.model(cfg, w)
+    with _session(cfg, w, flags) as s:
+        run_teacher_forced(s, om, prompt, 2, "short")
+        for layer in range(2):
+            for which in range(2):
+                got = s.ll_dbg_get_kv(layer, which, n_prompt + 2)
+                assert rel_l2(got, om.kv(layer, which)) < 3e-3, (layer, which)
+    om.close()
+
+
 def test_larger_activations_exercise_softmax_and_rope(torch_cuda, oracle32):
     """Weights scaled up so attention is far from uniform and RoPE matters."""
     cfg = wl.custom_cfg(2, 4, 64, 256, 300, 160)
