@@ -139,7 +139,7 @@ struct Instance {
   bool own_stream = false;
   hipGraph_t dec_graph = nullptr;
   hipGraphExec_t dec_exec = nullptr;
-  bool skinny = false;          // prompts of <= 64 tokens take the short-prompt kernels
+  bool skinny = false;          // prompts of <= 32 tokens take the short-prompt kernels
   std::vector<int> pf_buckets;
   std::vector<hipGraph_t> pf_graph;
   std::vector<hipGraphExec_t> pf_exec;
@@ -391,25 +391,14 @@ void launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0, co
   else hipLaunchKernelGGL((pf_gemm_kernel<64, 3>), grid, dim3(LL_WG), PF_GEMM_LDS_BYTES(64, 3), s, ga);
 }
 
-int g_skinny_rb[3] = {2, 1, 4};   // row blocks per workgroup for SK_QKV, SK_RES, SK_GATEUP
-
-template <int MODE, int RB>
-void launch_skinny_rb(hipStream_t s, const SkinnyArgs& a, int Mb) {
-  const int units = skinny_units(MODE, a.N);
-  dim3 grid((units + RB - 1) / RB), block(SK_THREADS);
-  if (Mb == 16) hipLaunchKernelGGL((pf_skinny_kernel<MODE, 1, RB>), grid, block, 0, s, a);
-  else if (Mb == 32) hipLaunchKernelGGL((pf_skinny_kernel<MODE, 2, RB>), grid, block, 0, s, a);
-  else hipLaunchKernelGGL((pf_skinny_kernel<MODE, 4, RB>), grid, block, 0, s, a);
-}
-
-int g_skinny_persist = 1;
 int g_num_cus = 256;
 
 template <int MODE>
-void launch_skinny(hipStream_t s, const SkinnyArgs& a, int Mb) {
+void launch_skinny(Instance* I, hipStream_t s, SkinnyArgs a, int Mb) {
+  a.zeros_off = I->at<half_t>(I->L.zeros) - a.X;
   if constexpr (MODE != SK_RES) {
     const int per_wave = (((a.K + 31) >> 5) + SK_WAVES - 1) / SK_WAVES;
-    if (g_skinny_persist && Mb <= 32 && per_wave <= SKP_KSTEPS) {
+    if (per_wave <= SKP_KSTEPS) {
       const int units = skinny_units(MODE, a.N);
       dim3 grid(units < g_num_cus ? units : g_num_cus), block(SK_THREADS);
       if (Mb == 16) hipLaunchKernelGGL((pf_skinny_persist_kernel<MODE, 1>), grid, block, 0, s, a);
@@ -417,14 +406,25 @@ void launch_skinny(hipStream_t s, const SkinnyArgs& a, int Mb) {
       return;
     }
   }
-  switch (g_skinny_rb[MODE]) {
-    case 4: return launch_skinny_rb<MODE, 4>(s, a, Mb);
-    case 2: return launch_skinny_rb<MODE, 2>(s, a, Mb);
-    default: return launch_skinny_rb<MODE, 1>(s, a, Mb);
+  dim3 grid(skinny_units(MODE, a.N)), block(SK_THREADS);
+  const int per_wave = (((a.K + 31) >> 5) + SK_WAVES - 1) / SK_WAVES, nb = (per_wave + 7) / 8;
+  if constexpr (MODE == SK_RES) {       // the 7B shapes get the unrolled pipelines: K = 4096 and K = 11008
+    if (nb == 2) {
+      if (Mb == 16) hipLaunchKernelGGL((pf_skinny_kernel<MODE, 1, 2>), grid, block, 0, s, a);
+      else hipLaunchKernelGGL((pf_skinny_kernel<MODE, 2, 2>), grid, block, 0, s, a);
+      return;
+    }
+    if (nb == 6) {
+      if (Mb == 16) hipLaunchKernelGGL((pf_skinny_kernel<MODE, 1, 6>), grid, block, 0, s, a);
+      else hipLaunchKernelGGL((pf_skinny_kernel<MODE, 2, 6>), grid, block, 0, s, a);
+      return;
+    }
   }
+  if (Mb == 16) hipLaunchKernelGGL((pf_skinny_kernel<MODE, 1, 0>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((pf_skinny_kernel<MODE, 2, 0>), grid, block, 0, s, a);
 }
 
-// Prompts of at most 64 tokens: five kernels per layer, every projection streams its weights
+// Prompts of at most 32 tokens: five kernels per layer, every projection streams its weights
 // once and finishes its own epilogue; the norms ride on the projections around them.
 void enqueue_prefill_skinny(Instance* I, hipStream_t s, int Mb) {
   const ll_config& c = I->cfg;
@@ -447,7 +447,7 @@ void enqueue_prefill_skinny(Instance* I, hipStream_t s, int Mb) {
     a.X = Xn; a.W[0] = (const half_t*)W.wq; a.W[1] = (const half_t*)W.wk; a.W[2] = (const half_t*)W.wv;
     a.N = d; a.K = d; a.Q = Qh; a.kc = I->kcache(l); a.vc = I->vcache(l); a.rope = I->at<float2>(I->L.rope);
     a.ss_in = ss_attn;
-    launch_skinny<SK_QKV>(s, a, Mb);
+    launch_skinny<SK_QKV>(I, s, a, Mb);
     dim3 agrid(c.n_heads, 1);
     if (c.head_dim == 128)
       hipLaunchKernelGGL(pf_attn_kernel<128>, agrid, dim3(128), 0, s, Qh, I->kcache(l),
@@ -457,20 +457,20 @@ void enqueue_prefill_skinny(Instance* I, hipStream_t s, int Mb) {
                          I->vcache(l), I->state(), Oh, d, c.max_seq, tb);
     a.X = Oh; a.W[0] = (const half_t*)W.wo; a.W[1] = a.W[2] = nullptr; a.N = d; a.K = d; a.Xres = X;
     a.gain_next = (const half_t*)W.ffn_norm; a.Xh_next = Xn; a.ss_out = ss_ffn; a.ss_zero = ss_attn;
-    launch_skinny<SK_RES>(s, a, Mb);
+    launch_skinny<SK_RES>(I, s, a, Mb);
     a.X = Xn; a.W[0] = (const half_t*)W.w_gate; a.W[1] = (const half_t*)W.w_up; a.N = F; a.K = d; a.Hout = Hm;
     a.ss_in = ss_ffn;
-    launch_skinny<SK_GATEUP>(s, a, Mb);
+    launch_skinny<SK_GATEUP>(I, s, a, Mb);
     a.X = Hm; a.W[0] = (const half_t*)W.w_down; a.W[1] = nullptr; a.N = d; a.K = F; a.Xres = X;
     a.gain_next = l + 1 < c.n_layers ? (const half_t*)I->layers[l + 1].attn_norm : nullptr;
     a.Xh_next = Xn; a.ss_out = ss_attn; a.ss_zero = ss_ffn;
-    launch_skinny<SK_RES>(s, a, Mb);
+    launch_skinny<SK_RES>(I, s, a, Mb);
   }
   enqueue_head(I, s, X, 1, 1);
 }
 
 void enqueue_prefill(Instance* I, hipStream_t s, int Mb) {
-  if (Mb <= 64 && I->skinny) return enqueue_prefill_skinny(I, s, Mb);
+  if (Mb <= 32 && I->skinny) return enqueue_prefill_skinny(I, s, Mb);
   const ll_config& c = I->cfg;
   const int d = c.d_model, F = c.ffn_hidden;
   float* X = I->at<float>(I->L.pf_x);
@@ -663,16 +663,12 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipDeviceSynchronize(), "hipDeviceSynchronize")) return bail(rc);
 
   I->skinny = skinny_ok(*cfg);
-  if (const char* e = getenv("LL_SKINNY")) I->skinny = I->skinny && atoi(e) != 0;
-  if (const char* e = getenv("LL_SKINNY_PERSIST")) g_skinny_persist = atoi(e);
   {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
       g_num_cus = cus;
   }
-  if (const char* e = getenv("LL_SKINNY_RB"))
-    for (int i = 0; i < 3 && e[i]; ++i) g_skinny_rb[i] = e[i] - '0';
   for (int b = I->skinny ? 16 : 64; b <= L.mb_max; b <<= 1) I->pf_buckets.push_back(b);
 
   // Warm-up: one eager pass of every kernel chain (loads the code objects, so

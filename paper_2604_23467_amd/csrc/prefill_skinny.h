@@ -3,7 +3,7 @@
 // streaming its weights once, exactly like a decode step, and a square-tiled
 // GEMM wastes most of its tile.
 //
-// One workgroup of 8 waves owns RB blocks of 16 output rows over the WHOLE of K,
+// One workgroup of 8 waves owns a block of 16 output rows over the WHOLE of K,
 // so nothing is accumulated across workgroups: no split-K atomics, no zeroing,
 // and the epilogue of the layer (RoPE + KV-cache write, SwiGLU, residual add)
 // runs on the finished sums inside the same kernel, as in the decode GEMVs.
@@ -52,6 +52,7 @@ struct SkinnyArgs {
   half_t* kc;             // QKV: this layer's K cache [head][max_seq][head_dim]
   half_t* vc;
   const float2* rope;     // [max_seq][head_dim / 2] (cos, sin)
+  long zeros_off;         // element offset from X of >= 16 bytes of zeros (same allocation as X)
   int head_dim, max_seq;
 };
 
@@ -65,9 +66,12 @@ __host__ __device__ inline int skinny_units(int mode, int N) {
   return mode == SK_QKV ? 3 * (N / 16) : mode == SK_GATEUP ? N / 8 : N / 16;
 }
 
-template <int MODE, int TB, int RB>
-__global__ __launch_bounds__(SK_THREADS) void pf_skinny_kernel(SkinnyArgs a) {
-  __shared__ __attribute__((aligned(16))) float part[SK_WAVES * RB * TB * 16 * SK_PSTRIDE];
+// NB > 0: the host promises ceil(K steps per wave / 8) == NB and the batch pipeline is unrolled
+// with exact wait counts; NB = 0 walks any K with a loop that over-fetches one batch.
+template <int MODE, int TB, int NB>
+__global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_kernel(SkinnyArgs a) {
+  constexpr int RB = 1;
+  __shared__ __attribute__((aligned(16))) float part[SK_WAVES * TB * 16 * SK_PSTRIDE];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 15, g = lane >> 4;
@@ -76,15 +80,14 @@ __global__ __launch_bounds__(SK_THREADS) void pf_skinny_kernel(SkinnyArgs a) {
   const int units = skinny_units(MODE, N);
   const int hh = a.head_dim >> 1;
 
-  // weight row this lane streams for each of the workgroup's row blocks
-  const half_t* wrow[RB];
-#pragma unroll
-  for (int b = 0; b < RB; ++b) {
-    const int u = min((int)blockIdx.x * RB + b, units - 1);   // a block past the end repeats the last one, unwritten
+  // weight row this lane streams
+  const half_t* wrow;
+  {
+    const int u = blockIdx.x;
     if (MODE == SK_RES) {
-      wrow[b] = a.W[0] + (size_t)(u * 16 + r) * K;
+      wrow = a.W[0] + (size_t)(u * 16 + r) * K;
     } else if (MODE == SK_GATEUP) {
-      wrow[b] = a.W[r >> 3] + (size_t)(u * 8 + (r & 7)) * K;
+      wrow = a.W[r >> 3] + (size_t)(u * 8 + (r & 7)) * K;
     } else {
       const int per = N / 16, z = u / per, v = u - z * per;
       int row;
@@ -94,51 +97,90 @@ __global__ __launch_bounds__(SK_THREADS) void pf_skinny_kernel(SkinnyArgs a) {
         const int bph = hh / 8, head = v / bph, j0 = (v - head * bph) * 8;
         row = head * a.head_dim + j0 + (r & 7) + (r >> 3) * hh;
       }
-      wrow[b] = a.W[z] + (size_t)row * K;
+      wrow = a.W[z] + (size_t)row * K;
     }
   }
-  const half_t* xfrag = a.X + lane * 8;   // fragment (s, t) starts at ((s * TB + t) * 64 + lane) * 8
 
-  f4 acc[RB][TB];
+  f4 acc[TB];
 #pragma unroll
-  for (int b = 0; b < RB; ++b)
-#pragma unroll
-    for (int t = 0; t < TB; ++t) acc[b][t] = f4{0.f, 0.f, 0.f, 0.f};
+  for (int t = 0; t < TB; ++t) acc[t] = f4{0.f, 0.f, 0.f, 0.f};
 
-  // K range of this wave, in 32-wide MFMA steps
+  // SK_RES: thread o < 32 TB finishes rows 8 (o & 1) .. + 8 of token o >> 1.  What it adds to
+  // (the residual) and scales by (the next norm's gain) does not depend on the contraction, so
+  // it is fetched now and has long arrived when the sums are ready.
+  f4 ex0 = {0.f, 0.f, 0.f, 0.f}, ex1 = ex0;
+  h8 egain = {0, 0, 0, 0, 0, 0, 0, 0};
+  const bool efin = MODE == SK_RES && tid < TB * 32 && (tid >> 1) < n;
+  if (MODE == SK_RES && efin) {
+    const int c0 = blockIdx.x * 16 + (tid & 1) * 8;
+    const float* xp = a.Xres + (size_t)(tid >> 1) * N + c0;
+    ex0 = *as_global(reinterpret_cast<const f4*>(xp));
+    ex1 = *as_global(reinterpret_cast<const f4*>(xp + 4));
+    if (a.gain_next) egain = load_h8(a.gain_next + c0);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+
+  // K range of this wave, in 32-wide MFMA steps, walked in batches of U steps.  Two batches
+  // of registers alternate, so a batch's loads are in flight while the previous one is
+  // multiplied.  A step outside the range (or a lane's 8 halves past K) re-reads the row
+  // start and takes its B fragment from a block of zeros: no load is ever predicated.
   const int ksteps = (K + 31) >> 5;
   const int per_wave = (ksteps + SK_WAVES - 1) / SK_WAVES;
   const int s_begin = wave * per_wave, s_end = min(s_begin + per_wave, ksteps);
-  constexpr int U = (RB * TB >= 4) ? 4 : 8;      // k-steps whose loads are issued together
-  const h8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int s0 = s_begin; s0 < s_end; s0 += U) {
-    h8 fa[U][RB], fb[U][TB];
+  constexpr int U = 8;
+  h8 fa[2][U], fb[2][U][TB];
+  auto issue = [&](int s0, h8 (&A)[U], h8 (&B)[U][TB]) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int k = (s0 + u) * 32 + g * 8;
-      const bool in = (s0 + u < s_end) && (k < K);   // K % 8 == 0: 8 halves are all in or all out
+    for (int i = 0; i < U; ++i) {
+      const int st = s0 + i, k = st * 32 + g * 8;
+      const bool in = st < s_end && k < K;           // K % 8 == 0: 8 halves are all in or all out
+      A[i] = load_h8(wrow + (in ? k : 0));
 #pragma unroll
-      for (int b = 0; b < RB; ++b) fa[u][b] = in ? load_stream(wrow[b] + k) : zero;
-#pragma unroll
-      for (int t = 0; t < TB; ++t) fb[u][t] = in ? load_h8(xfrag + (size_t)((s0 + u) * TB + t) * 512) : zero;
+      for (int t = 0; t < TB; ++t)
+        B[i][t] = load_h8(a.X + (in ? (long)(st * TB + t) * 512 + lane * 8 : a.zeros_off));
     }
+  };
+  auto multiply = [&](const h8 (&A)[U], const h8 (&B)[U][TB]) {
 #pragma unroll
-    for (int u = 0; u < U; ++u)
+    for (int i = 0; i < U; ++i)
 #pragma unroll
-      for (int b = 0; b < RB; ++b)
+      for (int t = 0; t < TB; ++t)
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[i], B[i][t], acc[t], 0, 0, 0);
+  };
+  // The scheduling fences keep each batch's loads together and ahead of the other batch's
+  // MFMAs; left alone the compiler sinks every load next to its use to save registers, which
+  // serialises the memory latency.
+  issue(s_begin, fa[0], fb[0]);
+  if constexpr (NB > 0) {
 #pragma unroll
-        for (int t = 0; t < TB; ++t)
-          acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[u][b], fb[u][t], acc[b][t], 0, 0, 0);
+    for (int b = 0; b < NB; ++b) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (b + 1 < NB) issue(s_begin + (b + 1) * U, fa[(b + 1) & 1], fb[(b + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(fa[b & 1], fb[b & 1]);
+    }
+  } else {
+    for (int s0 = s_begin; s0 < s_end; s0 += 2 * U) {
+      __builtin_amdgcn_sched_barrier(0);
+      issue(s0 + U, fa[1], fb[1]);        // unconditional: past the range these are cache hits on the row start
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(fa[0], fb[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      issue(s0 + 2 * U, fa[0], fb[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(fa[1], fb[1]);
+    }
   }
 
   // accumulator layout of the 16x16 MFMA: lane holds token column (lane % 16) and weight
-  // rows 4 * (lane / 16) + 0..3; partials are stored as part[wave][block][token][row]
+  // rows 4 * (lane / 16) + 0..3; partials are stored as part[wave][token][row]
 #pragma unroll
-  for (int b = 0; b < RB; ++b)
-#pragma unroll
-    for (int t = 0; t < TB; ++t)
-      *reinterpret_cast<f4*>(part + (((wave * RB + b) * TB + t) * 16 + r) * SK_PSTRIDE + g * 4) = acc[b][t];
-  __syncthreads();
+  for (int t = 0; t < TB; ++t)
+    *reinterpret_cast<f4*>(part + ((wave * TB + t) * 16 + r) * SK_PSTRIDE + g * 4) = acc[t];
+  // bare barrier: the look-ahead loads of the last round are still in flight and nobody needs them
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
 
   // Epilogue: one thread finishes 8 consecutive rows of one token (16-byte stores throughout).
   // sum8(b, tok, h): rows 8h..8h+7 of block b for token tok, summed over the 8 waves' partials
@@ -155,34 +197,30 @@ __global__ __launch_bounds__(SK_THREADS) void pf_skinny_kernel(SkinnyArgs a) {
   };
 
   if (MODE == SK_RES) {
-    for (int o = tid; o < RB * TB * 32; o += SK_THREADS) {
-      const int h = o & 1, tok = (o >> 1) % (TB * 16), b = o / (TB * 32);
-      const int u = blockIdx.x * RB + b;
-      const bool live = u < units && tok < n;      // the same for both halves of a token
-      float ss = 0.f;
-      if (live) {
-        float v[8];
-        sum8(b, tok, h, v);
-        const int c0 = u * 16 + h * 8;
-        float* xp = a.Xres + (size_t)tok * N + c0;
-        const f4 x0 = *reinterpret_cast<const f4*>(xp), x1 = *reinterpret_cast<const f4*>(xp + 4);
+    float ss = 0.f;
+    if (efin) {
+      const int h = tid & 1, tok = tid >> 1;
+      float v[8];
+      sum8(0, tok, h, v);
+      const int c0 = blockIdx.x * 16 + h * 8;
+      float* xp = a.Xres + (size_t)tok * N + c0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { v[j] += x0[j]; v[4 + j] += x1[j]; }
-        *reinterpret_cast<f4*>(xp) = f4{v[0], v[1], v[2], v[3]};
-        *reinterpret_cast<f4*>(xp + 4) = f4{v[4], v[5], v[6], v[7]};
-        if (a.gain_next) {
-          const h8 gn = load_h8(a.gain_next + c0);
-          h8 xh;
+      for (int j = 0; j < 4; ++j) { v[j] += ex0[j]; v[4 + j] += ex1[j]; }
+      *reinterpret_cast<f4*>(xp) = f4{v[0], v[1], v[2], v[3]};
+      *reinterpret_cast<f4*>(xp + 4) = f4{v[4], v[5], v[6], v[7]};
+      if (a.gain_next) {
+        h8 xh;
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            xh[j] = (half_t)(v[j] * (float)gn[j]);
-            ss += v[j] * v[j];
-          }
-          *reinterpret_cast<h8*>(a.Xh_next + act_offset(tok, c0, N, TB)) = xh;
+        for (int j = 0; j < 8; ++j) {
+          xh[j] = (half_t)(v[j] * (float)egain[j]);
+          ss += v[j] * v[j];
         }
+        *reinterpret_cast<h8*>(a.Xh_next + act_offset(tok, c0, N, TB)) = xh;
       }
+    }
+    if (tid < TB * 32) {
       ss += dpp_mov<0xB1>(ss);                     // the token's other half sits in the neighbouring lane
-      if (live && h == 0 && a.gain_next) unsafeAtomicAdd(a.ss_out + tok * SK_SS_STRIDE, ss);
+      if (efin && (tid & 1) == 0 && a.gain_next) unsafeAtomicAdd(a.ss_out + (tid >> 1) * SK_SS_STRIDE, ss);
     }
     if (blockIdx.x == 0 && tid < TB * 16 && a.ss_zero) a.ss_zero[tid * SK_SS_STRIDE] = 0.f;
   } else {
@@ -252,19 +290,11 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
   const int ksteps = (K + 31) >> 5;
   const int per_wave = (ksteps + SK_WAVES - 1) / SK_WAVES;      // <= SKP_KSTEPS (host checked)
   const int s_begin = wave * per_wave, s_end = min(s_begin + per_wave, ksteps);
-  const h8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
   constexpr int HALF = SKP_KSTEPS / 2;
 
   bool in[SKP_KSTEPS];
 #pragma unroll
   for (int i = 0; i < SKP_KSTEPS; ++i) in[i] = (s_begin + i < s_end) && ((s_begin + i) * 32 + g * 8 < K);
-
-  h8 fb[SKP_KSTEPS][TB];
-#pragma unroll
-  for (int i = 0; i < SKP_KSTEPS; ++i)
-#pragma unroll
-    for (int t = 0; t < TB; ++t)
-      fb[i][t] = in[i] ? load_h8(a.X + ((size_t)((s_begin + i) * TB + t) * 64 + lane) * 8) : zero;
 
   // weight row of this lane in row block u
   auto row_ptr = [&](int u) -> const half_t* {
@@ -285,16 +315,22 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
 #pragma unroll
   for (int i = 0; i < SKP_KSTEPS; ++i) koff[i] = in[i] ? (s_begin + i) * 32 + g * 8 : 0;
 
-  float rs = 0.f;                                   // the finishing lanes' token scale
-  if (lane < TB * 16 && lane < n) rs = 1.0f / sqrtf(a.ss_in[lane * SK_SS_STRIDE] / (float)K + a.eps);
-
+  // the weight stream starts first, the (cached) activations follow
   int u = blockIdx.x;
   h8 fa0[HALF], fa1[HALF];
-  if (u < units) {
-    const half_t* wp = row_ptr(u);
+  {
+    const half_t* wp = row_ptr(u < units ? u : 0);
 #pragma unroll
     for (int i = 0; i < HALF; ++i) fa0[i] = load_h8(wp + koff[i]);
   }
+  __builtin_amdgcn_sched_barrier(0);
+  h8 fb[SKP_KSTEPS][TB];
+#pragma unroll
+  for (int i = 0; i < SKP_KSTEPS; ++i)
+#pragma unroll
+    for (int t = 0; t < TB; ++t)
+      fb[i][t] = load_h8(a.X + (in[i] ? ((long)((s_begin + i) * TB + t) * 64 + lane) * 8 : a.zeros_off));
+  __builtin_amdgcn_sched_barrier(0);
   int round = 0;
   for (; u < units; u += gridDim.x, ++round) {
     {
@@ -310,9 +346,11 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
 #pragma unroll
       for (int t = 0; t < TB; ++t)
         acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa0[i], fb[i][t], acc[t], 0, 0, 0);
-    const int un = u + gridDim.x;
-    if (un < units) {
-      const half_t* wp = row_ptr(un);
+    // always issued, so that the waits below are exact: after the last block the target is
+    // row block 0, which every workgroup re-reads from cache
+    {
+      const int un = u + gridDim.x;
+      const half_t* wp = row_ptr(un < units ? un : 0);
 #pragma unroll
       for (int i = 0; i < HALF; ++i) fa0[i] = load_h8(wp + koff[i]);
     }
@@ -333,7 +371,7 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
 
     if (wave == (round & (SK_WAVES - 1)) && lane < TB * 16 && lane < n) {
       const int tok = lane;
-      const float scale = rs;                 // token = lane in every wave
+      const float scale = 1.0f / sqrtf(a.ss_in[tok * SK_SS_STRIDE] / (float)K + a.eps);
       f4 s[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
       for (int w = 0; w < SK_WAVES; ++w) {

@@ -92,6 +92,21 @@ def test_shapes_tails_and_buckets(torch_cuda, oracle32, shape, flags):
     om.close()
 
 
+@pytest.mark.parametrize("n_prompt", [5, 20])
+def test_short_prompt_wide_model(torch_cuda, oracle32, n_prompt):
+    """d_model 4224 > 4096: the short-prompt Q/K/V and gate/up projections cannot keep their
+    activations in registers and take the general kernel."""
+    cfg = wl.custom_cfg(1, 33, 128, 64, 64, 40)
+    w = wl.weights_astype(wl.make_weights_numpy(cfg, seed=41, gain_jitter=0.1), np.float16)
+    prompt = wl.make_tokens(n_prompt, cfg["vocab"], seed=n_prompt)
+    om = oracle32.model(cfg, w)
+    with _session(cfg, w) as s:
+        run_teacher_forced(s, om, prompt, 2, "wide")
+        for which in range(2):
+            assert rel_l2(s.ll_dbg_get_kv(0, which, n_prompt + 2), om.kv(0, which)) < 3e-3
+    om.close()
+
+
 @pytest.mark.parametrize("flags", [0, 1], ids=["graph", "eager"])
 @pytest.mark.parametrize("n_prompt", [2, 15, 16, 17, 31, 32, 33, 50])
 def test_short_prompt_row_blocks(torch_cuda, oracle32, n_prompt, flags):
@@ -204,7 +219,7 @@ def test_error_paths_on_device(torch_cuda):
 
 
 # ------------------------------------------------------------ config 2: one 7B-shaped layer
-@pytest.mark.parametrize("kv_len", [10, 128, 500])
+@pytest.mark.parametrize("kv_len", [10, 25, 128, 500])
 def test_one_7b_layer_decode_step(torch_cuda, oracle32, kv_len):
     """d=4096, 32x128 heads, FFN 11008, fp16 N(0,0.02) weights.  The cache is
     filled by prefilling kv_len random hidden states (token i's embedding is an
