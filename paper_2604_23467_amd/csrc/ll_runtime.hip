@@ -16,6 +16,7 @@
 #include "decode_mega.h"
 #include "prefill_kernels.h"
 #include "prefill_skinny.h"
+#include "prefill_gemm.h"
 
 namespace {
 
@@ -362,8 +363,24 @@ void enqueue_decode(Instance* I, hipStream_t s) {
   else enqueue_decode_multi(I, s);
 }
 
+const int g_gemm_wgs = 128;   // workgroups a GEMM launch should reach before K is no longer split
+
+// K splits of a projection GEMM: one workgroup per CU where the tiles allow it, but at least 8
+// slabs per workgroup; fewer, longer workgroups beat full occupancy bought with atomics (measured)
+int gemm_splits(int N, int K, int nmat, int Mb) {
+  const int bm = Mb >= 128 ? 128 : 64;
+  const int tiles = (Mb / bm) * ((N + PF_BN - 1) / PF_BN) * nmat;
+  const int nslabs = (K + PF_BK - 1) / PF_BK;
+  int ks = (g_gemm_wgs + tiles - 1) / tiles;
+  if (ks > nslabs / 8) ks = nslabs / 8;
+  if (ks < 1) ks = 1;
+  const int per = (nslabs + ks - 1) / ks;
+  return (nslabs + per - 1) / per;
+}
+
+// C += A W^T; fresh: C holds nothing to keep (the caller has zeroed it if gemm_splits() > 1)
 void launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0, const void* w1,
-                 const void* w2, int nmat, float* C, int ldc, int N, int K, int Mb) {
+                 const void* w2, int nmat, float* C, int ldc, int N, int K, int Mb, bool fresh) {
   GemmArgs ga{};
   ga.A = A;
   ga.W[0] = (const half_t*)w0; ga.W[1] = (const half_t*)w1; ga.W[2] = (const half_t*)w2;
@@ -374,21 +391,17 @@ void launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0, co
   ga.mtiles = Mb / bm;
   ga.ntiles = (N + PF_BN - 1) / PF_BN;
   const int total_nt = ga.ntiles * nmat;
-  const int tiles = ga.mtiles * total_nt;
-  const int ktiles = (K + PF_BK - 1) / PF_BK;
-  // 128-row tiles: one workgroup per CU (measured best of 1..3); 64-row tiles are weight-stream
-  // bound and want two resident workgroups per CU with their slabs in flight
-  const int want_wgs = bm == 128 ? 256 : 512;
-  int ks = (want_wgs + tiles - 1) / tiles;
-  if (ks > ktiles / 4) ks = ktiles / 4;          // at least 4 slabs per workgroup
-  if (ks < 1) ks = 1;
-  ga.kt_per_split = (ktiles + ks - 1) / ks;
-  ks = (ktiles + ga.kt_per_split - 1) / ga.kt_per_split;
+  const int nslabs = (K + PF_BK - 1) / PF_BK;
+  const int ks = gemm_splits(N, K, nmat, Mb);
+  ga.slabs_per_split = (nslabs + ks - 1) / ks;
   ga.atomic = ks > 1;
+  ga.overwrite = fresh && ks == 1;
   const int nt_rounds = (total_nt + 7) / 8;      // n-tiles are dealt to the 8 XCDs
   dim3 grid(nt_rounds * ga.mtiles * 8, ks);
-  if (bm == 128) hipLaunchKernelGGL((pf_gemm_kernel<128, 2>), grid, dim3(LL_WG), PF_GEMM_LDS_BYTES(128, 2), s, ga);
-  else hipLaunchKernelGGL((pf_gemm_kernel<64, 3>), grid, dim3(LL_WG), PF_GEMM_LDS_BYTES(64, 3), s, ga);
+  if (bm == 128)
+    hipLaunchKernelGGL((pf_gemm_kernel<128, 3>), grid, dim3(PF_GEMM_THREADS), PF_GEMM_LDS_BYTES(128, 3), s, ga);
+  else
+    hipLaunchKernelGGL((pf_gemm_kernel<64, 3>), grid, dim3(PF_GEMM_THREADS), PF_GEMM_LDS_BYTES(64, 3), s, ga);
 }
 
 int g_num_cus = 256;
@@ -485,8 +498,8 @@ void enqueue_prefill(Instance* I, hipStream_t s, int Mb) {
   for (int l = 0; l < c.n_layers; ++l) {
     const ll_layer_weights& W = I->layers[l];
     hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(LL_WG), 0, s, X, (const half_t*)W.attn_norm,
-                       Xn, d, c.rms_eps, QKV, 3 * d, 0);
-    launch_gemm(I, s, Xn, W.wq, W.wk, W.wv, 3, QKV, 3 * d, d, d, Mb);
+                       Xn, d, c.rms_eps, QKV, gemm_splits(d, d, 3, Mb) > 1 ? 3 * d : 0, 0);
+    launch_gemm(I, s, Xn, W.wq, W.wk, W.wv, 3, QKV, 3 * d, d, d, Mb, true);
     hipLaunchKernelGGL(pf_rope_kv_kernel, dim3(Mb), dim3(LL_WG), 0, s, QKV,
                        I->at<float2>(I->L.rope), I->state(), Qh, I->kcache(l), I->vcache(l), d,
                        c.head_dim, c.max_seq);
@@ -497,13 +510,13 @@ void enqueue_prefill(Instance* I, hipStream_t s, int Mb) {
     else
       hipLaunchKernelGGL(pf_attn_kernel<64>, agrid, dim3(128), 0, s, Qh, I->kcache(l),
                          I->vcache(l), I->state(), Oh, d, c.max_seq, 0);
-    launch_gemm(I, s, Oh, W.wo, nullptr, nullptr, 1, X, d, d, d, Mb);
+    launch_gemm(I, s, Oh, W.wo, nullptr, nullptr, 1, X, d, d, d, Mb, false);
     hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(LL_WG), 0, s, X, (const half_t*)W.ffn_norm,
-                       Xn, d, c.rms_eps, GU, 2 * F, 0);
-    launch_gemm(I, s, Xn, W.w_gate, W.w_up, nullptr, 2, GU, 2 * F, F, d, Mb);
+                       Xn, d, c.rms_eps, GU, gemm_splits(F, d, 2, Mb) > 1 ? 2 * F : 0, 0);
+    launch_gemm(I, s, Xn, W.w_gate, W.w_up, nullptr, 2, GU, 2 * F, F, d, Mb, true);
     hipLaunchKernelGGL(pf_swiglu_kernel, dim3(Mb, (F + LL_WG * 4 - 1) / (LL_WG * 4)), dim3(LL_WG), 0,
                        s, GU, I->state(), Hm, F);
-    launch_gemm(I, s, Hm, W.w_down, nullptr, nullptr, 1, X, d, d, F, Mb);
+    launch_gemm(I, s, Hm, W.w_down, nullptr, nullptr, 1, X, d, d, F, Mb, false);
   }
   enqueue_head(I, s, X, 1, 1);
 }
@@ -635,8 +648,8 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipMemset(I->at<int>(L.tokens), 0, (size_t)L.mb_max * 4), "hipMemset(tokens)"))
     return bail(rc);
   if (!hip_or_bail(hipMemset(I->at<char>(L.zeros), 0, 256), "hipMemset(zeros)")) return bail(rc);
-  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128, 2>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128, 2)),
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128, 3>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128, 3)),
                    "hipFuncSetAttribute(gemm 128)")) return bail(rc);
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<64, 3>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(64, 3)),

@@ -1,0 +1,192 @@
+// Prefill projection GEMM for gfx950, prompts of 33..512 tokens (Sec. IV-E / Table I, the upper
+// part of the TTFT range): C[M][ldc] (fp32) += A[M][K] (fp16 activations) * W_z[N][K]^T (fp16).
+//
+// v_mfma_f32_32x32x16_f16, the full-rate fp16 matrix instruction of this chip (measured: 2.0
+// PFLOP/s with one wave per SIMD and 8 independent accumulators; the 16x16x32 form reaches
+// 0.83), activations as the A operand, weights as the B operand.
+//
+// Workgroup = 4 waves side by side along N, tile = BM rows x 256 columns x 64 k per slab
+// (BM = 128, or 64 for prompts of at most 64 rows); a wave owns all BM rows of 64 columns:
+// BM/32 x 2 accumulators of 32 x 32.  The wide tile is what the memory system needs: every
+// slab moves (BM + 256) x 128 bytes from L2 for BM x 256 x 128 flop, and with M <= 512 split
+// over 256 CUs it is the L2 -> CU traffic, not HBM, that bounds these GEMMs.
+//
+// Both operands go global -> LDS directly (global_load_lds_dwordx4: no staging registers)
+// into a ring of NS stages, NS - 1 slabs ahead of the one being multiplied.  A direct load
+// writes the 64 lanes' 16-byte pieces to consecutive LDS addresses, so rows are stored
+// unpadded (128 bytes) and 16-byte chunk c of row r lives at chunk position c ^ (r & 7);
+// fragment reads of 32 rows x 2 chunks then run at the LDS's full rate (measured).  Pieces
+// outside the matrices (K tail, rows >= N, slabs past the split's end) are fetched from a block
+// of zeros, so no lane is ever switched off and the wait counts are static.
+//
+// Split-K over blockIdx.y with fp32 atomic adds when a prompt gives too few tiles to occupy
+// the chip (the caller zeroes C first unless it is the residual stream); one split stores, or
+// adds in place when C is the residual stream.  Tile order keeps the M tiles that
+// share a weight tile on one XCD (workgroups are dealt to the 8 XCDs round robin), so the
+// re-reads of a weight tile hit that XCD's L2.
+#pragma once
+#include "ll_device.h"
+
+struct GemmArgs {
+  const half_t* A;        // [>= mtiles * BM rows][K]
+  const half_t* W[3];
+  float* C;
+  const DevState* st;
+  const half_t* zeros;    // >= 16 bytes of zeros in global memory
+  int N, K, ldc, nmat;
+  int mtiles, ntiles;     // tiles of BM rows / 256 columns (per matrix)
+  int slabs_per_split;    // 64-wide K slabs per blockIdx.y
+  int atomic;             // more than one K split: accumulate with atomics
+  int overwrite;          // single split and C holds nothing to keep: store instead of adding
+};
+
+#define PF_BN 256
+#define PF_BK 64
+#define PF_GEMM_WAVES 4
+#define PF_GEMM_THREADS (PF_GEMM_WAVES * 64)
+#define PF_GEMM_LDS_BYTES(BM, NS) ((NS) * ((BM) + PF_BN) * PF_BK * 2)
+
+// s_waitcnt vmcnt(N) (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the export and LDS counters
+// left at "no wait")
+template <int N>
+__device__ __forceinline__ void wait_vm_at_most() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | 0x70 | 0xF00 | ((N >> 4) << 14));
+}
+
+template <int BM, int NS>
+__global__ __launch_bounds__(PF_GEMM_THREADS, 1) void pf_gemm_kernel(GemmArgs g) {
+  constexpr int MT = BM / 32;                          // 32-row accumulators per wave
+  constexpr int NT = 2;                                // 32-column accumulators per wave
+  constexpr int A_LD = BM / 8 / PF_GEMM_WAVES;         // 1 KB direct loads per wave and slab (8 rows each)
+  constexpr int W_LD = PF_BN / 8 / PF_GEMM_WAVES;
+  constexpr int PER_SLAB = A_LD + W_LD;
+  constexpr int STAGE_HALVES = (BM + PF_BN) * PF_BK;
+  static_assert(PER_SLAB * (NS - 1) < 64, "vmcnt is a 6-bit counter");
+  extern __shared__ __attribute__((aligned(16))) half_t pf_lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  // XCD-aware tile order: slot t of XCD x handles n-tile (t / mtiles) * 8 + x, m-tile t % mtiles
+  const int total_nt = g.ntiles * g.nmat;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int nt_all = (slot / g.mtiles) * 8 + xcd;
+  const int mt = slot % g.mtiles;
+  if (nt_all >= total_nt) return;
+  const int z = nt_all / g.ntiles, nt = nt_all - z * g.ntiles;
+  const int m0 = mt * BM, n0 = nt * PF_BN;
+  if (m0 >= g.st->n_prompt) return;
+
+  const int K = g.K;
+  const int nslabs_all = (K + PF_BK - 1) / PF_BK;
+  const int sl0 = blockIdx.y * g.slabs_per_split;
+  const int sl1 = min(sl0 + g.slabs_per_split, nslabs_all);
+  if (sl0 >= sl1) return;
+
+  // this lane's piece of every 8-row group: row (lane / 8), physical chunk (lane % 8),
+  // which holds logical chunk (lane % 8) ^ (row & 7) = (lane % 8) ^ (lane / 8)
+  const int lrow = lane >> 3, lchunk = (lane & 7) ^ lrow;
+  const half_t* arow[A_LD];
+  const half_t* wrow[W_LD];
+#pragma unroll
+  for (int i = 0; i < A_LD; ++i)
+    arow[i] = g.A + (size_t)(m0 + (wave * A_LD + i) * 8 + lrow) * K + lchunk * 8;
+#pragma unroll
+  for (int i = 0; i < W_LD; ++i) {
+    const int n = n0 + (wave * W_LD + i) * 8 + lrow;
+    wrow[i] = (n < g.N) ? g.W[z] + (size_t)n * K + lchunk * 8 : nullptr;
+  }
+  auto issue = [&](int sl, int stage) {
+    half_t* sa = pf_lds + stage * STAGE_HALVES;
+    half_t* sw = sa + BM * PF_BK;
+    const bool kin = sl < sl1 && sl * PF_BK + lchunk * 8 < K;   // K % 8 == 0: a chunk is all in or all out
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+      const half_t* src = kin ? arow[i] + sl * PF_BK : g.zeros;
+      __builtin_amdgcn_global_load_lds((const LL_GLOBAL void*)src,
+                                       (__attribute__((address_space(3))) void*)(sa + (wave * A_LD + i) * 8 * PF_BK),
+                                       16, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < W_LD; ++i) {
+      const half_t* src = (kin && wrow[i]) ? wrow[i] + sl * PF_BK : g.zeros;
+      __builtin_amdgcn_global_load_lds((const LL_GLOBAL void*)src,
+                                       (__attribute__((address_space(3))) void*)(sw + (wave * W_LD + i) * 8 * PF_BK),
+                                       16, 0, 0);
+    }
+  };
+
+  f16v acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s) issue(sl0 + s, s);
+
+  const int r = lane & 31, half = lane >> 5;
+  for (int sl = sl0; sl < sl1; ++sl) {
+    const int stage = (sl - sl0) % NS;
+    // this wave's pieces of slab sl have landed (younger slabs may still be in flight) ...
+    wait_vm_at_most<PER_SLAB * (NS - 2)>();
+    // ... and so have everybody else's; everybody is also done reading the stage of slab sl - 1.
+    // A bare s_barrier: __syncthreads() carries a fence that would drain ALL loads in flight.
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    issue(sl + NS - 1, (stage + NS - 1) % NS);
+    const half_t* sa = pf_lds + stage * STAGE_HALVES + r * PF_BK;
+    const half_t* sw = sa + (BM + wave * 64) * PF_BK;
+    // fragments of k-step ks + 1 are read from LDS while the matrix cores work on k-step ks
+    auto load_frags = [&](int ks, h8 (&fa)[MT], h8 (&fb)[NT]) {
+      const int pc = ((ks * 2 + half) ^ (r & 7)) * 8;   // all fragment rows start at multiples of 8
+#pragma unroll
+      for (int i = 0; i < MT; ++i) fa[i] = *reinterpret_cast<const h8*>(sa + i * 32 * PF_BK + pc);
+#pragma unroll
+      for (int j = 0; j < NT; ++j) fb[j] = *reinterpret_cast<const h8*>(sw + j * 32 * PF_BK + pc);
+    };
+    h8 fa[2][MT], fb[2][NT];
+    load_frags(0, fa[0], fb[0]);
+#pragma unroll
+    for (int ks = 0; ks < PF_BK / 16; ++ks) {
+      if (ks + 1 < PF_BK / 16) load_frags(ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+    }
+  }
+  wait_vm_at_most<0>();   // the zero-filled look-ahead loads must not outlive the workgroup's LDS
+
+  // accumulator layout of the 32x32 MFMA: lane holds column (lane % 32) and
+  // rows 8*(e/4) + 4*(lane/32) + e%4 for e = 0..15
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    const int col = n0 + wave * 64 + j * 32 + r;
+    if (col >= g.N) continue;
+    float* cbase = g.C + (size_t)z * g.N + col + (size_t)(m0 + 4 * half) * g.ldc;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      if (g.atomic) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          unsafeAtomicAdd(cbase + (size_t)(i * 32 + 8 * (e >> 2) + (e & 3)) * g.ldc, acc[i][j][e]);
+      } else if (g.overwrite) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          *as_global(cbase + (size_t)(i * 32 + 8 * (e >> 2) + (e & 3)) * g.ldc) = acc[i][j][e];
+      } else {
+        // all 16 loads first: an add-in-place per element would serialise 16 memory round trips
+        float old[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) old[e] = *as_global(cbase + (size_t)(i * 32 + 8 * (e >> 2) + (e & 3)) * g.ldc);
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          *as_global(cbase + (size_t)(i * 32 + 8 * (e >> 2) + (e & 3)) * g.ldc) = old[e] + acc[i][j][e];
+      }
+    }
+  }
+}

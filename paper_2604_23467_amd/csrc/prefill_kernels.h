@@ -1,8 +1,7 @@
 // Short-prompt prefill kernels for gfx950 (prompts of 10-500 tokens, the
 // paper's TTFT regime, Sec. IV-E / Table I): the same layer as the decode path
-// but for n rows at positions 0..n-1, so the projections are real dense
-// contractions and run on the matrix cores (v_mfma_f32_32x32x16_f16, fp16
-// operands, fp32 accumulate), and attention is LDS-tiled and causal.
+// but for n rows at positions 0..n-1: the elementwise kernels around the
+// projection GEMM (prefill_gemm.h) and the causal attention on the matrix cores.
 //
 // Every kernel is launched on a grid sized for a prompt-length bucket Mb and
 // reads the true n from DevState, so one captured graph per bucket serves all
@@ -62,181 +61,6 @@ __global__ __launch_bounds__(LL_WG) void pf_rmsnorm_kernel(const float* __restri
   float* z = zero_buf + (size_t)r * zero_row_floats;
   const f4 zero = {0.f, 0.f, 0.f, 0.f};
   for (int i = tid * 4; i < zero_row_floats; i += LL_WG * 4) *reinterpret_cast<f4*>(z + i) = zero;
-}
-
-// C[M][ldc] (fp32) += A[M][K] (fp16) * W_z[N][K]^T (fp16) for z < nmat, output
-// columns z*N + n.  BM x 128 tile per workgroup (BM = 64 for the short-prompt
-// bucket, 128 otherwise), four waves in a 2 x 2 arrangement, each owning a
-// (BM/2) x 64 block = BM/64 x 2 MFMA accumulators of 32 x 32.
-//
-// K is walked in 64-wide slabs through a ring of PF_STAGES LDS buffers that is
-// filled by direct global->LDS loads (global_load_lds_dwordx4: no staging
-// registers), PF_STAGES - 1 slabs ahead of the one being multiplied.  With
-// both operands in LDS a 64 x 64 wave tile moves 1 KB of LDS per MFMA, which
-// is what bounds this kernel (measured: dropping the MFMAs changes nothing,
-// dropping the loads gains 25 %), so LDS capacity is better spent on a second
-// resident workgroup than on deeper prefetch: 2 stages for the 128-row tile
-// (measured against 3 and 4).  The 64-row tile of the short-prompt bucket is
-// bound by the weight stream instead and gets 3 stages.  A direct load writes the 64 lanes' 16-byte pieces to consecutive LDS addresses, so
-// rows are stored unpadded (128 bytes) and bank conflicts are avoided by an XOR
-// swizzle instead: 16-byte chunk c of row r lives at chunk position c ^ (r & 7).
-// Pieces outside the matrices (K tail, rows >= N) are fetched from a block of
-// zeros, so no lane is ever switched off.
-//
-// Split-K over blockIdx.y with fp32 atomic adds when the prompt gives too few
-// output tiles to spread the weight stream (read once) over all CUs; with one
-// split the tile is added with plain read-modify-writes.  Workgroup -> tile
-// mapping keeps the M-tiles that share a weight tile on one XCD (workgroups
-// are dealt to the 8 XCDs round robin), so the re-reads hit that XCD's L2.
-struct GemmArgs {
-  const half_t* A;
-  const half_t* W[3];
-  float* C;
-  const DevState* st;
-  const half_t* zeros;  // >= 16 bytes of zeros in global memory
-  int N, K, ldc, nmat;
-  int mtiles, ntiles;   // tiles of BM rows / 128 columns (per matrix)
-  int kt_per_split;     // 64-wide K slabs per blockIdx.y
-  int atomic;           // more than one K split: accumulate with atomics
-};
-
-#define PF_BN 128
-#define PF_BK 64
-#define PF_GEMM_LDS_BYTES(BM, STAGES) ((STAGES) * ((BM) + PF_BN) * PF_BK * 2)
-
-template <int N>
-__device__ __forceinline__ void wait_vm_at_most() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-template <int BM, int PF_STAGES>
-__global__ __launch_bounds__(LL_WG) void pf_gemm_kernel(GemmArgs g) {
-  constexpr int MT = BM / 64;             // 32-row MFMA tiles per wave
-  constexpr int A_LD = BM / 32;           // 1 KB direct loads per wave and slab for A (8 rows each)
-  constexpr int W_LD = PF_BN / 32;
-  constexpr int STAGE_HALVES = (BM + PF_BN) * PF_BK;
-  extern __shared__ __attribute__((aligned(16))) half_t pf_lds[];
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-
-  // XCD-aware tile order: slot t of XCD x handles n-tile (t / mtiles) * 8 + x, m-tile t % mtiles
-  const int total_nt = g.ntiles * g.nmat;
-  const int b = blockIdx.x;
-  const int xcd = b & 7, slot = b >> 3;
-  const int nt_all = (slot / g.mtiles) * 8 + xcd;
-  const int mt = slot % g.mtiles;
-  if (nt_all >= total_nt) return;
-  const int z = nt_all / g.ntiles, nt = nt_all - z * g.ntiles;
-  const int m0 = mt * BM, n0 = nt * PF_BN;
-  if (m0 >= g.st->n_prompt) return;
-
-  const int K = g.K;
-  const int ktiles = (K + PF_BK - 1) / PF_BK;
-  const int kt0 = blockIdx.y * g.kt_per_split;
-  const int kt1 = min(kt0 + g.kt_per_split, ktiles);
-  if (kt0 >= kt1) return;
-
-  // this lane's piece of every 8-row block: row (lane / 8), physical chunk (lane % 8),
-  // which holds logical chunk (lane % 8) ^ (row & 7) = (lane % 8) ^ (lane / 8)
-  const int lrow = lane >> 3;
-  const int lchunk = (lane & 7) ^ lrow;
-  const half_t* arow[A_LD];
-  const half_t* wrow[W_LD];
-#pragma unroll
-  for (int i = 0; i < A_LD; ++i)
-    arow[i] = g.A + (size_t)(m0 + (wave * A_LD + i) * 8 + lrow) * K + lchunk * 8;
-#pragma unroll
-  for (int i = 0; i < W_LD; ++i) {
-    const int n = n0 + (wave * W_LD + i) * 8 + lrow;
-    wrow[i] = (n < g.N) ? g.W[z] + (size_t)n * K + lchunk * 8 : nullptr;
-  }
-  auto issue = [&](int kt, int stage) {
-    half_t* sa = pf_lds + stage * STAGE_HALVES;
-    half_t* sw = sa + BM * PF_BK;
-    const bool kin = kt < kt1 && kt * PF_BK + lchunk * 8 < K;   // K % 8 == 0: a chunk is all in or all out
-#pragma unroll
-    for (int i = 0; i < A_LD; ++i) {
-      const half_t* src = kin ? arow[i] + kt * PF_BK : g.zeros;
-      __builtin_amdgcn_global_load_lds((const LL_GLOBAL void*)src,
-                                       (__attribute__((address_space(3))) void*)(sa + (wave * A_LD + i) * 8 * PF_BK),
-                                       16, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < W_LD; ++i) {
-      const half_t* src = (kin && wrow[i]) ? wrow[i] + kt * PF_BK : g.zeros;
-      __builtin_amdgcn_global_load_lds((const LL_GLOBAL void*)src,
-                                       (__attribute__((address_space(3))) void*)(sw + (wave * W_LD + i) * 8 * PF_BK),
-                                       16, 0, 0);
-    }
-  };
-
-  const int wm = wave >> 1, wn = wave & 1;
-  f16v acc[MT][2];
-#pragma unroll
-  for (int i = 0; i < MT; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-#pragma unroll
-  for (int s = 0; s < PF_STAGES - 1; ++s) issue(kt0 + s, s);
-
-  for (int kt = kt0; kt < kt1; ++kt) {
-    const int stage = (kt - kt0) % PF_STAGES;
-    // this wave's pieces of slab kt have landed (later slabs may still be in flight) ...
-    wait_vm_at_most<(A_LD + W_LD) * (PF_STAGES - 2)>();
-    // ... and so have everybody else's; everybody is also done reading slab kt - 1.
-    // A bare s_barrier: __syncthreads() carries a fence that would drain ALL loads in flight.
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    issue(kt + PF_STAGES - 1, (stage + PF_STAGES - 1) % PF_STAGES);
-    const half_t* sa = pf_lds + stage * STAGE_HALVES;
-    const half_t* sw = sa + BM * PF_BK;
-    // fragments of k-step ks + 1 are read from LDS while the matrix cores work on k-step ks
-    const int r = lane & 31;
-    auto load_frags = [&](int ks, h8 (&fa)[MT], h8 (&fb)[2]) {
-      const int c = ks * 2 + (lane >> 5);           // logical 16-byte chunk of the row
-      const int pc = (c ^ (r & 7)) * 8;              // all tile rows start at multiples of 8
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-        fa[i] = *reinterpret_cast<const h8*>(sa + (wm * (BM / 2) + i * 32 + r) * PF_BK + pc);
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        fb[j] = *reinterpret_cast<const h8*>(sw + (wn * 64 + j * 32 + r) * PF_BK + pc);
-    };
-    h8 fa[2][MT], fb[2][2];
-    load_frags(0, fa[0], fb[0]);
-#pragma unroll
-    for (int ks = 0; ks < PF_BK / 16; ++ks) {
-      if (ks + 1 < PF_BK / 16) load_frags(ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
-    }
-  }
-  wait_vm_at_most<0>();   // the zero-filled look-ahead loads must not outlive the workgroup's LDS
-
-  // accumulator layout of the 32x32 MFMA: lane holds column (lane % 32) and
-  // rows 8*(e/4) + 4*(lane/32) + e%4 for e = 0..15
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int col = n0 + wn * 64 + j * 32 + (lane & 31);
-    if (col >= g.N) continue;
-    float* cbase = g.C + (size_t)z * g.N + col;
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = m0 + wm * (BM / 2) + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        float* cp = cbase + (size_t)row * g.ldc;
-        if (g.atomic) unsafeAtomicAdd(cp, acc[i][j][e]);
-        else *cp += acc[i][j][e];
-      }
-  }
 }
 
 // RoPE on the q and k thirds of QKV[r] (fp32, [Mb][3d]) at position r, then
