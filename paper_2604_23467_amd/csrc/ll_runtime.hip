@@ -363,15 +363,17 @@ void enqueue_decode(Instance* I, hipStream_t s) {
   else enqueue_decode_multi(I, s);
 }
 
-const int g_gemm_wgs = 128;   // workgroups a GEMM launch should reach before K is no longer split
 
-// K splits of a projection GEMM: one workgroup per CU where the tiles allow it, but at least 8
-// slabs per workgroup; fewer, longer workgroups beat full occupancy bought with atomics (measured)
-int gemm_splits(int N, int K, int nmat, int Mb) {
+
+// K splits of a projection GEMM.  Splitting buys occupancy with atomics (and a zeroing pass for
+// fresh outputs): measured best is to stop at 128 workgroups, except for the residual-stream
+// GEMMs of the 512-row bucket, which are worth splitting up to 256.  At least 8 slabs per split.
+int gemm_splits(int N, int K, int nmat, int Mb, bool fresh = true) {
   const int bm = Mb >= 128 ? 128 : 64;
   const int tiles = (Mb / bm) * ((N + PF_BN - 1) / PF_BN) * nmat;
   const int nslabs = (K + PF_BK - 1) / PF_BK;
-  int ks = (g_gemm_wgs + tiles - 1) / tiles;
+  const int want = (!fresh && Mb >= 512) ? 256 : 128;
+  int ks = (want + tiles - 1) / tiles;
   if (ks > nslabs / 8) ks = nslabs / 8;
   if (ks < 1) ks = 1;
   const int per = (nslabs + ks - 1) / ks;
@@ -392,7 +394,7 @@ void launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0, co
   ga.ntiles = (N + PF_BN - 1) / PF_BN;
   const int total_nt = ga.ntiles * nmat;
   const int nslabs = (K + PF_BK - 1) / PF_BK;
-  const int ks = gemm_splits(N, K, nmat, Mb);
+  const int ks = gemm_splits(N, K, nmat, Mb, fresh);
   ga.slabs_per_split = (nslabs + ks - 1) / ks;
   ga.atomic = ks > 1;
   ga.overwrite = fresh && ks == 1;
