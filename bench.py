@@ -235,6 +235,20 @@ def main():
             t0 = time.perf_counter()
             gs.ll_decode_step()
             gl[i] = time.perf_counter() - t0
+        # in-graph stochastic sampling (temperature 0.8, top-k 50, top-p 0.95) against greedy, same session
+        gs.ll_reset()
+        gs.ll_set_sampling(0.8, 50, 0.95, 1234)
+        gs.ll_prefill(prompt[:10])
+        gs.ll_decode_n(10)
+        sl = np.empty(100)
+        for i in range(100):
+            t0 = time.perf_counter()
+            gs.ll_decode_step()
+            sl[i] = time.perf_counter() - t0
+        sampling = dict(temperature=0.8, top_k=50, top_p=0.95, p50_us=pct(sl, 50) * 1e6, p99_us=pct(sl, 99) * 1e6,
+                        greedy_p50_us=pct(gl, 50) * 1e6)
+        log("[bench] prompt 10, 100 steps with top-k/top-p sampling in the graph: p50 %.1f us p99 %.1f us (greedy p50 %.1f us)"
+            % (sampling["p50_us"], sampling["p99_us"], sampling["greedy_p50_us"]))
         gs.close()
         ps = binding.Session(cfg, w_t, flags=binding.LL_FLAG_PERSISTENT)
         ps.ll_prefill(prompt[:10])
@@ -247,7 +261,8 @@ def main():
         ps.close()
         eager = dict(prompt=10, steps=100, eager_p50_us=pct(el, 50) * 1e6, eager_p99_us=pct(el, 99) * 1e6,
                      graph_p50_us=pct(gl, 50) * 1e6, graph_p99_us=pct(gl, 99) * 1e6,
-                     persistent_kernel_p50_us=pct(pl, 50) * 1e6, persistent_kernel_p99_us=pct(pl, 99) * 1e6)
+                     persistent_kernel_p50_us=pct(pl, 50) * 1e6, persistent_kernel_p99_us=pct(pl, 99) * 1e6,
+                     sampling=sampling)
         log("[bench] prompt 10, 100 steps: graph p50 %.1f us p99 %.1f us | eager p50 %.1f us p99 %.1f us | "
             "one persistent kernel p50 %.1f us p99 %.1f us"
             % (eager["graph_p50_us"], eager["graph_p99_us"], eager["eager_p50_us"], eager["eager_p99_us"],

@@ -127,6 +127,22 @@ int32_t ll_decode_n(int32_t k, int32_t *out_tokens);
  * workspace binding are kept. */
 int ll_reset(void);
 
+/* Token selection of every following ll_prefill / ll_decode_step.  The paper keeps "token
+ * sampling" in its host-side dynamic domain (Sec. III-A, III-C) and names stochastic operations
+ * as what stays outside graph replay (Sec. VI-C); here the selection runs inside the captured
+ * graph and its parameters live in device memory, so no graph is re-captured.
+ *   temperature = 0: greedy argmax (the state after ll_init).
+ *   temperature > 0: z = logits * float(1 / temperature); keep the top_k largest z (0 = all,
+ *     equal values by lower index); softmax over them; keep the smallest set of highest
+ *     probabilities whose mass reaches top_p (1 = all, equal values by lower index); draw by
+ *     walking the kept tokens in index order with u = (x >> 8) * 2^-24, x = first word of
+ *     Philox4x32-10(counter = (i, 0, 0, 0), key = seed), i = tokens produced since the last
+ *     ll_reset.  A reset therefore replays the same token stream.
+ * LL_E_BAD_ARG for temperature < 0 or not finite, top_k < 0, top_p outside (0, 1];
+ * LL_E_CAPACITY for temperature > 0 with vocab > 32768; LL_E_STATE for temperature > 0 in the
+ * persistent-kernel mode.  The setting survives ll_reset. */
+int ll_set_sampling(float temperature, int32_t top_k, float top_p, uint64_t seed);
+
 /* Destroys graphs and host buffers; caller memory is untouched. */
 int ll_shutdown(void);
 

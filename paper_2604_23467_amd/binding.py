@@ -24,7 +24,7 @@ KERNEL_CLASSES = ("embed", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "
 LAYER_KEYS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
 
 EXPORTS = ("ll_workspace_bytes", "ll_init", "ll_prefill", "ll_decode_step", "ll_decode_n", "ll_reset",
-           "ll_shutdown", "ll_max_prompt", "ll_position", "ll_decode_mode", "ll_last_error", "ll_dbg_get_logits",
+           "ll_set_sampling", "ll_shutdown", "ll_max_prompt", "ll_position", "ll_decode_mode", "ll_last_error", "ll_dbg_get_logits",
            "ll_dbg_get_hidden", "ll_dbg_force_next_token", "ll_dbg_get_kv", "ll_dbg_profile_decode",
            "ll_dbg_time_decode", "ll_dbg_time_kernel_class", "ll_dbg_stream_copy", "ll_dbg_trace_decode")
 
@@ -78,6 +78,8 @@ def load():
     for name in ("ll_max_prompt", "ll_position", "ll_decode_mode"):
         getattr(L, name).restype = C.c_int32
         getattr(L, name).argtypes = []
+    L.ll_set_sampling.restype = C.c_int
+    L.ll_set_sampling.argtypes = [C.c_float, C.c_int32, C.c_float, C.c_uint64]
     L.ll_last_error.restype = C.c_char_p
     L.ll_last_error.argtypes = []
     L.ll_dbg_get_logits.restype = C.c_int
@@ -125,6 +127,12 @@ def ll_dbg_stream_copy(dst, src):
     assert dst.numel() * dst.element_size() == nbytes
     return _check(load().ll_dbg_stream_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()),
                                             C.c_size_t(nbytes)))
+
+
+def ll_set_sampling_raw(temperature, top_k, top_p, seed):
+    """ll_set_sampling on whatever instance the library holds (an error without one)."""
+    return _check(load().ll_set_sampling(C.c_float(temperature), C.c_int32(top_k), C.c_float(top_p),
+                                         C.c_uint64(seed)))
 
 
 def ll_last_error():
@@ -191,6 +199,9 @@ class Session:
 
     def ll_reset(self):
         return _check(self.lib.ll_reset())
+
+    def ll_set_sampling(self, temperature, top_k=0, top_p=1.0, seed=0):
+        return ll_set_sampling_raw(temperature, top_k, top_p, seed)
 
     def ll_shutdown(self):
         if self.open:

@@ -472,55 +472,6 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_decode_kernel(
   }
 }
 
-// Final argmax over the per-workgroup candidates of the LM head (ties: lowest
-// index), then the state advance that makes the next replay self-contained:
-// the token becomes next_token, the position moves on, and the id is written
-// to a pinned host ring the caller reads after synchronising.
-//   prefill = 1: pos := n_prompt, steps := 1, ring[0] := token
-//   prefill = 0: pos += 1, ring[steps] := token, steps += 1
-__global__ __launch_bounds__(LL_WG) void sample_kernel(const float* __restrict__ pval,
-                                                       const int* __restrict__ pidx, int nparts,
-                                                       DevState* st, int* host_ring, int ring_size,
-                                                       int prefill) {
-  __shared__ float sv[LL_WG];
-  __shared__ int si[LL_WG];
-  const int tid = threadIdx.x;
-  float bv = -INFINITY;
-  int bi = 0x7fffffff;
-  for (int i = tid; i < nparts; i += LL_WG) {
-    const float v = pval[i];
-    const int ix = pidx[i];
-    if (v > bv || (v == bv && ix < bi)) { bv = v; bi = ix; }
-  }
-  sv[tid] = bv;
-  si[tid] = bi;
-  __syncthreads();
-  for (int off = LL_WG / 2; off > 0; off >>= 1) {
-    if (tid < off) {
-      const float v = sv[tid + off];
-      const int ix = si[tid + off];
-      if (v > sv[tid] || (v == sv[tid] && ix < si[tid])) { sv[tid] = v; si[tid] = ix; }
-    }
-    __syncthreads();
-  }
-  if (tid == 0) {
-    int tok = si[0];
-    if (tok == 0x7fffffff) tok = 0;   // every logit NaN: still a valid id
-    int idx;
-    if (prefill) {
-      st->pos = st->n_prompt;
-      idx = 0;
-      st->steps = 1;
-    } else {
-      st->pos = st->pos + 1;
-      idx = st->steps;
-      st->steps = idx + 1;
-    }
-    st->next_token = tok;
-    if (idx < ring_size) host_ring[idx] = tok;
-  }
-}
-
 // Plain device-to-device copy with the same 16-byte streaming loads the GEMVs
 // use.  It exists to calibrate hardware traffic counters against a known byte
 // count; nothing on the decode path calls it.

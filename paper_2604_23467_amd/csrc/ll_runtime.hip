@@ -13,6 +13,7 @@
 
 #include "../../include/ll.h"
 #include "decode_kernels.h"
+#include "sample_kernels.h"
 #include "decode_mega.h"
 #include "prefill_kernels.h"
 #include "prefill_skinny.h"
@@ -75,7 +76,7 @@ bool skinny_ok(const ll_config& c) {
 struct Layout {
   size_t kv, rope, x, q, o, m, attn_part, attn_cnt, logits, amax_val, amax_idx, state, tokens;
   size_t pf_x, pf_xn, pf_qkv, pf_q, pf_o, pf_gu, pf_h, pf_ss;
-  size_t mk_layers, mk_bar, mk_amax_val, mk_amax_idx, mk_trace, zeros;
+  size_t mk_layers, mk_bar, mk_amax_val, mk_amax_idx, mk_trace, zeros, sample_cfg;
   size_t total;
   int attn_splits, lm_wgs, max_prompt, mb_max;
   size_t kv_layer_halves;   // halves per layer per K or V
@@ -121,6 +122,7 @@ Layout make_layout(const ll_config& c) {
   L.pf_h = take(M * ((F + 31) / 32 * 32) * 2);
   L.pf_ss = take(2 * 64 * SK_SS_STRIDE * 4);
   L.zeros = take(256);
+  L.sample_cfg = take(sizeof(SampleCfg));
   L.mk_layers = take((size_t)c.n_layers * sizeof(MkLayer));
   L.mk_bar = take((size_t)MK_BAR_WORDS * 4);
   L.mk_amax_val = take(1024 * 4);   // one candidate per workgroup of the persistent kernel
@@ -224,9 +226,9 @@ void enqueue_head(Instance* I, hipStream_t s, const float* xin, int from_prompt_
   }
   if (I->runs(LL_KC_SAMPLE)) {
     ProfScope ps(I, s, LL_KC_SAMPLE);
-    hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(LL_WG), 0, s, I->at<float>(I->L.amax_val),
-                       I->at<int>(I->L.amax_idx), I->L.lm_wgs, I->state(), I->dev_ring, I->ring_size,
-                       prefill);
+    hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(SMP_THREADS), 0, s, I->at<float>(I->L.amax_val),
+                       I->at<int>(I->L.amax_idx), I->L.lm_wgs, I->at<float>(I->L.logits), c.vocab,
+                       I->at<SampleCfg>(I->L.sample_cfg), I->state(), I->dev_ring, I->ring_size, prefill);
   }
 }
 
@@ -650,6 +652,8 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipMemset(I->at<int>(L.tokens), 0, (size_t)L.mb_max * 4), "hipMemset(tokens)"))
     return bail(rc);
   if (!hip_or_bail(hipMemset(I->at<char>(L.zeros), 0, 256), "hipMemset(zeros)")) return bail(rc);
+  if (!hip_or_bail(hipMemset(I->at<char>(L.sample_cfg), 0, sizeof(SampleCfg)), "hipMemset(sampling)"))
+    return bail(rc);                                           // inv_temp = 0: greedy
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128, 3>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128, 3)),
                    "hipFuncSetAttribute(gemm 128)")) return bail(rc);
@@ -732,6 +736,30 @@ int ll_reset(void) {
   HIPCHK(hipStreamSynchronize(g->stream));
   g->pos = 0;
   g->steps = 0;
+  return LL_OK;
+}
+
+int ll_set_sampling(float temperature, int32_t top_k, float top_p, uint64_t seed) {
+  if (!(temperature >= 0.f) || !(temperature < INFINITY))
+    return fail(LL_E_BAD_ARG, "ll_set_sampling: temperature = %g, need a finite value >= 0", (double)temperature);
+  if (top_k < 0) return fail(LL_E_BAD_ARG, "ll_set_sampling: top_k = %d < 0", top_k);
+  if (!(top_p > 0.f && top_p <= 1.f))
+    return fail(LL_E_BAD_ARG, "ll_set_sampling: top_p = %g outside (0, 1]", (double)top_p);
+  if (!g) return fail(LL_E_NOT_INIT, "ll_set_sampling: not initialised");
+  Instance* I = g;
+  if (temperature > 0.f && I->use_mega)
+    return fail(LL_E_STATE, "ll_set_sampling: the persistent-kernel mode selects greedily only");
+  if (temperature > 0.f && I->cfg.vocab > SMP_MAX_VOCAB)
+    return fail(LL_E_CAPACITY, "ll_set_sampling: vocab = %d > %d", I->cfg.vocab, SMP_MAX_VOCAB);
+  SampleCfg* h = reinterpret_cast<SampleCfg*>(I->host_stage);
+  memset(h, 0, sizeof(SampleCfg));
+  h->inv_temp = temperature > 0.f ? (float)(1.0 / (double)temperature) : 0.f;
+  h->top_k = top_k;
+  h->top_p = top_p;
+  h->seed_lo = (uint32_t)(seed & 0xffffffffu);
+  h->seed_hi = (uint32_t)(seed >> 32);
+  HIPCHK(hipMemcpyAsync(I->at<SampleCfg>(I->L.sample_cfg), h, sizeof(SampleCfg), hipMemcpyHostToDevice, I->stream));
+  HIPCHK(hipStreamSynchronize(I->stream));
   return LL_OK;
 }
 

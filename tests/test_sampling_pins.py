@@ -5,6 +5,7 @@ import json
 import os
 
 import numpy as np
+import pytest
 from oracle import sampling as sp
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -95,3 +96,12 @@ def test_index_order_walk_and_last_token_fallback():
     assert [sp.sample(z, 1.0, 0, 1.0, u)[0] for u in (0.05, 0.1, 0.69, 0.7, 0.99)] == [0, 1, 1, 2, 2]
     tok, info = sp.sample(z, 1.0, 0, 1.0, 1.0)                    # u = 1 cannot be drawn; the walk still ends inside
     assert tok == 2
+
+
+@pytest.mark.parametrize("bad", [dict(temperature=-1.0), dict(top_k=-1), dict(top_p=0.0), dict(top_p=1.5)])
+def test_binding_rejects_bad_sampling_parameters_without_a_gpu(bad):
+    from paper_2604_23467_amd import binding
+    args = dict(temperature=1.0, top_k=0, top_p=1.0, seed=1)
+    args.update(bad)
+    with pytest.raises(binding.LLError):
+        binding.ll_set_sampling_raw(**args)                       # not initialised or bad argument: an error either way
