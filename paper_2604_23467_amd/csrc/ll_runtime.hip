@@ -226,7 +226,7 @@ void enqueue_head(Instance* I, hipStream_t s, const float* xin, int from_prompt_
   }
   if (I->runs(LL_KC_SAMPLE)) {
     ProfScope ps(I, s, LL_KC_SAMPLE);
-    hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(SMP_THREADS), 0, s, I->at<float>(I->L.amax_val),
+    hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(SMP_THREADS), SMP_Z_WORDS * 4, s, I->at<float>(I->L.amax_val),
                        I->at<int>(I->L.amax_idx), I->L.lm_wgs, I->at<float>(I->L.logits), c.vocab,
                        I->at<SampleCfg>(I->L.sample_cfg), I->state(), I->dev_ring, I->ring_size, prefill);
   }
@@ -654,6 +654,9 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipMemset(I->at<char>(L.zeros), 0, 256), "hipMemset(zeros)")) return bail(rc);
   if (!hip_or_bail(hipMemset(I->at<char>(L.sample_cfg), 0, sizeof(SampleCfg)), "hipMemset(sampling)"))
     return bail(rc);                                           // inv_temp = 0: greedy
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&sample_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, SMP_Z_WORDS * 4),
+                   "hipFuncSetAttribute(sample)")) return bail(rc);
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128, 3>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128, 3)),
                    "hipFuncSetAttribute(gemm 128)")) return bail(rc);

@@ -23,6 +23,7 @@
 #define SMP_THREADS 1024
 #define SMP_PER 32                               // consecutive tokens per thread
 #define SMP_MAX_VOCAB (SMP_THREADS * SMP_PER)
+#define SMP_Z_WORDS (SMP_THREADS * (SMP_PER + 1))   // dynamic LDS of sample_kernel, in 4-byte words
 
 struct SampleCfg {
   float inv_temp;      // float(1 / T); 0 selects greedy argmax
@@ -51,22 +52,167 @@ __device__ __forceinline__ uint32_t order_key(float z) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-// Block-wide sums over SMP_THREADS threads; every thread gets the result.  `red` holds one
-// slot per wave; two barriers per call keep consecutive calls from overlapping.
-__device__ __forceinline__ float smp_block_sum(float v, float* red) {
-  v = wave_sum(v);
+__device__ __forceinline__ float key_to_float(uint32_t k) {
+  return __builtin_bit_cast(float, (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+// Block-wide sums of three values at once over SMP_THREADS threads; every thread gets the
+// results.  `red` holds two banks of 3 x 16 wave slots used alternately (`phase` counts the
+// calls), so one barrier per call is enough: a bank is rewritten only two calls later, and
+// nobody can be two barriers ahead of a thread that still reads it.
+struct Sum3 { float a, b, c; };
+__device__ __forceinline__ Sum3 smp_block_sum3(float a, float b, float c, float* red, int& phase) {
+  constexpr int NW = SMP_THREADS / 64;
+  a = wave_sum(a);
+  b = wave_sum(b);
+  c = wave_sum(c);
   const int tid = threadIdx.x;
-  if ((tid & 63) == 0) red[tid >> 6] = v;
+  float* bank = red + (phase & 1) * 3 * NW;
+  ++phase;
+  if ((tid & 63) == 0) { bank[tid >> 6] = a; bank[NW + (tid >> 6)] = b; bank[2 * NW + (tid >> 6)] = c; }
   __syncthreads();
-  float s = 0.f;
+  Sum3 s = {0.f, 0.f, 0.f};
 #pragma unroll
-  for (int w = 0; w < SMP_THREADS / 64; ++w) s += red[w];
-  __syncthreads();
+  for (int w = 0; w < NW; ++w) { s.a += bank[w]; s.b += bank[NW + w]; s.c += bank[2 * NW + w]; }
   return s;
 }
-__device__ __forceinline__ int smp_block_sum_int(int v, float* red) {
-  // counts stay below 2^24, so they are exact in the float lanes of the wave reduction
-  return (int)(smp_block_sum((float)v, red) + 0.5f);
+__device__ __forceinline__ float smp_block_sum(float v, float* red, int& phase) {
+  return smp_block_sum3(v, 0.f, 0.f, red, phase).a;
+}
+// counts stay below 2^24, so they are exact in the float lanes of the reduction
+__device__ __forceinline__ int smp_block_sum_int(int v, float* red, int& phase) {
+  return (int)(smp_block_sum(v, red, phase) + 0.5f);
+}
+__device__ __forceinline__ float smp_block_max(float m, float* red, int& phase) {
+  constexpr int NW = SMP_THREADS / 64;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+  const int tid = threadIdx.x;
+  float* bank = red + (phase & 1) * 3 * NW;
+  ++phase;
+  if ((tid & 63) == 0) bank[tid >> 6] = m;
+  __syncthreads();
+  m = bank[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) m = fmaxf(m, bank[w]);
+  return m;
+}
+
+// Exclusive prefix sum over the threads in thread order (and the grand total), one barrier:
+// shuffle scan inside each wave, then every thread adds the totals of the waves before its own,
+// always in the same order, so the result is reproducible.
+__device__ __forceinline__ float smp_block_scan_excl(float v, float* red, int& phase, float* total) {
+  constexpr int NW = SMP_THREADS / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float incl = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const float up = __shfl_up(incl, off);
+    if (lane >= off) incl += up;
+  }
+  float* bank = red + (phase & 1) * 3 * NW;
+  ++phase;
+  if (lane == 63) bank[wave] = incl;
+  __syncthreads();
+  float before = 0.f, all = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    if (w < wave) before += bank[w];
+    all += bank[w];
+  }
+  *total = all;
+  const float prev = __shfl_up(incl, 1);
+  return before + (lane > 0 ? prev : 0.f);
+}
+
+// Nucleus cut and draw over PER kept-or-dropped slots per thread; slot j of a thread is token
+// id0 + j and thread order is index order.  Dropped slots have key 0 and e 0.
+template <int PER>
+__device__ __forceinline__ int smp_nucleus_and_draw(uint32_t (&key)[PER], float (&e)[PER], int id0, float top_p,
+                                                    float u, float* red, int& phase, int* found) {
+  const int tid = threadIdx.x;
+  auto ties_before = [&](uint32_t at) {
+    int mine = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) mine += key[j] == at;
+    float all;
+    return (int)(smp_block_scan_excl((float)mine, red, phase, &all) + 0.5f);   // counts < 2^24: exact
+  };
+  // top-p: largest key whose upper set holds top_p of the mass, ties by index order
+  if (top_p < 1.f) {
+    float mine = 0.f;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) mine += e[j];
+    const float want = top_p * smp_block_sum(mine, red, phase);
+    uint32_t prefix = 0u;
+    for (int bit = 31; bit >= 1; bit -= 2) {      // two bits per pass: three candidate prefixes, one reduction
+      const uint32_t c1 = prefix | (1u << (bit - 1)), c2 = prefix | (2u << (bit - 1)), c3 = prefix | (3u << (bit - 1));
+      float m1 = 0.f, m2 = 0.f, m3 = 0.f;
+#pragma unroll
+      for (int j = 0; j < PER; ++j) {
+        m1 += key[j] >= c1 ? e[j] : 0.f;
+        m2 += key[j] >= c2 ? e[j] : 0.f;
+        m3 += key[j] >= c3 ? e[j] : 0.f;
+      }
+      const Sum3 m = smp_block_sum3(m1, m2, m3, red, phase);
+      prefix = m.c >= want ? c3 : m.b >= want ? c2 : m.a >= want ? c1 : prefix;
+    }
+    if (prefix != 0u) {                            // prefix = 0: rounding left the total below the target, keep all
+      float above = 0.f, etau = 0.f;
+#pragma unroll
+      for (int j = 0; j < PER; ++j) {
+        above += key[j] > prefix ? e[j] : 0.f;
+        if (key[j] == prefix) etau = e[j];
+      }
+      above = smp_block_sum(above, red, phase);
+      etau = smp_block_max(etau, red, phase);      // every tie has the same e; take it from whichever thread holds one
+      int n_tie = (int)ceilf((want - above) / etau);
+      if (n_tie < 1) n_tie = 1;
+      int seen = ties_before(prefix);
+#pragma unroll
+      for (int j = 0; j < PER; ++j) {
+        bool in = key[j] > prefix;
+        if (key[j] == prefix) { in = seen < n_tie; ++seen; }
+        if (!in) { key[j] = 0u; e[j] = 0.f; }
+      }
+    }
+  }
+
+  // the draw: running sum of e in index order against u * total
+  float mine = 0.f;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) mine += e[j];
+  if (tid == 0) *found = 0x7fffffff;
+  float total;
+  const float run0 = smp_block_scan_excl(mine, red, phase, &total);   // (its barrier also publishes *found)
+  const float target = u * total;
+  // every thread continues the walk from the running sum in front of its range; the lowest
+  // token whose running sum exceeds the target wins, exactly as in a sequential walk
+  {
+    float run = run0;
+    int pick = 0x7fffffff;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      if (e[j] > 0.f) {
+        run += e[j];
+        if (pick == 0x7fffffff && run > target) pick = id0 + j;
+      }
+    }
+    if (pick != 0x7fffffff) atomicMin(found, pick);
+  }
+  __syncthreads();
+  if (*found == 0x7fffffff) {
+    // rounding left no running sum above the target: the last kept token
+    __syncthreads();
+    if (tid == 0) *found = -1;
+    __syncthreads();
+    int last = -1;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) if (e[j] > 0.f) last = id0 + j;
+    if (last >= 0) atomicMax(found, last);
+    __syncthreads();
+  }
+  return *found < 0 ? 0 : *found;
 }
 
 //   prefill = 1: pos := n_prompt, steps := 1, ring[0] := token (draw index 0)
@@ -77,10 +223,12 @@ __global__ __launch_bounds__(SMP_THREADS) void sample_kernel(const float* __rest
                                                              const SampleCfg* __restrict__ cfg,
                                                              DevState* st, int* host_ring, int ring_size,
                                                              int prefill) {
+  extern __shared__ float smp_z[];     // SMP_Z_WORDS words, used by the stochastic path only
   __shared__ float sv[SMP_THREADS];
   __shared__ int si[SMP_THREADS];
-  __shared__ float red[SMP_THREADS / 64];
-  __shared__ float scan[SMP_THREADS];
+  __shared__ uint32_t sk[SMP_THREADS];
+  __shared__ float red[2 * 3 * (SMP_THREADS / 64)];
+  int phase = 0;
   __shared__ int found;
   const int tid = threadIdx.x;
   const float inv_temp = cfg->inv_temp;
@@ -109,172 +257,104 @@ __global__ __launch_bounds__(SMP_THREADS) void sample_kernel(const float* __rest
     tok = si[0];
     if (tok == 0x7fffffff) tok = 0;   // every logit NaN: still a valid id
   } else {
-    // ---- stochastic: thread t holds tokens 32 t .. 32 t + 31
+    // ---- stochastic: thread t holds tokens 32 t .. 32 t + 31.  The logits are read once, coalesced,
+    // into LDS rows of 32 padded to 33 words, from which a thread takes its row without bank conflicts
+    // (read straight from global memory, every load instruction of a wave would touch 64 cache lines).
+    for (int i = tid; i < vocab; i += SMP_THREADS) smp_z[i + (i >> 5)] = logits[i];
+    __syncthreads();
     const int base = tid * SMP_PER;
     uint32_t key[SMP_PER];
     float zmax = -INFINITY;
 #pragma unroll
     for (int j = 0; j < SMP_PER; ++j) {
       const int i = base + j;
-      const float z = i < vocab ? __fmul_rn(logits[i], inv_temp) + 0.f : 0.f;   // + 0: -0 and +0 are one value
+      const float z = i < vocab ? __fmul_rn(smp_z[base + tid + j], inv_temp) + 0.f : 0.f;   // + 0: -0 and +0 are one value
       key[j] = i < vocab ? order_key(z) : 0u;
       if (i < vocab) zmax = fmaxf(zmax, z);
     }
-    // block max through the sum helper's storage: max is exact in any order
-    {
-      float m = zmax;
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-      if ((tid & 63) == 0) red[tid >> 6] = m;
-      __syncthreads();
-      m = red[0];
-#pragma unroll
-      for (int w = 1; w < SMP_THREADS / 64; ++w) m = fmaxf(m, red[w]);
-      __syncthreads();
-      zmax = m;
-    }
+    zmax = smp_block_max(zmax, red, phase);
 
     // (1) top-k: the k-th largest key by bisection, then the ties at that key by index order
     const int top_k = cfg->top_k;
     uint32_t cut = 1u;          // candidates: key > cut, or key == cut among the first tie_take ties
     int tie_take = 0x7fffffff;  // (cut = 1 with all ties taken keeps every real token: keys are >= 0x007FFFFF)
-    if (top_k >= 1 && top_k < vocab) {
+    const bool cutting = top_k >= 1 && top_k < vocab;
+    if (cutting) {
+      // two bits per pass; a wave counts with ballots, so an element costs one compare per candidate prefix
+      constexpr int NW = SMP_THREADS / 64;
       uint32_t prefix = 0u;
-      for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t c = prefix | (1u << bit);
-        int n = 0;
+      for (int bit = 31; bit >= 1; bit -= 2) {
+        const uint32_t c1 = prefix | (1u << (bit - 1)), c2 = prefix | (2u << (bit - 1)), c3 = prefix | (3u << (bit - 1));
+        int n1 = 0, n2 = 0, n3 = 0;
 #pragma unroll
-        for (int j = 0; j < SMP_PER; ++j) n += key[j] >= c;
-        if (smp_block_sum_int(n, red) >= top_k) prefix = c;
+        for (int j = 0; j < SMP_PER; ++j) {
+          n1 += __builtin_popcountll(__ballot(key[j] >= c1));
+          n2 += __builtin_popcountll(__ballot(key[j] >= c2));
+          n3 += __builtin_popcountll(__ballot(key[j] >= c3));
+        }
+        int* bank = reinterpret_cast<int*>(red) + (phase & 1) * 3 * NW;
+        ++phase;
+        if ((tid & 63) == 0) { bank[tid >> 6] = n1; bank[NW + (tid >> 6)] = n2; bank[2 * NW + (tid >> 6)] = n3; }
+        __syncthreads();
+        int t1 = 0, t2 = 0, t3 = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) { t1 += bank[w]; t2 += bank[NW + w]; t3 += bank[2 * NW + w]; }
+        prefix = t3 >= top_k ? c3 : t2 >= top_k ? c2 : t1 >= top_k ? c1 : prefix;
       }
       cut = prefix;
       int gt = 0;
 #pragma unroll
       for (int j = 0; j < SMP_PER; ++j) gt += key[j] > cut;
-      tie_take = top_k - smp_block_sum_int(gt, red);
+      tie_take = top_k - smp_block_sum_int(gt, red, phase);
     }
-    // exclusive count of ties before this thread, in index order
-    auto ties_before = [&](uint32_t at) {
-      int mine = 0;
-#pragma unroll
-      for (int j = 0; j < SMP_PER; ++j) mine += key[j] == at;
-      scan[tid] = (float)mine;
-      __syncthreads();
-      for (int off = 1; off < SMP_THREADS; off <<= 1) {
-        const float add = tid >= off ? scan[tid - off] : 0.f;
-        __syncthreads();
-        scan[tid] += add;
-        __syncthreads();
-      }
-      const int before = (int)(scan[tid] + 0.5f) - mine;
-      __syncthreads();
-      return before;
-    };
     float e[SMP_PER];
+    int kept = 0;
     {
-      int seen = (tie_take != 0x7fffffff) ? ties_before(cut) : 0;
+      int seen = 0;
+      if (cutting) {
+        int mine = 0;
+#pragma unroll
+        for (int j = 0; j < SMP_PER; ++j) mine += key[j] == cut;
+        float all;
+        seen = (int)(smp_block_scan_excl((float)mine, red, phase, &all) + 0.5f);   // ties before this thread
+      }
 #pragma unroll
       for (int j = 0; j < SMP_PER; ++j) {
         bool in = key[j] > cut;
         if (key[j] == cut && key[j] != 0u) { in = seen < tie_take; ++seen; }
         if (!in) key[j] = 0u;                       // dropped tokens leave the key space
-        const float z = (base + j) < vocab ? __fmul_rn(logits[base + j], inv_temp) + 0.f : 0.f;
-        e[j] = in ? expf(z - zmax) : 0.f;
+        e[j] = in ? expf(key_to_float(key[j]) - zmax) : 0.f;
+        kept += in;
       }
     }
-
-    // (2) top-p: largest key whose upper set holds top_p of the mass, ties by index order
-    const float top_p = cfg->top_p;
-    if (top_p < 1.f) {
-      float mine = 0.f;
-#pragma unroll
-      for (int j = 0; j < SMP_PER; ++j) mine += e[j];
-      const float want = top_p * smp_block_sum(mine, red);
-      uint32_t prefix = 0u;
-      for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t c = prefix | (1u << bit);
-        float m = 0.f;
-#pragma unroll
-        for (int j = 0; j < SMP_PER; ++j) m += key[j] >= c ? e[j] : 0.f;
-        if (smp_block_sum(m, red) >= want) prefix = c;
-      }
-      if (prefix != 0u) {                            // prefix = 0: rounding left the total below the target, keep all
-        float above = 0.f, etau = 0.f;
-#pragma unroll
-        for (int j = 0; j < SMP_PER; ++j) {
-          above += key[j] > prefix ? e[j] : 0.f;
-          if (key[j] == prefix) etau = e[j];
-        }
-        above = smp_block_sum(above, red);
-        // every tie has the same e; take it from whichever thread holds one
-        {
-          float m = etau;
-#pragma unroll
-          for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-          if ((tid & 63) == 0) red[tid >> 6] = m;
-          __syncthreads();
-          m = red[0];
-#pragma unroll
-          for (int w = 1; w < SMP_THREADS / 64; ++w) m = fmaxf(m, red[w]);
-          __syncthreads();
-          etau = m;
-        }
-        int n_tie = (int)ceilf((want - above) / etau);
-        if (n_tie < 1) n_tie = 1;
-        int seen = ties_before(prefix);
-#pragma unroll
-        for (int j = 0; j < SMP_PER; ++j) {
-          bool in = key[j] > prefix;
-          if (key[j] == prefix) { in = seen < n_tie; ++seen; }
-          if (!in) { key[j] = 0u; e[j] = 0.f; }
-        }
-      }
-    }
-
-    // (3) the draw: running sum of e in index order against u * total
-    float mine = 0.f;
-#pragma unroll
-    for (int j = 0; j < SMP_PER; ++j) mine += e[j];
-    scan[tid] = mine;
-    if (tid == 0) found = 0x7fffffff;
-    __syncthreads();
-    for (int off = 1; off < SMP_THREADS; off <<= 1) {
-      const float add = tid >= off ? scan[tid - off] : 0.f;
-      __syncthreads();
-      scan[tid] += add;
-      __syncthreads();
-    }
-    const float total = scan[SMP_THREADS - 1];
     uint32_t ctr[4] = {(uint32_t)(prefill ? 0 : st->steps), 0u, 0u, 0u};
     philox4x32_10(ctr, cfg->seed_lo, cfg->seed_hi);
-    const float target = (float)(ctr[0] >> 8) * (1.0f / 16777216.0f) * total;
-    // every thread continues the walk from the running sum in front of its range; the lowest
-    // token whose running sum exceeds the target wins, exactly as in a sequential walk
-    {
-      float run = tid > 0 ? scan[tid - 1] : 0.f;
-      int pick = 0x7fffffff;
+    const float u = (float)(ctr[0] >> 8) * (1.0f / 16777216.0f);
+
+    // (2) nucleus and draw.  After a top-k cut to at most one candidate per thread the survivors are
+    // packed, in index order, one per thread, and the remaining passes cost one element instead of 32.
+    if (cutting && top_k <= SMP_THREADS) {
+      float all;
+      int at = (int)(smp_block_scan_excl((float)kept, red, phase, &all) + 0.5f);
 #pragma unroll
       for (int j = 0; j < SMP_PER; ++j) {
-        if (e[j] > 0.f) {
-          run += e[j];
-          if (pick == 0x7fffffff && run > target) pick = base + j;
+        if (key[j] != 0u) {
+          sk[at] = key[j];
+          sv[at] = e[j];
+          si[at] = base + j;
+          ++at;
         }
       }
-      if (pick != 0x7fffffff) atomicMin(&found, pick);
+      __syncthreads();
+      const int ncand = (int)(all + 0.5f);
+      uint32_t k1[1] = {tid < ncand ? sk[tid] : 0u};
+      float e1[1] = {tid < ncand ? sv[tid] : 0.f};
+      const int id = tid < ncand ? si[tid] : 0;
+      __syncthreads();
+      tok = smp_nucleus_and_draw<1>(k1, e1, id, cfg->top_p, u, red, phase, &found);
+    } else {
+      tok = smp_nucleus_and_draw<SMP_PER>(key, e, base, cfg->top_p, u, red, phase, &found);
     }
-    __syncthreads();
-    if (found == 0x7fffffff) {
-      // rounding left no running sum above the target: the last kept token
-      __syncthreads();
-      if (tid == 0) found = -1;
-      __syncthreads();
-      int last = -1;
-#pragma unroll
-      for (int j = 0; j < SMP_PER; ++j) if (e[j] > 0.f) last = base + j;
-      if (last >= 0) atomicMax(&found, last);
-      __syncthreads();
-    }
-    tok = found < 0 ? 0 : found;
   }
 
   if (tid == 0) {
