@@ -54,18 +54,27 @@ enum {
                               (same kernels, same order: isolates the dispatch cost the
                               paper's Sec. I-B / III-B attribute to per-kernel launches) */
   LL_FLAG_MULTIKERNEL = 2, /* decode step = graph of one kernel per fused operator (~160 nodes) */
-  LL_FLAG_PERSISTENT = 4   /* decode step = graph of ONE persistent kernel with in-kernel grid
+  LL_FLAG_PERSISTENT = 4,  /* decode step = graph of ONE persistent kernel with in-kernel grid
                               barriers (needs d_model <= 4096 and one resident workgroup per
                               CU; ll_init fails with LL_E_BAD_CONFIG otherwise).  With neither
                               of the two flags the library picks the faster one it has measured
                               for the 7B shape, currently the multi-kernel graph. */
+  LL_FLAG_PER_LENGTH_GRAPHS = 8
+                           /* the paper's own mechanism, kept as an ablation (Alg. 1, Sec. IV-A):
+                              one decode graph PER KV LENGTH in a rolling buffer of 8 with
+                              least-recently-used eviction; a miss captures before it replays,
+                              and the graph of the next length is captured by a second thread on
+                              a second stream while the current one replays.  Same kernels as
+                              the multi-kernel graph (they read the length from device memory);
+                              excludes LL_FLAG_EAGER and LL_FLAG_PERSISTENT. */
 };
 
 /* what ll_decode_step() replays, see ll_decode_mode() */
 enum {
   LL_MODE_PERSISTENT_GRAPH = 0,   /* graph of ONE persistent kernel with in-kernel grid barriers */
   LL_MODE_MULTIKERNEL_GRAPH = 1,  /* graph of one kernel per fused operator */
-  LL_MODE_EAGER = 2               /* the multi-kernel chain launched kernel by kernel */
+  LL_MODE_EAGER = 2,              /* the multi-kernel chain launched kernel by kernel */
+  LL_MODE_PER_LENGTH_GRAPHS = 3   /* the multi-kernel graph, captured once per KV length */
 };
 
 /* Model shape.  Constraints: n_heads * head_dim == d_model; head_dim is 64 or
@@ -159,6 +168,10 @@ int ll_decode_mode(void);
 const char *ll_last_error(void);
 
 /* ---- measurement and test hooks (not part of the four-call contract) ---- */
+
+/* Per-length graph mode: out4 = { replays that found their graph in the buffer, captures that
+ * blocked a step, captures overlapped with a replay, nanoseconds spent capturing }. */
+int ll_dbg_graph_stats(int64_t *out4);
 
 /* Logits [vocab] of the most recent prefill/decode step, copied to the host. */
 int ll_dbg_get_logits(float *host_out);

@@ -19,13 +19,14 @@ LL_E_WORKSPACE, LL_E_STATE, LL_E_HIP, LL_E_ALREADY_INIT = -5, -6, -7, -8
 LL_FLAG_EAGER = 1
 LL_FLAG_MULTIKERNEL = 2
 LL_FLAG_PERSISTENT = 4
-LL_MODE_PERSISTENT_GRAPH, LL_MODE_MULTIKERNEL_GRAPH, LL_MODE_EAGER = 0, 1, 2
+LL_FLAG_PER_LENGTH_GRAPHS = 8
+LL_MODE_PERSISTENT_GRAPH, LL_MODE_MULTIKERNEL_GRAPH, LL_MODE_EAGER, LL_MODE_PER_LENGTH_GRAPHS = 0, 1, 2, 3
 KERNEL_CLASSES = ("embed", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "sample")
 LAYER_KEYS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
 
 EXPORTS = ("ll_workspace_bytes", "ll_init", "ll_prefill", "ll_decode_step", "ll_decode_n", "ll_reset",
            "ll_set_sampling", "ll_shutdown", "ll_max_prompt", "ll_position", "ll_decode_mode", "ll_last_error", "ll_dbg_get_logits",
-           "ll_dbg_get_hidden", "ll_dbg_force_next_token", "ll_dbg_get_kv", "ll_dbg_profile_decode",
+           "ll_dbg_get_hidden", "ll_dbg_graph_stats", "ll_dbg_force_next_token", "ll_dbg_get_kv", "ll_dbg_profile_decode",
            "ll_dbg_time_decode", "ll_dbg_time_kernel_class", "ll_dbg_stream_copy", "ll_dbg_trace_decode")
 
 
@@ -84,6 +85,8 @@ def load():
     L.ll_last_error.argtypes = []
     L.ll_dbg_get_logits.restype = C.c_int
     L.ll_dbg_get_logits.argtypes = [C.POINTER(C.c_float)]
+    L.ll_dbg_graph_stats.restype = C.c_int
+    L.ll_dbg_graph_stats.argtypes = [C.POINTER(C.c_int64)]
     L.ll_dbg_get_hidden.restype = C.c_int
     L.ll_dbg_get_hidden.argtypes = [C.POINTER(C.c_float)]
     L.ll_dbg_force_next_token.restype = C.c_int
@@ -237,6 +240,12 @@ class Session:
         out = np.empty(self.cfg["vocab"], dtype=np.float32)
         _check(self.lib.ll_dbg_get_logits(out.ctypes.data_as(C.POINTER(C.c_float))))
         return out
+
+    def ll_dbg_graph_stats(self):
+        out = (C.c_int64 * 4)()
+        _check(self.lib.ll_dbg_graph_stats(out))
+        return dict(buffered_replays=out[0], blocking_captures=out[1], overlapped_captures=out[2],
+                    capture_ms=out[3] / 1e6)
 
     def ll_dbg_get_hidden(self):
         out = np.empty(self.cfg["d_model"], dtype=np.float32)

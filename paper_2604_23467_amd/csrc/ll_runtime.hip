@@ -8,6 +8,8 @@
 #include <cstdlib>
 #include <cstring>
 #include <algorithm>
+#include <chrono>
+#include <future>
 #include <string>
 #include <vector>
 
@@ -160,6 +162,16 @@ struct Instance {
   int mega_grid = 0;
   size_t mega_lds = 0;
   int mega_splits = 1;
+  // the paper's mechanism as an option: one decode graph per KV length in a rolling buffer
+  struct LenGraph { int len = -1; hipGraph_t graph = nullptr; hipGraphExec_t exec = nullptr; uint64_t used = 0; };
+  bool per_length = false;
+  std::vector<LenGraph> lg;      // at most kLenGraphBuffer entries
+  uint64_t lg_clock = 0;
+  hipStream_t cap_stream = nullptr;
+  std::future<int> lg_future;    // capture of the next length, running on a second thread
+  LenGraph lg_pending;
+  std::string lg_pending_err;
+  int64_t lg_stats[4] = {0, 0, 0, 0};   // replays of a buffered graph, blocking captures, overlapped captures, capture ns
   int only_class = -1;           // timing hook: launch only this kernel class of the decode chain
   bool runs(int klass) const { return only_class < 0 || only_class == klass; }
 
@@ -525,14 +537,18 @@ void enqueue_prefill(Instance* I, hipStream_t s, int Mb) {
   enqueue_head(I, s, X, 1, 1);
 }
 
-int capture(Instance* I, hipGraph_t* graph, hipGraphExec_t* exec, int prefill_bucket) {
-  HIPCHK(hipStreamBeginCapture(I->stream, hipStreamCaptureModeThreadLocal));
-  if (prefill_bucket) enqueue_prefill(I, I->stream, prefill_bucket);
-  else enqueue_decode(I, I->stream);
-  hipError_t e = hipStreamEndCapture(I->stream, graph);
+int capture_on(Instance* I, hipStream_t cs, hipGraph_t* graph, hipGraphExec_t* exec, int prefill_bucket) {
+  HIPCHK(hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal));
+  if (prefill_bucket) enqueue_prefill(I, cs, prefill_bucket);
+  else enqueue_decode(I, cs);
+  hipError_t e = hipStreamEndCapture(cs, graph);
   if (e != hipSuccess) return fail(LL_E_HIP, "hipStreamEndCapture: %s", hipGetErrorString(e));
   HIPCHK(hipGraphInstantiate(exec, *graph, nullptr, nullptr, 0));
   return LL_OK;
+}
+
+int capture(Instance* I, hipGraph_t* graph, hipGraphExec_t* exec, int prefill_bucket) {
+  return capture_on(I, I->stream, graph, exec, prefill_bucket);
 }
 
 int write_state(Instance* I, int pos, int next_token, int n_prompt, int steps) {
@@ -545,6 +561,14 @@ int write_state(Instance* I, int pos, int next_token, int n_prompt, int steps) {
 
 void destroy(Instance* I) {
   if (!I) return;
+  if (I->lg_future.valid()) (void)I->lg_future.get();
+  if (I->lg_pending.exec) (void)hipGraphExecDestroy(I->lg_pending.exec);
+  if (I->lg_pending.graph) (void)hipGraphDestroy(I->lg_pending.graph);
+  for (auto& e : I->lg) {
+    if (e.exec) (void)hipGraphExecDestroy(e.exec);
+    if (e.graph) (void)hipGraphDestroy(e.graph);
+  }
+  if (I->cap_stream) (void)hipStreamDestroy(I->cap_stream);
   if (I->dec_exec) (void)hipGraphExecDestroy(I->dec_exec);
   if (I->dec_graph) (void)hipGraphDestroy(I->dec_graph);
   for (auto e : I->pf_exec) if (e) (void)hipGraphExecDestroy(e);
@@ -557,7 +581,83 @@ void destroy(Instance* I) {
 
 bool eager(const Instance* I) { return (I->cfg.flags & LL_FLAG_EAGER) != 0; }
 
+// ---- one graph per KV length (Alg. 1; Sec. IV-A): rolling buffer, LRU eviction, the next length
+// captured by a second thread on a second stream while the current graph replays.  The kernels
+// read the length from the device state, so every one of these graphs is the same graph: what
+// this mode measures is what capturing per length costs.
+constexpr size_t kLenGraphBuffer = 8;
+
+Instance::LenGraph* lg_find(Instance* I, int len) {
+  for (auto& e : I->lg) if (e.len == len) return &e;
+  return nullptr;
+}
+
+// the stream is idle when this runs, so nothing that is evicted can still be executing
+void lg_insert(Instance* I, const Instance::LenGraph& ng) {
+  if (I->lg.size() >= kLenGraphBuffer) {
+    size_t victim = 0;
+    for (size_t i = 1; i < I->lg.size(); ++i) if (I->lg[i].used < I->lg[victim].used) victim = i;
+    (void)hipGraphExecDestroy(I->lg[victim].exec);
+    (void)hipGraphDestroy(I->lg[victim].graph);
+    I->lg[victim] = ng;
+  } else {
+    I->lg.push_back(ng);
+  }
+}
+
+int lg_capture(Instance* I, int len, Instance::LenGraph* out, std::string* err) {
+  const auto t0 = std::chrono::steady_clock::now();
+  out->len = len;
+  out->used = 0;
+  const int rc = capture_on(I, I->cap_stream, &out->graph, &out->exec, 0);
+  if (rc != LL_OK && err) *err = g_err;          // this thread's message, for the caller's thread
+  I->lg_stats[3] += std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - t0).count();
+  return rc;
+}
+
+int lg_join(Instance* I) {
+  if (!I->lg_future.valid()) return LL_OK;
+  const int rc = I->lg_future.get();
+  if (rc != LL_OK) {
+    I->lg_pending = Instance::LenGraph();
+    return fail(rc, "capture of the next length failed: %s", I->lg_pending_err.c_str());
+  }
+  lg_insert(I, I->lg_pending);
+  I->lg_pending = Instance::LenGraph();
+  return LL_OK;
+}
+
+int run_decode_steps_per_length(Instance* I, int k) {
+  for (int i = 0; i < k; ++i) {
+    const int len = I->pos + i;                  // cached positions when this step starts
+    Instance::LenGraph* e = lg_find(I, len);
+    if (e) {
+      ++I->lg_stats[0];
+    } else {
+      Instance::LenGraph ng;
+      const int rc = lg_capture(I, len, &ng, nullptr);
+      if (rc != LL_OK) return rc;
+      ++I->lg_stats[1];
+      lg_insert(I, ng);
+      e = lg_find(I, len);
+    }
+    e->used = ++I->lg_clock;
+    HIPCHK(hipGraphLaunch(e->exec, I->stream));
+    if (len + 1 < I->cfg.max_seq && !lg_find(I, len + 1)) {
+      ++I->lg_stats[2];
+      I->lg_future = std::async(std::launch::async, [I, len] {
+        return lg_capture(I, len + 1, &I->lg_pending, &I->lg_pending_err);
+      });
+    }
+    HIPCHK(hipStreamSynchronize(I->stream));     // the replay and the capture overlap here
+    const int rc = lg_join(I);
+    if (rc != LL_OK) return rc;
+  }
+  return LL_OK;
+}
+
 int run_decode_steps(Instance* I, int k) {
+  if (I->per_length) return run_decode_steps_per_length(I, k);
   for (int i = 0; i < k; ++i) {
     if (eager(I)) enqueue_decode(I, I->stream);
     else HIPCHK(hipGraphLaunch(I->dec_exec, I->stream));
@@ -681,6 +781,14 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
     std::string why;
     I->use_mega = mega_plan(I, &why);
     if (!I->use_mega) return bail(fail(LL_E_BAD_CONFIG, "ll_init: persistent kernel unavailable: %s", why.c_str()));
+  }
+  if (cfg->flags & LL_FLAG_PER_LENGTH_GRAPHS) {
+    if (cfg->flags & (LL_FLAG_EAGER | LL_FLAG_PERSISTENT))
+      return bail(fail(LL_E_BAD_CONFIG, "ll_init: LL_FLAG_PER_LENGTH_GRAPHS replays the multi-kernel graph; "
+                                        "it excludes LL_FLAG_EAGER and LL_FLAG_PERSISTENT"));
+    I->per_length = true;
+    if (!hip_or_bail(hipStreamCreateWithFlags(&I->cap_stream, hipStreamNonBlocking), "hipStreamCreate(capture)"))
+      return bail(rc);
   }
   if (!hip_or_bail(hipDeviceSynchronize(), "hipDeviceSynchronize")) return bail(rc);
 
@@ -840,7 +948,15 @@ int32_t ll_decode_step(void) { return ll_decode_n(1, nullptr); }
 int ll_decode_mode(void) {
   if (!g) return fail(LL_E_NOT_INIT, "ll_decode_mode: not initialised");
   if (g->cfg.flags & LL_FLAG_EAGER) return LL_MODE_EAGER;
+  if (g->per_length) return LL_MODE_PER_LENGTH_GRAPHS;
   return g->use_mega ? LL_MODE_PERSISTENT_GRAPH : LL_MODE_MULTIKERNEL_GRAPH;
+}
+
+int ll_dbg_graph_stats(int64_t* out4) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_dbg_graph_stats: not initialised");
+  if (!out4) return fail(LL_E_BAD_ARG, "ll_dbg_graph_stats: null output");
+  for (int i = 0; i < 4; ++i) out4[i] = g->lg_stats[i];
+  return LL_OK;
 }
 
 int ll_dbg_get_logits(float* host_out) {

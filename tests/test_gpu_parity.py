@@ -165,6 +165,36 @@ def test_graph_replay_equals_eager_and_decode_n(torch_cuda):
     assert max_abs(m[1], e[1]) < 1e-4 and max_abs(g[1], e[1]) < 1e-4 and max_abs(g[1], g[3]) < 1e-4
 
 
+def test_per_length_graph_buffer_replays_the_same_tokens(torch_cuda):
+    """The paper's mechanism (one graph per KV length, rolling buffer of 8, next length captured
+    while the current one replays) must generate what the single graph generates."""
+    from paper_2604_23467_amd import binding as b
+    cfg = wl.tiny_cfg(max_seq=64)
+    w = wl.make_weights_numpy(cfg, seed=3)
+    prompt = wl.make_tokens(12, cfg["vocab"], seed=9)
+    with _session(cfg, w) as s:
+        ref = [s.ll_prefill(prompt)] + [s.ll_decode_step() for _ in range(30)]
+    with _session(cfg, w, b.LL_FLAG_PER_LENGTH_GRAPHS) as s:
+        assert s.ll_decode_mode() == b.LL_MODE_PER_LENGTH_GRAPHS
+        got = [s.ll_prefill(prompt)] + [s.ll_decode_step() for _ in range(20)] + s.ll_decode_n(10).tolist()
+        st = s.ll_dbg_graph_stats()
+        # the first step captures its own graph; every later one finds the graph captured during the step before
+        assert got == ref and st["blocking_captures"] == 1 and st["overlapped_captures"] == 30
+        assert st["buffered_replays"] == 29 and st["capture_ms"] > 0
+        s.ll_reset()                       # lengths 12..19 left the 8-deep buffer long ago: the cycle restarts
+        again = [s.ll_prefill(prompt)] + [s.ll_decode_step() for _ in range(5)]
+        assert again == ref[:6] and s.ll_dbg_graph_stats()["blocking_captures"] == 2
+        s.ll_reset()
+        s.ll_prefill(prompt[:11])          # lengths 11.. : 11 is new, 12..17 are still buffered
+        s.ll_decode_n(4)
+        st2 = s.ll_dbg_graph_stats()
+        assert st2["blocking_captures"] == 3 and st2["overlapped_captures"] == 35
+    for bad in (b.LL_FLAG_PER_LENGTH_GRAPHS | b.LL_FLAG_EAGER, b.LL_FLAG_PER_LENGTH_GRAPHS | b.LL_FLAG_PERSISTENT):
+        with pytest.raises(b.LLError) as e:
+            _session(cfg, w, bad)
+        assert e.value.code == b.LL_E_BAD_CONFIG
+
+
 def test_prefill_matches_token_by_token_decode(torch_cuda, oracle32):
     """The MFMA prefill and the GEMV decode path are two implementations of the
     same layer: feeding the prompt through decode steps must give the same
