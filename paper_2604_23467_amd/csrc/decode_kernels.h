@@ -122,27 +122,10 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
   const float* xin = a.xin;
   if (MODE == GM_LMHEAD && a.x_row_from_prompt) xin += (size_t)(a.st->n_prompt - 1) * K;
 
-  // O projection: its input is the merge of the attention kernel's S partials per
-  // head.  First the per-partial weights exp(m_s - M) / sum_s l_s exp(m_s - M) ...
-  float* wn = red + 8;
-  if (MODE == GM_ORES && a.attn_part) {
-    const int PS = ATTN_PART_STRIDE(a.head_dim), S = a.attn_splits;
-    for (int head = tid; head < K / a.head_dim; head += LL_WG) {
-      const float* hp = a.attn_part + (size_t)head * S * PS;
-      float M = -INFINITY, L = 0.f;
-      for (int sp = 0; sp < S; ++sp) M = fmaxf(M, hp[sp * PS]);
-      for (int sp = 0; sp < S; ++sp) {
-        const float mi = hp[sp * PS];
-        const float w = (mi > -INFINITY) ? __expf(mi - M) : 0.f;
-        wn[head * S + sp] = w;
-        L += hp[sp * PS + 1] * w;
-      }
-      const float rl = 1.0f / L;
-      for (int sp = 0; sp < S; ++sp) wn[head * S + sp] *= rl;
-    }
-    __syncthreads();
-  }
-
+  // O projection: its input is the merge of the attention kernel's (at most two) partials per
+  // head, o = sum_s w_s acc_s with w_s = exp(m_s - M) / sum_s l_s exp(m_s - M).  Every thread
+  // fetches the (m, l) headers next to the accumulators it stages and forms the weights
+  // itself, so the whole merge costs one L2 round trip and no extra barrier.
   // ... then the staging proper, four float4 per thread and pass with all of a
   // pass's loads issued before any is used (one L2 round trip, not four).
   float ss = 0.f;
@@ -151,6 +134,7 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
     f4 v[SU], v2[SU];
     h4 g[SU];
     float w0[SU], w1[SU];
+    float2 hd0[SU], hd1[SU];     // (m, l) of the two partials
 #pragma unroll
     for (int j = 0; j < SU; ++j) {
       const int k = (i0 + j * LL_WG) * 4;
@@ -160,15 +144,17 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
       w0[j] = w1[j] = 0.f;
       if (k < K) {
         if (MODE == GM_ORES && a.attn_part) {
-          // o[k..k+3] of head k / head_dim: the (at most two) partial accumulators weighted by wn
+          // o[k..k+3] of head k / head_dim: the (at most two) partial accumulators
           const int HD = a.head_dim, PS = ATTN_PART_STRIDE(HD);
           const int head = k / HD, dcol = k - head * HD;
-          const float* hp = a.attn_part + (size_t)head * a.attn_splits * PS + 4 + dcol;
+          const float* hb = a.attn_part + (size_t)head * a.attn_splits * PS;
+          const float* hp = hb + 4 + dcol;
           v[j] = *reinterpret_cast<const f4*>(hp);
-          w0[j] = wn[head * a.attn_splits];
+          hd0[j] = *reinterpret_cast<const float2*>(hb);
+          hd1[j] = make_float2(-INFINITY, 0.f);
           if (a.attn_splits > 1) {
             v2[j] = *reinterpret_cast<const f4*>(hp + PS);
-            w1[j] = wn[head * a.attn_splits + 1];
+            hd1[j] = *reinterpret_cast<const float2*>(hb + PS);
           }
         } else {
           v[j] = *reinterpret_cast<const f4*>(xin + k);
@@ -181,7 +167,13 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
       const int k = (i0 + j * LL_WG) * 4;
       if (k >= nchp * 512) continue;
       f4 t = v[j];
-      if (MODE == GM_ORES && a.attn_part) {
+      if (MODE == GM_ORES && a.attn_part && k < K) {
+        const float M = fmaxf(hd0[j].x, hd1[j].x);
+        const float e0 = (hd0[j].x > -INFINITY) ? __expf(hd0[j].x - M) : 0.f;
+        const float e1 = (hd1[j].x > -INFINITY) ? __expf(hd1[j].x - M) : 0.f;
+        const float rl = 1.0f / (hd0[j].y * e0 + hd1[j].y * e1);
+        w0[j] = e0 * rl;
+        w1[j] = e1 * rl;
         t[0] = v[j][0] * w0[j] + v2[j][0] * w1[j];
         t[1] = v[j][1] * w0[j] + v2[j][1] * w1[j];
         t[2] = v[j][2] * w0[j] + v2[j][2] * w1[j];
