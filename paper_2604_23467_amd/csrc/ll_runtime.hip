@@ -186,7 +186,7 @@ Instance* g = nullptr;
 size_t gemv_lds_bytes(int K) {
   const int nch = (K + 511) / 512;
   const int nchp = (nch + kGemvU - 1) / kGemvU * kGemvU;
-  return ((size_t)nchp * 512 + 8 + 512) * sizeof(float);   // input vector, reduction scratch, attention merge weights
+  return ((size_t)nchp * 512 + 8) * sizeof(float);   // input vector, reduction scratch
 }
 
 struct ProfScope {
