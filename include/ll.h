@@ -155,7 +155,9 @@ int ll_set_sampling(float temperature, int32_t top_k, float top_p, uint64_t seed
 /* Destroys graphs and host buffers; caller memory is untouched. */
 int ll_shutdown(void);
 
-/* Longest prompt ll_prefill() accepts for the current instance. */
+/* Longest prompt ll_prefill() accepts for the current instance: max_seq - 1.  Prompts of more
+ * than 512 tokens are fed through the prefill kernels in chunks of 512 (the "longer contexts"
+ * direction of Sec. VI-E); the chunking is invisible to the caller. */
 int32_t ll_max_prompt(void);
 
 /* Number of cached positions (0 when empty), or LL_E_NOT_INIT. */

@@ -96,8 +96,8 @@ Layout make_layout(const ll_config& c) {
   const size_t d = c.d_model, F = c.ffn_hidden, V = c.vocab;
   L.attn_splits = (c.n_heads * 2 <= 512) ? 2 : 1;   // two 1024-thread workgroups per head
   L.lm_wgs = gemv_grid((c.vocab + 1) / 2);
-  L.max_prompt = c.max_seq - 1 < kMaxPromptBucket ? c.max_seq - 1 : kMaxPromptBucket;
-  L.mb_max = prompt_bucket(L.max_prompt);
+  L.max_prompt = c.max_seq - 1;                   // longer than the largest bucket: fed in chunks
+  L.mb_max = prompt_bucket(L.max_prompt < kMaxPromptBucket ? L.max_prompt : kMaxPromptBucket);
   L.kv_layer_halves = (size_t)c.n_heads * c.max_seq * c.head_dim;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
@@ -148,6 +148,9 @@ struct Instance {
   std::vector<int> pf_buckets;
   std::vector<hipGraph_t> pf_graph;
   std::vector<hipGraphExec_t> pf_exec;
+  hipGraph_t pf_body_graph = nullptr;       // largest bucket without LM head and sampling: all but the last chunk
+  hipGraphExec_t pf_body_exec = nullptr;    // of a prompt longer than that bucket
+  int last_chunk_rows = 0;                  // rows of the most recent prefill's last chunk
   int* host_ring = nullptr;      // pinned, device-visible; kernels write generated ids here
   int* dev_ring = nullptr;       // device address of host_ring
   int ring_size = 0;
@@ -455,7 +458,7 @@ void launch_skinny(Instance* I, hipStream_t s, SkinnyArgs a, int Mb) {
 
 // Prompts of at most 32 tokens: five kernels per layer, every projection streams its weights
 // once and finishes its own epilogue; the norms ride on the projections around them.
-void enqueue_prefill_skinny(Instance* I, hipStream_t s, int Mb) {
+void enqueue_prefill_skinny(Instance* I, hipStream_t s, int Mb, bool with_head) {
   const ll_config& c = I->cfg;
   const int d = c.d_model, F = c.ffn_hidden;
   float* X = I->at<float>(I->L.pf_x);
@@ -495,11 +498,11 @@ void enqueue_prefill_skinny(Instance* I, hipStream_t s, int Mb) {
     a.Xh_next = Xn; a.ss_out = ss_attn; a.ss_zero = ss_ffn;
     launch_skinny<SK_RES>(I, s, a, Mb);
   }
-  enqueue_head(I, s, X, 1, 1);
+  if (with_head) enqueue_head(I, s, X, 1, 1);
 }
 
-void enqueue_prefill(Instance* I, hipStream_t s, int Mb) {
-  if (Mb <= 32 && I->skinny) return enqueue_prefill_skinny(I, s, Mb);
+void enqueue_prefill(Instance* I, hipStream_t s, int Mb, bool with_head = true) {
+  if (Mb <= 32 && I->skinny) return enqueue_prefill_skinny(I, s, Mb, with_head);
   const ll_config& c = I->cfg;
   const int d = c.d_model, F = c.ffn_hidden;
   float* X = I->at<float>(I->L.pf_x);
@@ -534,12 +537,13 @@ void enqueue_prefill(Instance* I, hipStream_t s, int Mb) {
                        s, GU, I->state(), Hm, F);
     launch_gemm(I, s, Hm, W.w_down, nullptr, nullptr, 1, X, d, d, F, Mb, false);
   }
-  enqueue_head(I, s, X, 1, 1);
+  if (with_head) enqueue_head(I, s, X, 1, 1);
 }
 
-int capture_on(Instance* I, hipStream_t cs, hipGraph_t* graph, hipGraphExec_t* exec, int prefill_bucket) {
+int capture_on(Instance* I, hipStream_t cs, hipGraph_t* graph, hipGraphExec_t* exec, int prefill_bucket,
+               bool with_head = true) {
   HIPCHK(hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal));
-  if (prefill_bucket) enqueue_prefill(I, cs, prefill_bucket);
+  if (prefill_bucket) enqueue_prefill(I, cs, prefill_bucket, with_head);
   else enqueue_decode(I, cs);
   hipError_t e = hipStreamEndCapture(cs, graph);
   if (e != hipSuccess) return fail(LL_E_HIP, "hipStreamEndCapture: %s", hipGetErrorString(e));
@@ -571,6 +575,8 @@ void destroy(Instance* I) {
   if (I->cap_stream) (void)hipStreamDestroy(I->cap_stream);
   if (I->dec_exec) (void)hipGraphExecDestroy(I->dec_exec);
   if (I->dec_graph) (void)hipGraphDestroy(I->dec_graph);
+  if (I->pf_body_exec) (void)hipGraphExecDestroy(I->pf_body_exec);
+  if (I->pf_body_graph) (void)hipGraphDestroy(I->pf_body_graph);
   for (auto e : I->pf_exec) if (e) (void)hipGraphExecDestroy(e);
   for (auto gr : I->pf_graph) if (gr) (void)hipGraphDestroy(gr);
   if (I->host_ring) (void)hipHostFree(I->host_ring);
@@ -819,6 +825,9 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
     I->pf_exec.assign(I->pf_buckets.size(), nullptr);
     for (size_t i = 0; i < I->pf_buckets.size(); ++i)
       if ((rc = capture(I, &I->pf_graph[i], &I->pf_exec[i], I->pf_buckets[i])) != LL_OK) return bail(rc);
+    if (L.max_prompt > L.mb_max &&
+        (rc = capture_on(I, I->stream, &I->pf_body_graph, &I->pf_body_exec, L.mb_max, false)) != LL_OK)
+      return bail(rc);
   }
   if ((rc = write_state(I, 0, 0, 0, 0)) != LL_OK) return bail(rc);
   if (!hip_or_bail(hipStreamSynchronize(I->stream), "init sync")) return bail(rc);
@@ -896,24 +905,35 @@ int32_t ll_prefill(const int32_t* tokens, int32_t n) {
     if (tokens[i] < 0 || tokens[i] >= I->cfg.vocab)
       return fail(LL_E_BAD_ARG, "ll_prefill: tokens[%d] = %d outside [0, %d)", i, tokens[i], I->cfg.vocab);
 
-  const int Mb = (I->skinny && n <= 32) ? (n <= 16 ? 16 : 32) : prompt_bucket(n);
-  // prompt ids and the state block travel in one pinned staging buffer
+  // prompt ids and the state block travel in one pinned staging buffer.  A prompt longer than the
+  // largest bucket goes through in chunks of that size: every chunk but the last runs the layers
+  // only (its rows just fill the KV cache), the last one also produces the first token.
   DevState* hs = reinterpret_cast<DevState*>(I->host_stage);
   int* htok = reinterpret_cast<int*>(reinterpret_cast<char*>(I->host_stage) + sizeof(DevState));
-  memset(hs, 0, sizeof(DevState));
-  hs->n_prompt = n;
-  memcpy(htok, tokens, (size_t)n * 4);
-  HIPCHK(hipMemcpyAsync(I->state(), hs, sizeof(DevState), hipMemcpyHostToDevice, I->stream));
-  HIPCHK(hipMemcpyAsync(I->at<int>(I->L.tokens), htok, (size_t)n * 4, hipMemcpyHostToDevice, I->stream));
-  if (eager(I)) {
-    enqueue_prefill(I, I->stream, Mb);
-    HIPCHK(hipGetLastError());
-  } else {
-    size_t bi = 0;
-    while (I->pf_buckets[bi] != Mb) ++bi;
-    HIPCHK(hipGraphLaunch(I->pf_exec[bi], I->stream));
+  for (int p0 = 0; p0 < n;) {
+    const int m = n - p0 > I->L.mb_max ? I->L.mb_max : n - p0;
+    const bool last = p0 + m == n;
+    const int Mb = (I->skinny && m <= 32) ? (m <= 16 ? 16 : 32) : prompt_bucket(m);
+    memset(hs, 0, sizeof(DevState));
+    hs->pos = p0;
+    hs->n_prompt = m;
+    memcpy(htok, tokens + p0, (size_t)m * 4);
+    HIPCHK(hipMemcpyAsync(I->state(), hs, sizeof(DevState), hipMemcpyHostToDevice, I->stream));
+    HIPCHK(hipMemcpyAsync(I->at<int>(I->L.tokens), htok, (size_t)m * 4, hipMemcpyHostToDevice, I->stream));
+    if (eager(I)) {
+      enqueue_prefill(I, I->stream, Mb, last);
+      HIPCHK(hipGetLastError());
+    } else if (!last) {
+      HIPCHK(hipGraphLaunch(I->pf_body_exec, I->stream));
+    } else {
+      size_t bi = 0;
+      while (I->pf_buckets[bi] != Mb) ++bi;
+      HIPCHK(hipGraphLaunch(I->pf_exec[bi], I->stream));
+    }
+    HIPCHK(hipStreamSynchronize(I->stream));       // the staging buffer is reused by the next chunk
+    I->last_chunk_rows = m;
+    p0 += m;
   }
-  HIPCHK(hipStreamSynchronize(I->stream));
   I->pos = n;
   I->steps = 1;
   I->last_was_prefill = true;
@@ -973,7 +993,7 @@ int ll_dbg_get_hidden(float* host_out) {
   if (g->pos == 0) return fail(LL_E_STATE, "ll_dbg_get_hidden: no step has run");
   HIPCHK(hipStreamSynchronize(g->stream));
   const float* src = g->last_was_prefill
-                         ? g->at<float>(g->L.pf_x) + (size_t)(g->pos - 1) * g->cfg.d_model
+                         ? g->at<float>(g->L.pf_x) + (size_t)(g->last_chunk_rows - 1) * g->cfg.d_model
                          : g->at<float>(g->L.x);
   HIPCHK(hipMemcpy(host_out, src, (size_t)g->cfg.d_model * 4, hipMemcpyDeviceToHost));
   return LL_OK;

@@ -6,7 +6,10 @@
 // Every kernel is launched on a grid sized for a prompt-length bucket Mb and
 // reads the true n from DevState, so one captured graph per bucket serves all
 // prompts that fit it.  Rows >= n are zero on entry and never reach the KV
-// cache or the logits.
+// cache or the logits.  A prompt longer than the largest bucket is fed in
+// chunks: DevState.pos holds the number of positions already cached (p0), row r
+// of the chunk sits at position p0 + r, and attention also covers the p0 keys
+// of the earlier chunks.
 #pragma once
 #include "ll_device.h"
 
@@ -63,8 +66,8 @@ __global__ __launch_bounds__(LL_WG) void pf_rmsnorm_kernel(const float* __restri
   for (int i = tid * 4; i < zero_row_floats; i += LL_WG * 4) *reinterpret_cast<f4*>(z + i) = zero;
 }
 
-// RoPE on the q and k thirds of QKV[r] (fp32, [Mb][3d]) at position r, then
-// q -> fp16 Q[r], k/v -> the KV cache rows of position r.  grid = (Mb), rows >= n idle.
+// RoPE on the q and k thirds of QKV[r] (fp32, [Mb][3d]) at position p0 + r, then
+// q -> fp16 Q[r], k/v -> the KV cache rows of position p0 + r.  grid = (Mb), rows >= n idle.
 __global__ __launch_bounds__(LL_WG) void pf_rope_kv_kernel(const float* __restrict__ QKV,
                                                            const float2* __restrict__ rope,
                                                            const DevState* __restrict__ st,
@@ -74,20 +77,21 @@ __global__ __launch_bounds__(LL_WG) void pf_rope_kv_kernel(const float* __restri
                                                            int head_dim, int max_seq) {
   const int r = blockIdx.x;
   if (r >= st->n_prompt) return;
+  const int pos = st->pos + r;
   const int hh = head_dim >> 1;
   const float* row = QKV + (size_t)r * 3 * d;
   for (int p = threadIdx.x; p < d / 2; p += LL_WG) {
     const int head = p / hh, j = p - head * hh;
     const int ia = head * head_dim + j, ib = ia + hh;
-    const float2 cs = rope[(size_t)r * hh + j];
+    const float2 cs = rope[(size_t)pos * hh + j];
     const float qa = row[ia], qb = row[ib];
     Q[(size_t)r * d + ia] = (half_t)(qa * cs.x - qb * cs.y);
     Q[(size_t)r * d + ib] = (half_t)(qb * cs.x + qa * cs.y);
     const float ka = row[d + ia], kb = row[d + ib];
-    half_t* kr = kc + ((size_t)head * max_seq + r) * head_dim;
+    half_t* kr = kc + ((size_t)head * max_seq + pos) * head_dim;
     kr[j] = (half_t)(ka * cs.x - kb * cs.y);
     kr[j + hh] = (half_t)(kb * cs.x + ka * cs.y);
-    half_t* vr = vc + ((size_t)head * max_seq + r) * head_dim;
+    half_t* vr = vc + ((size_t)head * max_seq + pos) * head_dim;
     vr[j] = (half_t)row[2 * d + ia];
     vr[j + hh] = (half_t)row[2 * d + ib];
   }
@@ -120,7 +124,7 @@ __global__ __launch_bounds__(128) void pf_attn_kernel(const half_t* __restrict__
   __shared__ __attribute__((aligned(16))) half_t Ks[TK * K_STRIDE];
   __shared__ __attribute__((aligned(16))) half_t Vt[HD * V_STRIDE];
   const int h = blockIdx.x, q0 = blockIdx.y * QB;
-  const int n = st->n_prompt;
+  const int n = st->n_prompt, p0 = st->pos;   // rows of this chunk, positions cached before it
   if (q0 >= n) return;
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, ql = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -143,13 +147,13 @@ __global__ __launch_bounds__(128) void pf_attn_kernel(const half_t* __restrict__
 
   const half_t* kh = kc + (size_t)h * max_seq * HD;
   const half_t* vh = vc + (size_t)h * max_seq * HD;
-  const int last_key = min(q0 + QB, n) - 1;   // the block's last valid query attends it
+  const int last_key = p0 + min(q0 + QB, n) - 1;   // the block's last valid query attends it
 
   for (int k0 = 0; k0 <= last_key; k0 += TK) {
     __syncthreads();   // the previous tile has been consumed
     for (int idx = tid; idx < TK * CPR; idx += 128) {
       const int key = idx / CPR, c = idx - key * CPR;
-      const int kr = min(k0 + key, n - 1);
+      const int kr = min(k0 + key, p0 + n - 1);
       *reinterpret_cast<h8*>(Ks + key * K_STRIDE + c * 8) = load_h8(kh + (size_t)kr * HD + c * 8);
       const h8 v = load_h8(vh + (size_t)kr * HD + c * 8);
       // position of this key inside a V^T row: k-step s = key / 16, then half and slot as above
@@ -159,7 +163,7 @@ __global__ __launch_bounds__(128) void pf_attn_kernel(const half_t* __restrict__
       for (int e = 0; e < 8; ++e) Vt[(c * 8 + e) * V_STRIDE + pos] = v[e];
     }
     __syncthreads();
-    if (k0 > wave_last_q) continue;   // whole tile above this wave's diagonal
+    if (k0 > p0 + wave_last_q) continue;   // whole tile above this wave's diagonal
 
     f16v sc;
 #pragma unroll
@@ -173,7 +177,7 @@ __global__ __launch_bounds__(128) void pf_attn_kernel(const half_t* __restrict__
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       const int key = k0 + 8 * (e >> 2) + 4 * hf + (e & 3);
-      sc[e] = (key <= qi) ? sc[e] * scale : -INFINITY;
+      sc[e] = (key <= p0 + qi) ? sc[e] * scale : -INFINITY;
       mx = fmaxf(mx, sc[e]);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32));

@@ -76,7 +76,7 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_kernel(SkinnyArgs a) 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 15, g = lane >> 4;
   const int K = a.K, N = a.N;
-  const int n = a.st->n_prompt;
+  const int n = a.st->n_prompt, p0 = a.st->pos;   // rows of this chunk, positions cached before it
   const int units = skinny_units(MODE, N);
   const int hh = a.head_dim >> 1;
 
@@ -245,12 +245,12 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_kernel(SkinnyArgs a) 
           const int c0 = v * 16, head = c0 / a.head_dim, e = c0 - head * a.head_dim;   // 16 rows of one head
 #pragma unroll
           for (int j = 0; j < 8; ++j) { o0[j] = (half_t)lo[j]; o1[j] = (half_t)hi[j]; }
-          half_t* vr = a.vc + ((size_t)head * a.max_seq + tok) * a.head_dim + e;
+          half_t* vr = a.vc + ((size_t)head * a.max_seq + p0 + tok) * a.head_dim + e;
           *reinterpret_cast<h8*>(vr) = o0;
           *reinterpret_cast<h8*>(vr + 8) = o1;
         } else {
           const int bph = hh / 8, head = v / bph, j0 = (v - head * bph) * 8;
-          const float2* cs = a.rope + (size_t)tok * hh + j0;   // prompt row tok sits at position tok
+          const float2* cs = a.rope + (size_t)(p0 + tok) * hh + j0;   // row tok of the chunk sits at position p0 + tok
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             const float2 t2 = cs[j];
@@ -258,7 +258,7 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_kernel(SkinnyArgs a) 
             o1[j] = (half_t)(hi[j] * t2.x + lo[j] * t2.y);
           }
           half_t* dst = z == 0 ? a.Q + (size_t)tok * N + head * a.head_dim
-                               : a.kc + ((size_t)head * a.max_seq + tok) * a.head_dim;
+                               : a.kc + ((size_t)head * a.max_seq + p0 + tok) * a.head_dim;
           *reinterpret_cast<h8*>(dst + j0) = o0;
           *reinterpret_cast<h8*>(dst + j0 + hh) = o1;
         }
@@ -284,7 +284,7 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 15, g = lane >> 4;
   const int K = a.K, N = a.N;
-  const int n = a.st->n_prompt;
+  const int n = a.st->n_prompt, p0 = a.st->pos;   // rows of this chunk, positions cached before it
   const int units = skinny_units(MODE, N);
   const int hh = a.head_dim >> 1;
   const int ksteps = (K + 31) >> 5;
@@ -396,12 +396,12 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
           const int c0 = v * 16, head = c0 / a.head_dim, e = c0 - head * a.head_dim;
 #pragma unroll
           for (int j = 0; j < 8; ++j) { o0[j] = (half_t)lo[j]; o1[j] = (half_t)hi[j]; }
-          half_t* vr = a.vc + ((size_t)head * a.max_seq + tok) * a.head_dim + e;
+          half_t* vr = a.vc + ((size_t)head * a.max_seq + p0 + tok) * a.head_dim + e;
           *reinterpret_cast<h8*>(vr) = o0;
           *reinterpret_cast<h8*>(vr + 8) = o1;
         } else {
           const int bph = hh / 8, head = v / bph, j0 = (v - head * bph) * 8;
-          const float2* cs = a.rope + (size_t)tok * hh + j0;
+          const float2* cs = a.rope + (size_t)(p0 + tok) * hh + j0;
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             const float2 t2 = cs[j];
@@ -409,7 +409,7 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
             o1[j] = (half_t)(hi[j] * t2.x + lo[j] * t2.y);
           }
           half_t* dst = z == 0 ? a.Q + (size_t)tok * N + head * a.head_dim
-                               : a.kc + ((size_t)head * a.max_seq + tok) * a.head_dim;
+                               : a.kc + ((size_t)head * a.max_seq + p0 + tok) * a.head_dim;
           *reinterpret_cast<h8*>(dst + j0) = o0;
           *reinterpret_cast<h8*>(dst + j0 + hh) = o1;
         }

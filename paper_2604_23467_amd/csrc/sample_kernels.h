@@ -215,7 +215,7 @@ __device__ __forceinline__ int smp_nucleus_and_draw(uint32_t (&key)[PER], float 
   return *found < 0 ? 0 : *found;
 }
 
-//   prefill = 1: pos := n_prompt, steps := 1, ring[0] := token (draw index 0)
+//   prefill = 1: pos += n_prompt (rows of the last prompt chunk), steps := 1, ring[0] := token (draw index 0)
 //   prefill = 0: pos += 1, ring[steps] := token, steps += 1   (draw index = steps before the step)
 __global__ __launch_bounds__(SMP_THREADS) void sample_kernel(const float* __restrict__ pval,
                                                              const int* __restrict__ pidx, int nparts,
@@ -360,7 +360,7 @@ __global__ __launch_bounds__(SMP_THREADS) void sample_kernel(const float* __rest
   if (tid == 0) {
     int idx;
     if (prefill) {
-      st->pos = st->n_prompt;
+      st->pos = st->pos + st->n_prompt;
       idx = 0;
       st->steps = 1;
     } else {
