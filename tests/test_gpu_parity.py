@@ -166,16 +166,16 @@ def test_graph_replay_equals_eager_and_decode_n(torch_cuda):
 
 
 @pytest.mark.parametrize("flags", [0, 1], ids=["graph", "eager"])
-@pytest.mark.parametrize("n_prompt", [513, 540, 600, 1100])
-def test_chunked_prefill_of_long_prompts(torch_cuda, oracle32, n_prompt, flags):
+@pytest.mark.parametrize("n_prompt,max_seq", [(513, 1200), (540, 1200), (600, 2000), (1100, 3500)])
+def test_chunked_prefill_of_long_prompts(torch_cuda, oracle32, n_prompt, max_seq, flags):
     """Prompts beyond the largest 512-row bucket are fed in chunks: 512 + a 1-row, a 28-row
-    (short-prompt kernels at a position offset), an 88-row and two full chunks + 76 rows."""
-    cfg = wl.custom_cfg(2, 2, 64, 136, 200, 1200)
+    (short-prompt kernels at a position offset), an 88-row and two full chunks + 76 rows, in instances of different capacity."""
+    cfg = wl.custom_cfg(2, 2, 64, 136, 200, max_seq)
     w = wl.weights_astype(wl.make_weights_numpy(cfg, seed=61, gain_jitter=0.1, emb_std=0.5), np.float16)
     prompt = wl.make_tokens(n_prompt, cfg["vocab"], seed=n_prompt)
     om = oracle32.model(cfg, w)
     with _session(cfg, w, flags) as s:
-        assert s.ll_max_prompt() == 1199
+        assert s.ll_max_prompt() == max_seq - 1
         run_teacher_forced(s, om, prompt, 3, "chunked")
         for which in range(2):
             assert rel_l2(s.ll_dbg_get_kv(1, which, n_prompt + 3), om.kv(1, which)) < 3e-3
