@@ -197,9 +197,23 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
 
   float best_v = -INFINITY;
   int best_i = 0x7fffffff;
+  int qkv_pos = 0;
+  if (MODE == GM_QKV) qkv_pos = a.st->pos;
 
   for (int p = gw; p < P; p += GW) {
     if (p != gw) select_rows(p);
+    // What the epilogue will need besides the sums does not depend on them: fetch it now, so the
+    // row pair ends without a memory round trip (the residual it adds to, or its RoPE factors).
+    float pre0 = 0.f, pre1 = 0.f;
+    float2 pcs = make_float2(1.f, 0.f);
+    if (MODE == GM_ORES || MODE == GM_DOWN) {
+      if (lane == 0) { pre0 = *as_global(a.out + rowA); pre1 = *as_global(a.out + rowB); }
+    } else if (MODE == GM_QKV) {
+      if (sec < 2) {
+        const int head = rowA / a.head_dim, j = rowA - head * a.head_dim;
+        pcs = a.rope[(size_t)qkv_pos * (a.head_dim >> 1) + j];
+      }
+    }
     float accA = 0.f, accB = 0.f;
     for (int c0 = 0; c0 < nch; c0 += U) {
       if (p != gw || c0 != 0) load_group(c0);
@@ -216,11 +230,11 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
     accB = wave_sum(accB) * inv;
 
     if (MODE == GM_QKV) {
-      const int pos = a.st->pos;
+      const int pos = qkv_pos;
       if (sec < 2) {
         const int hh = a.head_dim >> 1;
         const int head = rowA / a.head_dim, j = rowA - head * a.head_dim;
-        const float2 cs = a.rope[(size_t)pos * hh + j];
+        const float2 cs = pcs;
         const float ra = accA * cs.x - accB * cs.y;
         const float rb = accB * cs.x + accA * cs.y;
         if (lane == 0) {
@@ -243,8 +257,8 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
       if (lane == 0) a.out[p] = accA / (1.0f + expf(-accA)) * accB;
     } else if (MODE == GM_ORES || MODE == GM_DOWN) {
       if (lane == 0) {
-        a.out[rowA] += accA;
-        if (rowB != rowA) a.out[rowB] += accB;
+        a.out[rowA] = pre0 + accA;
+        if (rowB != rowA) a.out[rowB] = pre1 + accB;
       }
     } else {  // GM_LMHEAD
       if (lane == 0) {
@@ -304,6 +318,9 @@ __global__ __launch_bounds__(NSEG * 256, 2) void gemv_ksplit_kernel(GemvArgs a) 
     wa[u] = load_stream(pa + k);
     wb[u] = load_stream(pb + k);
   }
+  // the residual values the last step adds to, fetched up front
+  float pre0 = 0.f, pre1 = 0.f;
+  if (valid && seg == 0 && lane == 0) { pre0 = *as_global(a.out + rowA); pre1 = *as_global(a.out + rowB); }
 
   for (int i = tid; i < (nch + 1) * 128; i += NT) {   // chunk nch stays zero
     const int k = i * 4;
@@ -331,8 +348,8 @@ __global__ __launch_bounds__(NSEG * 256, 2) void gemv_ksplit_kernel(GemvArgs a) 
   __syncthreads();
   if (valid && seg == 0 && lane == 0) {
     for (int sg = 1; sg < NSEG; ++sg) { accA += part[(wave + sg) * 2]; accB += part[(wave + sg) * 2 + 1]; }
-    a.out[rowA] += accA;
-    a.out[rowB] += accB;
+    a.out[rowA] = pre0 + accA;
+    a.out[rowB] = pre1 + accB;
   }
 }
 
