@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--counters", action="store_true",
                     help="short run for `rocprofv3 --pmc`: a 256 MiB device copy as the counter "
                          "calibration, then prefill + the decode steps; no timing, no JSON")
+    ap.add_argument("--lib-gemm", action="store_true",
+                    help="context only: time torch.matmul (the vendor GEMM library) on the four projection "
+                         "shapes at M = 64..512 rows, weights rotated over 8 copies so they stream from HBM")
     ap.add_argument("--sweep", type=int, default=0, metavar="REPS",
                     help="latency sweep instead of the default run: for every prompt length in "
                          "{10,25,50,100,250,500}, REPS repetitions (token seed 1000*len + rep) of reset + "
@@ -99,6 +102,32 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    if args.lib_gemm:
+        out = {"metric": "vendor-library GEMM on the prefill projection shapes (context for the hand-written GEMM)",
+               "unit": "us", "dtype": "f16", "rows": {}}
+        shapes = {"qkv": (12288, 4096), "o": (4096, 4096), "gateup": (22016, 4096), "down": (4096, 11008)}
+        for m in (64, 128, 256, 512):
+            row = {}
+            for name, (n_, k_) in shapes.items():
+                ws = [torch.randn(n_, k_, device="cuda:0", dtype=torch.float16) for _ in range(8)]
+                x = torch.randn(m, k_, device="cuda:0", dtype=torch.float16)
+                for w_ in ws:
+                    torch.matmul(x, w_.t())
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(4):
+                    for w_ in ws:
+                        torch.matmul(x, w_.t())
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / 32
+                row[name] = {"us": us, "tflops": 2.0 * m * n_ * k_ / us / 1e6}
+                del ws
+            out["rows"][str(m)] = row
+            log("[bench] library GEMM, M = %3d: %s" % (m, "; ".join("%s %.1f us (%.0f TFLOP/s)" % (k, v["us"], v["tflops"]) for k, v in row.items())))
+        print(json.dumps(out), flush=True)
+        return 0
     K, W, n_prompt = args.steps, args.warmup, args.prompt
     cfg = wl.llama7b_cfg(max_seq=max(1024, n_prompt + max(K, W) + 64))
     log("[bench] drawing 7B-shaped fp16 weights on the GPU ...")
