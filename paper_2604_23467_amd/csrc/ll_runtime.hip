@@ -385,8 +385,10 @@ void enqueue_decode(Instance* I, hipStream_t s) {
 // K splits of a projection GEMM.  Splitting buys occupancy with atomics (and a zeroing pass for
 // fresh outputs): measured best is to stop at 128 workgroups, except for the residual-stream
 // GEMMs of the 512-row bucket, which are worth splitting up to 256.  At least 8 slabs per split.
+int gemm_bm(int Mb) { return Mb >= 128 ? 128 : 64; }
+
 int gemm_splits(int N, int K, int nmat, int Mb, bool fresh = true) {
-  const int bm = Mb >= 128 ? 128 : 64;
+  const int bm = gemm_bm(Mb);
   const int tiles = (Mb / bm) * ((N + PF_BN - 1) / PF_BN) * nmat;
   const int nslabs = (K + PF_BK - 1) / PF_BK;
   const int want = (!fresh && Mb >= 512) ? 256 : 128;
@@ -406,7 +408,7 @@ void launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0, co
   ga.C = C; ga.st = I->state();
   ga.zeros = I->at<half_t>(I->L.zeros);
   ga.N = N; ga.K = K; ga.ldc = ldc; ga.nmat = nmat;
-  const int bm = Mb >= 128 ? 128 : 64;
+  const int bm = gemm_bm(Mb);
   ga.mtiles = Mb / bm;
   ga.ntiles = (N + PF_BN - 1) / PF_BN;
   const int total_nt = ga.ntiles * nmat;
@@ -418,9 +420,9 @@ void launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0, co
   const int nt_rounds = (total_nt + 7) / 8;      // n-tiles are dealt to the 8 XCDs
   dim3 grid(nt_rounds * ga.mtiles * 8, ks);
   if (bm == 128)
-    hipLaunchKernelGGL((pf_gemm_kernel<128, 3>), grid, dim3(PF_GEMM_THREADS), PF_GEMM_LDS_BYTES(128, 3), s, ga);
+    hipLaunchKernelGGL((pf_gemm_kernel<128, 3, 2>), grid, dim3(PF_GEMM_THREADS * 2), PF_GEMM_LDS_BYTES(128, 3), s, ga);
   else
-    hipLaunchKernelGGL((pf_gemm_kernel<64, 3>), grid, dim3(PF_GEMM_THREADS), PF_GEMM_LDS_BYTES(64, 3), s, ga);
+    hipLaunchKernelGGL((pf_gemm_kernel<64, 3, 1>), grid, dim3(PF_GEMM_THREADS), PF_GEMM_LDS_BYTES(64, 3), s, ga);
 }
 
 int g_num_cus = 256;
@@ -763,10 +765,10 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&sample_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, SMP_Z_WORDS * 4),
                    "hipFuncSetAttribute(sample)")) return bail(rc);
-  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128, 3>),
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128, 3, 2>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128, 3)),
                    "hipFuncSetAttribute(gemm 128)")) return bail(rc);
-  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<64, 3>),
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<64, 3, 1>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(64, 3)),
                    "hipFuncSetAttribute(gemm 64)")) return bail(rc);
   if (!hip_or_bail(hipMemset(I->at<unsigned>(L.mk_bar), 0, (size_t)MK_BAR_WORDS * 4), "hipMemset(bar)"))

@@ -5,9 +5,11 @@
 // PFLOP/s with one wave per SIMD and 8 independent accumulators; the 16x16x32 form reaches
 // 0.83), activations as the A operand, weights as the B operand.
 //
-// Workgroup = 4 waves side by side along N, tile = BM rows x 256 columns x 64 k per slab
-// (BM = 128, or 64 for prompts of at most 64 rows); a wave owns all BM rows of 64 columns:
-// BM/32 x 2 accumulators of 32 x 32.  The wide tile is what the memory system needs: every
+// Workgroup tile = BM rows x 256 columns x 64 k per slab, 4 waves side by side along N and WM
+// along M: BM = 128 with 8 waves of 64 x 64 (two waves per SIMD hide each other's waits: measured
+// 3 % faster than 4 waves of 128 x 64), BM = 64 with 4 waves of 64 x 64 for prompts of at most 64
+// rows.  A 256 x 256 tile with two stages was also tried and lost (fewer tiles, shallower
+// pipeline).  The wide tile is what the memory system needs: every
 // slab moves (BM + 256) x 128 bytes from L2 for BM x 256 x 128 flop, and with M <= 512 split
 // over 256 CUs it is the L2 -> CU traffic, not HBM, that bounds these GEMMs.
 //
@@ -53,18 +55,20 @@ __device__ __forceinline__ void wait_vm_at_most() {
   __builtin_amdgcn_s_waitcnt((N & 15) | 0x70 | 0xF00 | ((N >> 4) << 14));
 }
 
-template <int BM, int NS>
-__global__ __launch_bounds__(PF_GEMM_THREADS, 1) void pf_gemm_kernel(GemmArgs g) {
-  constexpr int MT = BM / 32;                          // 32-row accumulators per wave
+template <int BM, int NS, int WM>
+__global__ __launch_bounds__(PF_GEMM_THREADS * WM, 1) void pf_gemm_kernel(GemmArgs g) {
+  constexpr int NWAVES = PF_GEMM_WAVES * WM;           // WM waves along M, 4 along N
+  constexpr int MT = BM / WM / 32;                     // 32-row accumulators per wave
   constexpr int NT = 2;                                // 32-column accumulators per wave
-  constexpr int A_LD = BM / 8 / PF_GEMM_WAVES;         // 1 KB direct loads per wave and slab (8 rows each)
-  constexpr int W_LD = PF_BN / 8 / PF_GEMM_WAVES;
+  constexpr int A_LD = BM / 8 / NWAVES;                // 1 KB direct loads per wave and slab (8 rows each)
+  constexpr int W_LD = PF_BN / 8 / NWAVES;
   constexpr int PER_SLAB = A_LD + W_LD;
   constexpr int STAGE_HALVES = (BM + PF_BN) * PF_BK;
   static_assert(PER_SLAB * (NS - 1) < 64, "vmcnt is a 6-bit counter");
   extern __shared__ __attribute__((aligned(16))) half_t pf_lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / PF_GEMM_WAVES, wn = wave % PF_GEMM_WAVES;
 
   // XCD-aware tile order: slot t of XCD x handles n-tile (t / mtiles) * 8 + x, m-tile t % mtiles
   const int total_nt = g.ntiles * g.nmat;
@@ -137,8 +141,8 @@ __global__ __launch_bounds__(PF_GEMM_THREADS, 1) void pf_gemm_kernel(GemmArgs g)
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     issue(sl + NS - 1, (stage + NS - 1) % NS);
-    const half_t* sa = pf_lds + stage * STAGE_HALVES + r * PF_BK;
-    const half_t* sw = sa + (BM + wave * 64) * PF_BK;
+    const half_t* sa = pf_lds + stage * STAGE_HALVES + (wm * (BM / WM) + r) * PF_BK;
+    const half_t* sw = pf_lds + stage * STAGE_HALVES + (BM + wn * 64 + r) * PF_BK;
     // fragments of k-step ks + 1 are read from LDS while the matrix cores work on k-step ks
     auto load_frags = [&](int ks, h8 (&fa)[MT], h8 (&fb)[NT]) {
       const int pc = ((ks * 2 + half) ^ (r & 7)) * 8;   // all fragment rows start at multiples of 8
@@ -165,9 +169,9 @@ __global__ __launch_bounds__(PF_GEMM_THREADS, 1) void pf_gemm_kernel(GemmArgs g)
   // rows 8*(e/4) + 4*(lane/32) + e%4 for e = 0..15
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
-    const int col = n0 + wave * 64 + j * 32 + r;
+    const int col = n0 + wn * 64 + j * 32 + r;
     if (col >= g.N) continue;
-    float* cbase = g.C + (size_t)z * g.N + col + (size_t)(m0 + 4 * half) * g.ldc;
+    float* cbase = g.C + (size_t)z * g.N + col + (size_t)(m0 + wm * (BM / WM) + 4 * half) * g.ldc;
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
       if (g.atomic) {
