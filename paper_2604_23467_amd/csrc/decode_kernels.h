@@ -481,6 +481,26 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_decode_kernel(
   }
 }
 
+// Merge of S > 2 attention partials of a head into o[head] (long-context instances only; with
+// two partials the O projection merges them while it stages its input).  grid = heads, HD threads.
+__global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict__ part, float* __restrict__ o,
+                                                         int S, int HD) {
+  const int h = blockIdx.x, t = threadIdx.x;
+  if (t >= HD) return;
+  const int PS = ATTN_PART_STRIDE(HD);
+  const float* hb = part + (size_t)h * S * PS;
+  float M = -INFINITY;
+  for (int sp = 0; sp < S; ++sp) M = fmaxf(M, hb[sp * PS]);
+  float L = 0.f, A = 0.f;
+  for (int sp = 0; sp < S; ++sp) {
+    const float mi = hb[sp * PS];
+    const float w = (mi > -INFINITY) ? __expf(mi - M) : 0.f;
+    L += hb[sp * PS + 1] * w;
+    A += hb[sp * PS + 4 + t] * w;
+  }
+  o[(size_t)h * HD + t] = A / L;
+}
+
 // Plain device-to-device copy with the same 16-byte streaming loads the GEMVs
 // use.  It exists to calibrate hardware traffic counters against a known byte
 // count; nothing on the decode path calls it.

@@ -94,7 +94,9 @@ int gemv_grid(int pairs) {
 Layout make_layout(const ll_config& c) {
   Layout L{};
   const size_t d = c.d_model, F = c.ffn_hidden, V = c.vocab;
-  L.attn_splits = (c.n_heads * 2 <= 512) ? 2 : 1;   // two 1024-thread workgroups per head
+  // 1024-thread workgroups per head: two (merged for free by the O projection) up to 2 K
+  // positions, eight plus a small merge kernel in long-context instances
+  L.attn_splits = c.n_heads * 2 > 512 ? 1 : c.max_seq <= 2048 ? 2 : 8;
   L.lm_wgs = gemv_grid((c.vocab + 1) / 2);
   L.max_prompt = c.max_seq - 1;                   // longer than the largest bucket: fed in chunks
   L.mb_max = prompt_bucket(L.max_prompt < kMaxPromptBucket ? L.max_prompt : kMaxPromptBucket);
@@ -281,12 +283,16 @@ void enqueue_decode_multi(Instance* I, hipStream_t s) {
       else
         hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(ATTN_THREADS), 0, s, q, I->kcache(l),
                            I->vcache(l), I->state(), I->at<float>(I->L.attn_part), c.max_seq);
+      if (I->L.attn_splits > 2)
+        hipLaunchKernelGGL(attn_merge_kernel, dim3(c.n_heads), dim3(128), 0, s, I->at<float>(I->L.attn_part), o,
+                           I->L.attn_splits, c.head_dim);
     }
     if (I->runs(LL_KC_OPROJ)) {
       ProfScope ps(I, s, LL_KC_OPROJ);
       GemvArgs a{};
       a.w0 = (const half_t*)W.wo; a.xin = o; a.out = x; a.N = d; a.K = d;
-      a.attn_part = I->at<float>(I->L.attn_part); a.attn_splits = I->L.attn_splits; a.head_dim = c.head_dim;
+      if (I->L.attn_splits <= 2) a.attn_part = I->at<float>(I->L.attn_part);   // else o holds the merged heads
+      a.attn_splits = I->L.attn_splits; a.head_dim = c.head_dim;
       launch_gemv<GM_ORES>(a, d / 2, 0, s);
     }
     if (I->runs(LL_KC_GATEUP)) {
