@@ -84,6 +84,10 @@ def main():
     ap.add_argument("--counters", action="store_true",
                     help="short run for `rocprofv3 --pmc`: a 256 MiB device copy as the counter "
                          "calibration, then prefill + the decode steps; no timing, no JSON")
+    ap.add_argument("--persistent-trace", action="store_true",
+                    help="one decode step of the single-persistent-kernel mode with its in-kernel phase "
+                         "timestamps (workgroup 0): where a phase's time goes between entry, staging, "
+                         "dot products, stores and the grid barrier")
     ap.add_argument("--lib-gemm", action="store_true",
                     help="context only: time torch.matmul (the vendor GEMM library) on the four projection "
                          "shapes at M = 64..512 rows, weights rotated over 8 copies so they stream from HBM")
@@ -146,6 +150,37 @@ def main():
         sess.ll_decode_n(K)
         sess.close()
         log("[bench] counter run done (%d decode steps after a %d-token prompt)" % (K, n_prompt))
+        return 0
+
+    if args.persistent_trace:
+        ps = binding.Session(cfg, w_t, flags=binding.LL_FLAG_PERSISTENT)
+        ps.ll_prefill(prompt)
+        ps.ll_decode_n(5)
+        dev_ms = ps.ll_dbg_time_decode(100) / 100
+        ps.ll_dbg_trace_decode()
+        t = ps.ll_dbg_trace_decode()                 # [phases][8] microseconds since the step's first stamp
+        ps.close()
+        names = ["qkv", "attn", "oproj", "gateup", "down"]
+        nl = cfg["n_layers"]
+        rows = {}
+        for k, nm in enumerate(names):
+            ph = np.array([t[5 * l + k] for l in range(2, nl - 1)])
+            nxt = np.array([t[5 * l + k + 1, 0] for l in range(2, nl - 1)])
+            staged = ph[:, 1] if (ph[:, 1] >= 0).all() else ph[:, 0]      # attention stages nothing: slot unused
+            rows[nm] = {"phase_us": float((nxt - ph[:, 0]).mean()),
+                        "entry_to_staged_us": float((staged - ph[:, 0]).mean()),
+                        "staged_to_dots_done_us": float((ph[:, 2] - staged).mean()),
+                        "dots_done_to_stored_us": float((ph[:, 3] - ph[:, 2]).mean()),
+                        "stored_to_barrier_passed_us": float((ph[:, 4] - ph[:, 3]).mean())}
+            log("[bench] persistent kernel, phase %-7s %.2f us: staging %.2f, dot products %.2f, stores %.2f, "
+                "barrier %.2f" % (nm, rows[nm]["phase_us"], rows[nm]["entry_to_staged_us"],
+                                  rows[nm]["staged_to_dots_done_us"], rows[nm]["dots_done_to_stored_us"],
+                                  rows[nm]["stored_to_barrier_passed_us"]))
+        out = {"metric": "phase timeline of the single persistent decode kernel (workgroup 0, mean over layers 2..30)",
+               "unit": "us", "device_ms_per_step": dev_ms, "step_us_by_trace": float(t[-1, 4] - t[0, 0]),
+               "phases": rows, "config": {"workload": "7B shape, prompt %d, KV %d" % (n_prompt, n_prompt + 106)}}
+        log("[bench] persistent kernel: %.3f ms/step on the device" % dev_ms)
+        print(json.dumps(out), flush=True)
         return 0
 
     sess = binding.Session(cfg, w_t)
