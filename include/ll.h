@@ -116,13 +116,14 @@ int ll_init(const ll_config *cfg, const ll_weights *w, void *workspace, size_t w
 /* Time-to-first-token call (the paper's TTFT metric, Sec. IV-E / Table I):
  * runs the whole prompt (1 <= n, n + 1 <= max_seq, n <= ll_max_prompt())
  * through the MFMA prefill path, fills KV positions 0..n-1 and returns the
- * first generated token t_1 (greedy: lowest index among the maxima of the
- * logits at position n-1).  Requires an empty context (after ll_init or
+ * first generated token t_1 (greedy by default: lowest index among the maxima of
+ * the logits at position n-1; see ll_set_sampling).  Requires an empty context (after ll_init or
  * ll_reset), else LL_E_STATE.  Blocks until the token is on the host. */
 int32_t ll_prefill(const int32_t *tokens, int32_t n);
 
 /* One decoding step (Alg. 1 loop body): feeds the previous step's token at the
- * next position, appends its key/value rows, returns the next greedy token.
+ * next position, appends its key/value rows, returns the next token (greedy by
+ * default, see ll_set_sampling).
  * Blocks until the token is on the host.  LL_E_STATE on an empty context,
  * LL_E_CAPACITY once max_seq positions are cached. */
 int32_t ll_decode_step(void);

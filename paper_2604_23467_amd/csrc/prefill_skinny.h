@@ -1,5 +1,5 @@
-// Projections of a SHORT prompt (at most 64 rows) for gfx950: the TTFT regime's
-// low end (10-50 tokens, Sec. IV-E / Table I), where the layer is bound by
+// Projections of a SHORT prompt (at most 32 rows) for gfx950: the TTFT regime's
+// low end (10-25 tokens, Sec. IV-E / Table I), where the layer is bound by
 // streaming its weights once, exactly like a decode step, and a square-tiled
 // GEMM wastes most of its tile.
 //
@@ -12,13 +12,17 @@
 //    consecutive k of one row (row = lane % 16, k = 8 * (lane / 16) ..), which is
 //    exactly a 16-byte streaming load from that weight row: a wave's load
 //    covers 16 rows x 64 contiguous bytes and goes straight into the A operand.
-//  * The activations (B operand, 16 tokens per block, TB blocks) are at most
-//    64 x K and stay in L2.  Their producers store them fragment-major
+//  * The activations (B operand, 16 tokens per block, TB = 1 or 2 blocks) are at
+//    most 32 x K and stay in L2.  Their producers store them fragment-major
 //    (act_offset), so a B fragment is one contiguous 1 KB load; read row-major
 //    with the weights' addressing, the 16 rows of a fragment sit a power of two
 //    apart and pile onto one L2 channel (measured: 53 us per layer and token block).
 //  * The 8 waves split K into 8 contiguous ranges; their partial 16 x 16 tiles
 //    meet in LDS, and the epilogue threads sum the 8 partials.
+//
+// The two wide projections (Q/K/V, gate/up) normally run in the persistent form
+// further down, which keeps a wave's activation fragments in registers; the
+// kernel right below serves O and down, and any K too long for that.
 //
 // Row blocks are chosen so that the epilogue's partners share a block: a
 // q/k block holds rows j..j+7 and j+hd/2..j+hd/2+7 of one head (the RoPE
@@ -53,6 +57,7 @@ struct SkinnyArgs {
   half_t* vc;
   const float2* rope;     // [max_seq][head_dim / 2] (cos, sin)
   long zeros_off;         // element offset from X of >= 16 bytes of zeros (same allocation as X)
+                          // positions: row r of the prompt chunk sits at position st->pos + r
   int head_dim, max_seq;
 };
 
