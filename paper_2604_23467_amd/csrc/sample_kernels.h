@@ -125,6 +125,62 @@ __device__ __forceinline__ float smp_block_scan_excl(float v, float* red, int& p
   return before + (lane > 0 ? prev : 0.f);
 }
 
+// k-th largest key over PER slots per thread (0 marks an empty slot) by bisecting the key's 32
+// bits two at a time; a wave counts with ballots, so a slot costs one compare per candidate prefix.
+// Returns 0 when fewer than k slots are filled.
+template <int PER>
+__device__ __forceinline__ uint32_t smp_kth_largest(const uint32_t (&key)[PER], int k, float* red, int& phase) {
+  constexpr int NW = SMP_THREADS / 64;
+  const int tid = threadIdx.x;
+  uint32_t prefix = 0u;
+  for (int bit = 31; bit >= 1; bit -= 2) {
+    const uint32_t c1 = prefix | (1u << (bit - 1)), c2 = prefix | (2u << (bit - 1)), c3 = prefix | (3u << (bit - 1));
+    int n1 = 0, n2 = 0, n3 = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      n1 += __builtin_popcountll(__ballot(key[j] >= c1));
+      n2 += __builtin_popcountll(__ballot(key[j] >= c2));
+      n3 += __builtin_popcountll(__ballot(key[j] >= c3));
+    }
+    int* bank = reinterpret_cast<int*>(red) + (phase & 1) * 3 * NW;
+    ++phase;
+    if ((tid & 63) == 0) { bank[tid >> 6] = n1; bank[NW + (tid >> 6)] = n2; bank[2 * NW + (tid >> 6)] = n3; }
+    __syncthreads();
+    int t1 = 0, t2 = 0, t3 = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { t1 += bank[w]; t2 += bank[NW + w]; t3 += bank[2 * NW + w]; }
+    prefix = t3 >= k ? c3 : t2 >= k ? c2 : t1 >= k ? c1 : prefix;
+  }
+  return prefix;
+}
+
+// Top-k cut over PER slots per thread (thread order = index order): slots outside the k largest
+// keys (equal keys enter by lower index) get key 0; every kept slot gets e = exp(z - zmax).
+// top_k = 0 keeps every filled slot.
+template <int PER>
+__device__ __forceinline__ void smp_apply_topk(uint32_t (&key)[PER], float (&e)[PER], int top_k, float zmax,
+                                               float* red, int& phase) {
+  uint32_t cut = 1u;          // kept: key > cut, or key == cut among the first tie_take ties
+  int tie_take = 0x7fffffff;  // (cut = 1 with all ties taken keeps every real token: real keys are >= 0x007FFFFF)
+  int seen = 0;
+  if (top_k > 0) {
+    cut = smp_kth_largest<PER>(key, top_k, red, phase);
+    int gt = 0, mine = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) { gt += key[j] > cut; mine += key[j] == cut; }
+    tie_take = top_k - smp_block_sum_int(gt, red, phase);
+    float all;
+    seen = (int)(smp_block_scan_excl((float)mine, red, phase, &all) + 0.5f);   // ties before this thread
+  }
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    bool in = key[j] > cut;
+    if (key[j] == cut && key[j] != 0u) { in = seen < tie_take; ++seen; }
+    if (!in) key[j] = 0u;
+    e[j] = in ? expf(key_to_float(key[j]) - zmax) : 0.f;
+  }
+}
+
 // Nucleus cut and draw over PER kept-or-dropped slots per thread; slot j of a thread is token
 // id0 + j and thread order is index order.  Dropped slots have key 0 and e 0.
 template <int PER>
@@ -274,85 +330,50 @@ __global__ __launch_bounds__(SMP_THREADS) void sample_kernel(const float* __rest
     }
     zmax = smp_block_max(zmax, red, phase);
 
-    // (1) top-k: the k-th largest key by bisection, then the ties at that key by index order
-    const int top_k = cfg->top_k;
-    uint32_t cut = 1u;          // candidates: key > cut, or key == cut among the first tie_take ties
-    int tie_take = 0x7fffffff;  // (cut = 1 with all ties taken keeps every real token: keys are >= 0x007FFFFF)
-    const bool cutting = top_k >= 1 && top_k < vocab;
-    if (cutting) {
-      // two bits per pass; a wave counts with ballots, so an element costs one compare per candidate prefix
-      constexpr int NW = SMP_THREADS / 64;
-      uint32_t prefix = 0u;
-      for (int bit = 31; bit >= 1; bit -= 2) {
-        const uint32_t c1 = prefix | (1u << (bit - 1)), c2 = prefix | (2u << (bit - 1)), c3 = prefix | (3u << (bit - 1));
-        int n1 = 0, n2 = 0, n3 = 0;
-#pragma unroll
-        for (int j = 0; j < SMP_PER; ++j) {
-          n1 += __builtin_popcountll(__ballot(key[j] >= c1));
-          n2 += __builtin_popcountll(__ballot(key[j] >= c2));
-          n3 += __builtin_popcountll(__ballot(key[j] >= c3));
-        }
-        int* bank = reinterpret_cast<int*>(red) + (phase & 1) * 3 * NW;
-        ++phase;
-        if ((tid & 63) == 0) { bank[tid >> 6] = n1; bank[NW + (tid >> 6)] = n2; bank[2 * NW + (tid >> 6)] = n3; }
-        __syncthreads();
-        int t1 = 0, t2 = 0, t3 = 0;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) { t1 += bank[w]; t2 += bank[NW + w]; t3 += bank[2 * NW + w]; }
-        prefix = t3 >= top_k ? c3 : t2 >= top_k ? c2 : t1 >= top_k ? c1 : prefix;
-      }
-      cut = prefix;
-      int gt = 0;
-#pragma unroll
-      for (int j = 0; j < SMP_PER; ++j) gt += key[j] > cut;
-      tie_take = top_k - smp_block_sum_int(gt, red, phase);
-    }
-    float e[SMP_PER];
-    int kept = 0;
-    {
-      int seen = 0;
-      if (cutting) {
-        int mine = 0;
-#pragma unroll
-        for (int j = 0; j < SMP_PER; ++j) mine += key[j] == cut;
-        float all;
-        seen = (int)(smp_block_scan_excl((float)mine, red, phase, &all) + 0.5f);   // ties before this thread
-      }
-#pragma unroll
-      for (int j = 0; j < SMP_PER; ++j) {
-        bool in = key[j] > cut;
-        if (key[j] == cut && key[j] != 0u) { in = seen < tie_take; ++seen; }
-        if (!in) key[j] = 0u;                       // dropped tokens leave the key space
-        e[j] = in ? expf(key_to_float(key[j]) - zmax) : 0.f;
-        kept += in;
-      }
-    }
     uint32_t ctr[4] = {(uint32_t)(prefill ? 0 : st->steps), 0u, 0u, 0u};
     philox4x32_10(ctr, cfg->seed_lo, cfg->seed_hi);
     const float u = (float)(ctr[0] >> 8) * (1.0f / 16777216.0f);
+    const int top_k = (cfg->top_k >= 1 && cfg->top_k < vocab) ? cfg->top_k : 0;
 
-    // (2) nucleus and draw.  After a top-k cut to at most one candidate per thread the survivors are
-    // packed, in index order, one per thread, and the remaining passes cost one element instead of 32.
-    if (cutting && top_k <= SMP_THREADS) {
-      float all;
-      int at = (int)(smp_block_scan_excl((float)kept, red, phase, &all) + 0.5f);
+    // (1) With a top-k cut of at most one candidate per thread, almost all of the vocabulary can be
+    // discarded cheaply first: the k-th largest of the threads' own maxima is a lower bound of the
+    // k-th largest key (at least k keys reach it), found with one slot per thread.  What reaches the
+    // bound is packed, in index order, one per thread, and every later pass costs one slot, not 32.
+    bool done = false;
+    if (top_k > 0 && top_k <= SMP_THREADS) {
+      uint32_t tmax[1] = {0u};
 #pragma unroll
-      for (int j = 0; j < SMP_PER; ++j) {
-        if (key[j] != 0u) {
-          sk[at] = key[j];
-          sv[at] = e[j];
-          si[at] = base + j;
-          ++at;
+      for (int j = 0; j < SMP_PER; ++j) tmax[0] = key[j] > tmax[0] ? key[j] : tmax[0];
+      const uint32_t bound = smp_kth_largest<1>(tmax, top_k, red, phase);
+      int reach = 0;
+#pragma unroll
+      for (int j = 0; j < SMP_PER; ++j) reach += key[j] >= bound;
+      float all;
+      int at = (int)(smp_block_scan_excl((float)reach, red, phase, &all) + 0.5f);
+      const int nreach = (int)(all + 0.5f);
+      if (bound != 0u && nreach <= SMP_THREADS) {            // uniform: `all` is the same in every thread
+#pragma unroll
+        for (int j = 0; j < SMP_PER; ++j) {
+          if (key[j] >= bound) {
+            sk[at] = key[j];
+            si[at] = base + j;
+            ++at;
+          }
         }
+        __syncthreads();
+        uint32_t k1[1] = {tid < nreach ? sk[tid] : 0u};
+        float e1[1];
+        const int id = tid < nreach ? si[tid] : 0;
+        __syncthreads();
+        smp_apply_topk<1>(k1, e1, top_k, zmax, red, phase);
+        tok = smp_nucleus_and_draw<1>(k1, e1, id, cfg->top_p, u, red, phase, &found);
+        done = true;
       }
-      __syncthreads();
-      const int ncand = (int)(all + 0.5f);
-      uint32_t k1[1] = {tid < ncand ? sk[tid] : 0u};
-      float e1[1] = {tid < ncand ? sv[tid] : 0.f};
-      const int id = tid < ncand ? si[tid] : 0;
-      __syncthreads();
-      tok = smp_nucleus_and_draw<1>(k1, e1, id, cfg->top_p, u, red, phase, &found);
-    } else {
+    }
+    // (2) otherwise: the cut (if any), the nucleus and the draw over all 32 slots per thread
+    if (!done) {
+      float e[SMP_PER];
+      smp_apply_topk<SMP_PER>(key, e, top_k, zmax, red, phase);
       tok = smp_nucleus_and_draw<SMP_PER>(key, e, base, cfg->top_p, u, red, phase, &found);
     }
   }

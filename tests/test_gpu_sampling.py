@@ -103,6 +103,28 @@ def test_equal_logits_exercise_the_tie_rules(torch_cuda):
         assert max(toks) <= 31 and len(set(toks)) > 5
 
 
+def test_ties_among_a_few_large_logits(torch_cuda):
+    """Two groups of ids share one LM-head row each (r and -r), the rest is zero: whichever group is
+    positive forms ~100 equal largest logits scattered over the vocabulary, so the cut runs through
+    ties that sit in different threads' ranges; the draw must be the oracle's, exactly."""
+    cfg = wl.custom_cfg(1, 2, 64, 136, 3000, 40)
+    w = wl.make_weights_numpy(cfg, seed=53)
+    r = w["lm_head"][0].copy() * 8
+    w["lm_head"][:] = 0
+    w["lm_head"][5::29] = r
+    w["lm_head"][11::31] = -r
+    with _session(cfg, wl.weights_astype(w, np.float16)) as s:
+        for k, p in ((7, 1.0), (64, 1.0), (64, 0.5), (150, 1.0), (150, 0.9)):
+            s.ll_reset()
+            s.ll_set_sampling(1.0, k, p, 17)
+            for i in range(12):
+                tok = s.ll_prefill([4, 5, 6]) if i == 0 else s.ll_decode_step()
+                logits = s.ll_dbg_get_logits()
+                assert (logits == logits.max()).sum() >= 90
+                ok, same = _accept(tok, logits, 1.0, k, p, sp.uniform(17, i))
+                assert ok, (k, p, i, tok)
+
+
 def test_streams_are_reproducible_and_seeded(torch_cuda):
     cfg = wl.tiny_cfg(max_seq=64)
     w = wl.make_weights_numpy(cfg, seed=3)
