@@ -97,3 +97,22 @@ __host__ __device__ __forceinline__ size_t act_offset(int tok, int k, int K, int
   if (tb == 0) return (size_t)tok * K + k;
   return ((size_t)((k >> 5) * tb + (tok >> 4)) * 64 + ((k >> 3) & 3) * 16 + (tok & 15)) * 8 + (k & 7);
 }
+
+// Where the prefill projection GEMM leaves its output: the K loop of all 256-column tiles is cut
+// into runs of `quota` 64-wide slabs, one run per workgroup (see prefill_gemm.h), and every run
+// stores its part of a tile's product into a slice of its own.  Column tile nt (counted over
+// the concatenated outputs of the GEMM's matrices) owns slabs nt * nslabs .. + nslabs - 1 of
+// that sequence, so its product is the sum of the slices 0 .. slice_count - 1.
+struct SliceMap {
+  int nslabs;             // 64-wide K slabs per tile
+  int quota;              // slabs per workgroup
+  int ntiles;             // 256-column tiles per matrix
+  int N;                  // columns per matrix
+  size_t slice_floats;    // floats per slice ([rows][ldc])
+};
+
+__host__ __device__ __forceinline__ int slice_count(const SliceMap& m, int col) {
+  const int z = col / m.N;
+  const int u0 = (z * m.ntiles + ((col - z * m.N) >> 8)) * m.nslabs;
+  return (u0 + m.nslabs - 1) / m.quota - u0 / m.quota + 1;
+}

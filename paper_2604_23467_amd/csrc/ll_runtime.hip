@@ -47,6 +47,8 @@ constexpr int kGemvU = 8;          // 512-element chunks of a weight row in flig
 constexpr int kGemvWgsPerCu = 4;   // measured best of 2/3/4 on the 7B shapes
 constexpr int kAttnMaxSplits = 16;
 constexpr int kMaxPromptBucket = 512;
+constexpr int kGemmWantWgs = 256;
+constexpr int kGemmMinSlabs = 8;
 constexpr size_t kAlign = 256;
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -75,9 +77,53 @@ bool skinny_ok(const ll_config& c) {
   return c.d_model % 16 == 0 && c.head_dim % 16 == 0 && c.ffn_hidden % 8 == 0;
 }
 
+// Row tile of the projection GEMM and how its K loops are dealt out: the 64-wide slabs of all
+// 256-column tiles form one sequence, cut into runs of `quota` slabs; with `mtiles` row tiles
+// the grid has runs x mtiles workgroups, at most one per CU (a second, partial round would cost
+// as much as a full one), and a run is at least kGemmMinSlabs long.
+int gemm_bm(int Mb) { return Mb >= 128 ? 128 : 64; }
+
+struct GemmPlan {
+  int mtiles, runs;
+  int max_slices;          // most pieces any tile is cut into
+  SliceMap map;
+};
+
+GemmPlan gemm_plan(int N, int K, int nmat, int Mb, int ldc) {
+  GemmPlan p{};
+  p.mtiles = Mb / gemm_bm(Mb);
+  p.map.nslabs = (K + 63) / 64;
+  p.map.ntiles = (N + 255) / 256;
+  p.map.N = N;
+  p.map.slice_floats = (size_t)Mb * ldc;
+  const int tiles = p.map.ntiles * nmat, S = p.map.nslabs;
+  // split-K: ks whole fractions of every tile, at most one round of workgroups over the CUs
+  int ks = kGemmWantWgs / (tiles * p.mtiles);
+  if (ks > S / kGemmMinSlabs) ks = S / kGemmMinSlabs;
+  if (ks < 1) ks = 1;
+  while (ks > 1 && (S + ks - 1) / ks * (ks - 1) >= S) --ks;      // no empty piece
+  const int wgs = tiles * p.mtiles * ks, rounds = (wgs + kGemmWantWgs - 1) / kGemmWantWgs;
+  if (ks == 1 && wgs * 5 < rounds * kGemmWantWgs * 4) {
+    // whole tiles would leave a fifth of a round idle: equal runs across tile borders instead
+    const int units = tiles * S;
+    int runs = kGemmWantWgs / p.mtiles;
+    if (runs > units / kGemmMinSlabs) runs = units / kGemmMinSlabs;
+    if (runs < 1) runs = 1;
+    p.map.quota = (units + runs - 1) / runs;
+    p.runs = (units + p.map.quota - 1) / p.map.quota;
+    p.max_slices = (S - 1) / p.map.quota + 2;
+  } else {
+    p.map.quota = (S + ks - 1) / ks;
+    p.map.nslabs = p.map.quota * ks;          // padded: tile t owns units t * nslabs .., the last piece is short
+    p.runs = tiles * ks;
+    p.max_slices = ks;
+  }
+  return p;
+}
+
 struct Layout {
   size_t kv, rope, x, q, o, m, attn_part, attn_cnt, logits, amax_val, amax_idx, state, tokens;
-  size_t pf_x, pf_xn, pf_qkv, pf_q, pf_o, pf_gu, pf_h, pf_ss;
+  size_t pf_x, pf_xn, pf_part, pf_q, pf_o, pf_h, pf_ss;
   size_t mk_layers, mk_bar, mk_amax_val, mk_amax_idx, mk_trace, zeros, sample_cfg;
   size_t total;
   int attn_splits, lm_wgs, max_prompt, mb_max;
@@ -119,10 +165,15 @@ Layout make_layout(const ll_config& c) {
   const size_t M = L.mb_max;
   L.pf_x = take(M * d * 4);
   L.pf_xn = take(M * ((d + 31) / 32 * 32) * 2);          // K rounded up: fragment-major layout
-  L.pf_qkv = take(M * 3 * d * 4);
   L.pf_q = take(M * d * 2);
   L.pf_o = take(M * ((d + 31) / 32 * 32) * 2);
-  L.pf_gu = take(M * 2 * F * 4);
+  size_t part = 0;                                       // slices of the widest GEMM output of any bucket
+  for (int mb = 64; mb <= L.mb_max; mb <<= 1) {
+    const GemmPlan plans[4] = {gemm_plan(d, d, 3, mb, 3 * d), gemm_plan(d, d, 1, mb, d),
+                               gemm_plan(F, d, 2, mb, 2 * F), gemm_plan(d, F, 1, mb, d)};
+    for (const GemmPlan& p : plans) part = std::max(part, p.max_slices * p.map.slice_floats);
+  }
+  L.pf_part = take(part * 4);
   L.pf_h = take(M * ((F + 31) / 32 * 32) * 2);
   L.pf_ss = take(2 * 64 * SK_SS_STRIDE * 4);
   L.zeros = take(256);
@@ -388,47 +439,25 @@ void enqueue_decode(Instance* I, hipStream_t s) {
 
 
 
-// K splits of a projection GEMM.  Splitting buys occupancy with atomics (and a zeroing pass for
-// fresh outputs): measured best is to stop at 128 workgroups, except for the residual-stream
-// GEMMs of the 512-row bucket, which are worth splitting up to 256.  At least 8 slabs per split.
-int gemm_bm(int Mb) { return Mb >= 128 ? 128 : 64; }
-
-int gemm_splits(int N, int K, int nmat, int Mb, bool fresh = true) {
-  const int bm = gemm_bm(Mb);
-  const int tiles = (Mb / bm) * ((N + PF_BN - 1) / PF_BN) * nmat;
-  const int nslabs = (K + PF_BK - 1) / PF_BK;
-  const int want = (!fresh && Mb >= 512) ? 256 : 128;
-  int ks = (want + tiles - 1) / tiles;
-  if (ks > nslabs / 8) ks = nslabs / 8;
-  if (ks < 1) ks = 1;
-  const int per = (nslabs + ks - 1) / ks;
-  return (nslabs + per - 1) / per;
-}
-
-// C += A W^T; fresh: C holds nothing to keep (the caller has zeroed it if gemm_splits() > 1)
-void launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0, const void* w1,
-                 const void* w2, int nmat, float* C, int ldc, int N, int K, int Mb, bool fresh) {
+// Projection GEMM A W_z^T into the slice buffer; the returned map tells the consuming kernel
+// which slices to add up for which column.
+SliceMap launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0, const void* w1,
+                     const void* w2, int nmat, int ldc, int N, int K, int Mb) {
+  const GemmPlan p = gemm_plan(N, K, nmat, Mb, ldc);
   GemmArgs ga{};
   ga.A = A;
   ga.W[0] = (const half_t*)w0; ga.W[1] = (const half_t*)w1; ga.W[2] = (const half_t*)w2;
-  ga.C = C; ga.st = I->state();
+  ga.C = I->at<float>(I->L.pf_part);
+  ga.st = I->state();
   ga.zeros = I->at<half_t>(I->L.zeros);
   ga.N = N; ga.K = K; ga.ldc = ldc; ga.nmat = nmat;
-  const int bm = gemm_bm(Mb);
-  ga.mtiles = Mb / bm;
-  ga.ntiles = (N + PF_BN - 1) / PF_BN;
-  const int total_nt = ga.ntiles * nmat;
-  const int nslabs = (K + PF_BK - 1) / PF_BK;
-  const int ks = gemm_splits(N, K, nmat, Mb, fresh);
-  ga.slabs_per_split = (nslabs + ks - 1) / ks;
-  ga.atomic = ks > 1;
-  ga.overwrite = fresh && ks == 1;
-  const int nt_rounds = (total_nt + 7) / 8;      // n-tiles are dealt to the 8 XCDs
-  dim3 grid(nt_rounds * ga.mtiles * 8, ks);
-  if (bm == 128)
+  ga.mtiles = p.mtiles; ga.runs = p.runs; ga.map = p.map;
+  dim3 grid((p.runs + 7) / 8 * 8 * p.mtiles);      // runs are dealt to the 8 XCDs
+  if (gemm_bm(Mb) == 128)
     hipLaunchKernelGGL((pf_gemm_kernel<128, 3, 2>), grid, dim3(PF_GEMM_THREADS * 2), PF_GEMM_LDS_BYTES(128, 3), s, ga);
   else
     hipLaunchKernelGGL((pf_gemm_kernel<64, 3, 1>), grid, dim3(PF_GEMM_THREADS), PF_GEMM_LDS_BYTES(64, 3), s, ga);
+  return p.map;
 }
 
 int g_num_cus = 256;
@@ -515,21 +544,27 @@ void enqueue_prefill(Instance* I, hipStream_t s, int Mb, bool with_head = true) 
   const int d = c.d_model, F = c.ffn_hidden;
   float* X = I->at<float>(I->L.pf_x);
   half_t* Xn = I->at<half_t>(I->L.pf_xn);
-  float* QKV = I->at<float>(I->L.pf_qkv);
   half_t* Qh = I->at<half_t>(I->L.pf_q);
   half_t* Oh = I->at<half_t>(I->L.pf_o);
-  float* GU = I->at<float>(I->L.pf_gu);
   half_t* Hm = I->at<half_t>(I->L.pf_h);
+  const float* P = I->at<float>(I->L.pf_part);     // slices of the GEMM that ran last
   hipLaunchKernelGGL(pf_embed_kernel, dim3(Mb, (d + LL_WG * 8 - 1) / (LL_WG * 8)), dim3(LL_WG), 0, s,
                      (const half_t*)I->w.tok_emb, I->at<int>(I->L.tokens), I->state(), X, d);
+  SliceMap res{};                                  // the residual GEMM whose slices are still to be added to X
+  const float* res_part = nullptr;
   for (int l = 0; l < c.n_layers; ++l) {
     const ll_layer_weights& W = I->layers[l];
-    hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(LL_WG), 0, s, X, (const half_t*)W.attn_norm,
-                       Xn, d, c.rms_eps, QKV, gemm_splits(d, d, 3, Mb) > 1 ? 3 * d : 0, 0);
-    launch_gemm(I, s, Xn, W.wq, W.wk, W.wv, 3, QKV, 3 * d, d, d, Mb, true);
-    hipLaunchKernelGGL(pf_rope_kv_kernel, dim3(Mb), dim3(LL_WG), 0, s, QKV,
-                       I->at<float2>(I->L.rope), I->state(), Qh, I->kcache(l), I->vcache(l), d,
-                       c.head_dim, c.max_seq);
+    hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(PF_NORM_THREADS), 0, s, X, (const half_t*)W.attn_norm,
+                       Xn, d, c.rms_eps, I->state(), res_part, res, 0);
+    const SliceMap qkv = launch_gemm(I, s, Xn, W.wq, W.wk, W.wv, 3, 3 * d, d, d, Mb);
+    if (c.head_dim % 8 == 0)
+      hipLaunchKernelGGL(pf_rope_kv4_kernel, dim3(Mb, (d / 8 + LL_WG - 1) / LL_WG), dim3(LL_WG), 0, s, P, qkv,
+                         I->at<float2>(I->L.rope), I->state(), Qh, I->kcache(l), I->vcache(l), d,
+                         c.head_dim, c.max_seq);
+    else
+      hipLaunchKernelGGL(pf_rope_kv_kernel, dim3(Mb), dim3(LL_WG), 0, s, P, qkv,
+                         I->at<float2>(I->L.rope), I->state(), Qh, I->kcache(l), I->vcache(l), d,
+                         c.head_dim, c.max_seq);
     dim3 agrid(c.n_heads, Mb / 64);
     if (c.head_dim == 128)
       hipLaunchKernelGGL(pf_attn_kernel<128>, agrid, dim3(128), 0, s, Qh, I->kcache(l),
@@ -537,14 +572,18 @@ void enqueue_prefill(Instance* I, hipStream_t s, int Mb, bool with_head = true) 
     else
       hipLaunchKernelGGL(pf_attn_kernel<64>, agrid, dim3(128), 0, s, Qh, I->kcache(l),
                          I->vcache(l), I->state(), Oh, d, c.max_seq, 0);
-    launch_gemm(I, s, Oh, W.wo, nullptr, nullptr, 1, X, d, d, d, Mb, false);
-    hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(LL_WG), 0, s, X, (const half_t*)W.ffn_norm,
-                       Xn, d, c.rms_eps, GU, gemm_splits(F, d, 2, Mb) > 1 ? 2 * F : 0, 0);
-    launch_gemm(I, s, Xn, W.w_gate, W.w_up, nullptr, 2, GU, 2 * F, F, d, Mb, true);
+    res = launch_gemm(I, s, Oh, W.wo, nullptr, nullptr, 1, d, d, d, Mb);
+    res_part = P;
+    hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(PF_NORM_THREADS), 0, s, X, (const half_t*)W.ffn_norm,
+                       Xn, d, c.rms_eps, I->state(), res_part, res, 0);
+    const SliceMap gu = launch_gemm(I, s, Xn, W.w_gate, W.w_up, nullptr, 2, 2 * F, F, d, Mb);
     hipLaunchKernelGGL(pf_swiglu_kernel, dim3(Mb, (F + LL_WG * 4 - 1) / (LL_WG * 4)), dim3(LL_WG), 0,
-                       s, GU, I->state(), Hm, F);
-    launch_gemm(I, s, Hm, W.w_down, nullptr, nullptr, 1, X, d, d, F, Mb, false);
+                       s, P, gu, I->state(), Hm, F);
+    res = launch_gemm(I, s, Hm, W.w_down, nullptr, nullptr, 1, d, d, F, Mb);
   }
+  if (with_head && res_part)    // (a chunk that is not the prompt's last needs nothing of X any more)
+    hipLaunchKernelGGL(pf_fold_kernel, dim3(Mb, (d + LL_WG * 4 - 1) / (LL_WG * 4)), dim3(LL_WG), 0, s, X,
+                       I->state(), P, res, d);
   if (with_head) enqueue_head(I, s, X, 1, 1);
 }
 

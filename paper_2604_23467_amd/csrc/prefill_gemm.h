@@ -21,25 +21,32 @@
 // outside the matrices (K tail, rows >= N, slabs past the split's end) are fetched from a block
 // of zeros, so no lane is ever switched off and the wait counts are static.
 //
-// Split-K over blockIdx.y with fp32 atomic adds when a prompt gives too few tiles to occupy
-// the chip (the caller zeroes C first unless it is the residual stream); one split stores, or
-// adds in place when C is the residual stream.  Tile order keeps the M tiles that
-// share a weight tile on one XCD (workgroups are dealt to the 8 XCDs round robin), so the
-// re-reads of a weight tile hit that XCD's L2.
+// Work is dealt out in runs of K slabs: the K loops of all column tiles, laid end to end, are
+// cut into equal runs of `quota` slabs, one run per workgroup.  With few tiles the host makes
+// the quota a whole fraction of a tile's K loop (split-K: every piece starts a fresh pipeline,
+// so pieces should not be cut twice); with more tiles than divide well over the CUs it deals
+// stream-K fashion, a run ending in the middle of a tile and continuing with the next one, so
+// that every CU gets the same share whatever the tile count.  Each piece of a tile stores its partial product as a slice of a scratch buffer with plain
+// stores, and the kernel that consumes the GEMM's output anyway (RoPE, SwiGLU, the next RMSNorm)
+// adds the slices of a tile up (SliceMap).  Measured alternatives: fp32 atomic adds onto one
+// buffer complete at about 1.1 TB/s on this chip (40 % of the GEMM time at 128 rows), and whole
+// tiles per workgroup leave CUs idle or cost a second, mostly empty round (344 tiles on 256 CUs
+// take as long as 512).  The M tiles of a column tile run as sibling workgroups over the same
+// run of slabs on one XCD (workgroups are dealt to the 8 XCDs round robin), so the re-reads of
+// a weight tile hit that XCD's L2.
 #pragma once
 #include "ll_device.h"
 
 struct GemmArgs {
   const half_t* A;        // [>= mtiles * BM rows][K]
   const half_t* W[3];
-  float* C;
+  float* C;               // slices: [slice][rows][ldc]
   const DevState* st;
   const half_t* zeros;    // >= 16 bytes of zeros in global memory
   int N, K, ldc, nmat;
-  int mtiles, ntiles;     // tiles of BM rows / 256 columns (per matrix)
-  int slabs_per_split;    // 64-wide K slabs per blockIdx.y
-  int atomic;             // more than one K split: accumulate with atomics
-  int overwrite;          // single split and C holds nothing to keep: store instead of adding
+  int mtiles;             // tiles of BM rows
+  int runs;               // workgroups per M tile that have work
+  SliceMap map;
 };
 
 #define PF_BN 256
@@ -70,21 +77,25 @@ __global__ __launch_bounds__(PF_GEMM_THREADS * WM, 1) void pf_gemm_kernel(GemmAr
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / PF_GEMM_WAVES, wn = wave % PF_GEMM_WAVES;
 
-  // XCD-aware tile order: slot t of XCD x handles n-tile (t / mtiles) * 8 + x, m-tile t % mtiles
-  const int total_nt = g.ntiles * g.nmat;
+  // slot t of XCD x: run (t / mtiles) * 8 + x of the slab sequence, M tile t % mtiles
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int nt_all = (slot / g.mtiles) * 8 + xcd;
-  const int mt = slot % g.mtiles;
-  if (nt_all >= total_nt) return;
-  const int z = nt_all / g.ntiles, nt = nt_all - z * g.ntiles;
-  const int m0 = mt * BM, n0 = nt * PF_BN;
-  if (m0 >= g.st->n_prompt) return;
-
-  const int K = g.K;
-  const int nslabs_all = (K + PF_BK - 1) / PF_BK;
-  const int sl0 = blockIdx.y * g.slabs_per_split;
-  const int sl1 = min(sl0 + g.slabs_per_split, nslabs_all);
-  if (sl0 >= sl1) return;
+  const int run = (slot / g.mtiles) * 8 + xcd;
+  const int m0 = (slot % g.mtiles) * BM;
+  if (run >= g.runs || m0 >= g.st->n_prompt) return;
+  const int K = g.K, S = g.map.nslabs;                  // S may be padded beyond the K loop's real slabs ...
+  const int s_real = (K + PF_BK - 1) / PF_BK;           // ... so that runs end where tiles end
+  const int total_units = g.map.ntiles * g.nmat * S;
+  const int r = lane & 31, half = lane >> 5;
+  int u = run * g.map.quota;
+  const int u_end = min(u + g.map.quota, total_units);
+  while (u < u_end) {
+  const int nt_all = u / S;
+  const int sl0 = u - nt_all * S;
+  const int span = min(S - sl0, u_end - u);
+  u += span;
+  const int cnt = min(span, s_real - sl0);              // >= 1 by the host's choice of S and quota
+  const int slice = run - (nt_all * S) / g.map.quota;
+  const int z = nt_all / g.map.ntiles, n0 = (nt_all - z * g.map.ntiles) * PF_BN;
 
   // this lane's piece of every 8-row group: row (lane / 8), physical chunk (lane % 8),
   // which holds logical chunk (lane % 8) ^ (row & 7) = (lane % 8) ^ (lane / 8)
@@ -99,10 +110,15 @@ __global__ __launch_bounds__(PF_GEMM_THREADS * WM, 1) void pf_gemm_kernel(GemmAr
     const int n = n0 + (wave * W_LD + i) * 8 + lrow;
     wrow[i] = (n < g.N) ? g.W[z] + (size_t)n * K + lchunk * 8 : nullptr;
   }
-  auto issue = [&](int sl, int stage) {
+  // Every workgroup walks its K range from a different starting slab (and wraps around): all
+  // tiles reading the same 128-byte column of their weight rows at the same time would keep
+  // hitting the same few memory channels, since the rows lie a multiple of 2 K bytes apart.
+  const int rot = (nt_all * 7) % cnt;
+  auto issue = [&](int it, int stage) {
     half_t* sa = pf_lds + stage * STAGE_HALVES;
     half_t* sw = sa + BM * PF_BK;
-    const bool kin = sl < sl1 && sl * PF_BK + lchunk * 8 < K;   // K % 8 == 0: a chunk is all in or all out
+    const int sl = sl0 + (it + rot < cnt ? it + rot : it + rot - cnt);
+    const bool kin = it < cnt && sl * PF_BK + lchunk * 8 < K;   // K % 8 == 0: a chunk is all in or all out
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
       const half_t* src = kin ? arow[i] + sl * PF_BK : g.zeros;
@@ -127,12 +143,12 @@ __global__ __launch_bounds__(PF_GEMM_THREADS * WM, 1) void pf_gemm_kernel(GemmAr
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+  __syncthreads();        // a previous piece's last fragment reads are over before its ring is refilled
 #pragma unroll
-  for (int s = 0; s < NS - 1; ++s) issue(sl0 + s, s);
+  for (int s = 0; s < NS - 1; ++s) issue(s, s);
 
-  const int r = lane & 31, half = lane >> 5;
-  for (int sl = sl0; sl < sl1; ++sl) {
-    const int stage = (sl - sl0) % NS;
+  for (int it = 0; it < cnt; ++it) {
+    const int stage = it % NS;
     // this wave's pieces of slab sl have landed (younger slabs may still be in flight) ...
     wait_vm_at_most<PER_SLAB * (NS - 2)>();
     // ... and so have everybody else's; everybody is also done reading the stage of slab sl - 1.
@@ -140,7 +156,7 @@ __global__ __launch_bounds__(PF_GEMM_THREADS * WM, 1) void pf_gemm_kernel(GemmAr
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    issue(sl + NS - 1, (stage + NS - 1) % NS);
+    issue(it + NS - 1, (stage + NS - 1) % NS);
     const half_t* sa = pf_lds + stage * STAGE_HALVES + (wm * (BM / WM) + r) * PF_BK;
     const half_t* sw = pf_lds + stage * STAGE_HALVES + (BM + wn * 64 + r) * PF_BK;
     // fragments of k-step ks + 1 are read from LDS while the matrix cores work on k-step ks
@@ -171,26 +187,13 @@ __global__ __launch_bounds__(PF_GEMM_THREADS * WM, 1) void pf_gemm_kernel(GemmAr
   for (int j = 0; j < NT; ++j) {
     const int col = n0 + wn * 64 + j * 32 + r;
     if (col >= g.N) continue;
-    float* cbase = g.C + (size_t)z * g.N + col + (size_t)(m0 + wm * (BM / WM) + 4 * half) * g.ldc;
+    float* cbase = g.C + slice * g.map.slice_floats + (size_t)z * g.N + col +
+                   (size_t)(m0 + wm * (BM / WM) + 4 * half) * g.ldc;
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      if (g.atomic) {
+    for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-          unsafeAtomicAdd(cbase + (size_t)(i * 32 + 8 * (e >> 2) + (e & 3)) * g.ldc, acc[i][j][e]);
-      } else if (g.overwrite) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e)
-          *as_global(cbase + (size_t)(i * 32 + 8 * (e >> 2) + (e & 3)) * g.ldc) = acc[i][j][e];
-      } else {
-        // all 16 loads first: an add-in-place per element would serialise 16 memory round trips
-        float old[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) old[e] = *as_global(cbase + (size_t)(i * 32 + 8 * (e >> 2) + (e & 3)) * g.ldc);
-#pragma unroll
-        for (int e = 0; e < 16; ++e)
-          *as_global(cbase + (size_t)(i * 32 + 8 * (e >> 2) + (e & 3)) * g.ldc) = old[e] + acc[i][j][e];
-      }
-    }
+      for (int e = 0; e < 16; ++e)
+        *as_global(cbase + (size_t)(i * 32 + 8 * (e >> 2) + (e & 3)) * g.ldc) = acc[i][j][e];
   }
+  }   // next piece of this workgroup's run
 }

@@ -32,43 +32,84 @@ __global__ __launch_bounds__(LL_WG) void pf_embed_kernel(const half_t* __restric
   }
 }
 
+// Sum of np split-K slices at p (slice stride in floats), four loads in flight at a time.
+__device__ __forceinline__ f4 pf_slice_sum(const float* p, int np, size_t slice_floats) {
+  f4 v = {0.f, 0.f, 0.f, 0.f};
+  int s = 0;
+  for (; s + 4 <= np; s += 4) {
+    const f4 a = *reinterpret_cast<const f4*>(p + (size_t)s * slice_floats);
+    const f4 b = *reinterpret_cast<const f4*>(p + (size_t)(s + 1) * slice_floats);
+    const f4 c = *reinterpret_cast<const f4*>(p + (size_t)(s + 2) * slice_floats);
+    const f4 e = *reinterpret_cast<const f4*>(p + (size_t)(s + 3) * slice_floats);
+    v += (a + b) + (c + e);
+  }
+  for (; s < np; ++s) v += *reinterpret_cast<const f4*>(p + (size_t)s * slice_floats);
+  return v;
+}
+
 // Row-wise RMSNorm of the fp32 residual stream into fp16 GEMM operands, one
-// workgroup per row.  As a side job each workgroup clears its row of the fp32
-// buffer the following split-K GEMM accumulates into.  frag_tb != 0 writes the
-// operands in the short-prompt kernels' fragment-major layout.
-__global__ __launch_bounds__(LL_WG) void pf_rmsnorm_kernel(const float* __restrict__ X,
-                                                           const half_t* __restrict__ gain,
-                                                           half_t* __restrict__ Xn, int d, float eps,
-                                                           float* __restrict__ zero_buf,
-                                                           int zero_row_floats, int frag_tb) {
-  __shared__ float red[LL_WG / 64];
+// 1024-thread workgroup per row.  The residual GEMM in front of it may have left
+// its result as np split-K slices ([np][rows][d] at part): they are added to X
+// here, X is stored back, and the norm is taken of the sum.  Rows past the prompt
+// give zero operands.  frag_tb != 0 writes the operands in the short-prompt
+// kernels' fragment-major layout.
+#define PF_NORM_THREADS 1024
+__global__ __launch_bounds__(PF_NORM_THREADS) void pf_rmsnorm_kernel(float* __restrict__ X,
+                                                                     const half_t* __restrict__ gain,
+                                                                     half_t* __restrict__ Xn, int d, float eps,
+                                                                     const DevState* __restrict__ st,
+                                                                     const float* __restrict__ part, SliceMap map,
+                                                                     int frag_tb) {
+  __shared__ float red[PF_NORM_THREADS / 64];
   const int r = blockIdx.x, tid = threadIdx.x;
-  const float* xr = X + (size_t)r * d;
+  if (r >= st->n_prompt) {
+    const h4 zero = {0, 0, 0, 0};
+    for (int i = tid * 4; i < d; i += PF_NORM_THREADS * 4)
+      *reinterpret_cast<h4*>(Xn + act_offset(r, i, d, frag_tb)) = zero;
+    return;
+  }
+  float* xr = X + (size_t)r * d;
+  const float* pr = part + (size_t)r * d;
   float ss = 0.f;
-  for (int i = tid * 4; i < d; i += LL_WG * 4) {
-    const f4 v = *reinterpret_cast<const f4*>(xr + i);
+  for (int i = tid * 4; i < d; i += PF_NORM_THREADS * 4) {
+    f4 v = *reinterpret_cast<const f4*>(xr + i);
+    if (part) {
+      v += pf_slice_sum(pr + i, slice_count(map, i), map.slice_floats);
+      *reinterpret_cast<f4*>(xr + i) = v;
+    }
     ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
   }
   ss = wave_sum(ss);
   if ((tid & 63) == 0) red[tid >> 6] = ss;
   __syncthreads();
-  const float inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
-  for (int i = tid * 4; i < d; i += LL_WG * 4) {
-    const f4 v = *reinterpret_cast<const f4*>(xr + i);
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < PF_NORM_THREADS / 64; ++w) tot += red[w];
+  const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int i = tid * 4; i < d; i += PF_NORM_THREADS * 4) {
+    const f4 v = *reinterpret_cast<const f4*>(xr + i);      // this thread's own stores of the loop above
     const h4 g = *reinterpret_cast<const h4*>(gain + i);
     h4 o;
 #pragma unroll
     for (int j = 0; j < 4; ++j) o[j] = (half_t)(v[j] * inv * (float)g[j]);
     *reinterpret_cast<h4*>(Xn + act_offset(r, i, d, frag_tb)) = o;
   }
-  float* z = zero_buf + (size_t)r * zero_row_floats;
-  const f4 zero = {0.f, 0.f, 0.f, 0.f};
-  for (int i = tid * 4; i < zero_row_floats; i += LL_WG * 4) *reinterpret_cast<f4*>(z + i) = zero;
 }
 
-// RoPE on the q and k thirds of QKV[r] (fp32, [Mb][3d]) at position p0 + r, then
-// q -> fp16 Q[r], k/v -> the KV cache rows of position p0 + r.  grid = (Mb), rows >= n idle.
-__global__ __launch_bounds__(LL_WG) void pf_rope_kv_kernel(const float* __restrict__ QKV,
+// X[r] += the slices of the last residual GEMM (nothing follows it that could).
+// grid = (rows, ceil(d / 1024))
+__global__ __launch_bounds__(LL_WG) void pf_fold_kernel(float* __restrict__ X, const DevState* __restrict__ st,
+                                                        const float* __restrict__ part, SliceMap map, int d) {
+  const int r = blockIdx.x, i = (blockIdx.y * LL_WG + threadIdx.x) * 4;
+  if (r >= st->n_prompt || i >= d) return;
+  float* x = X + (size_t)r * d + i;
+  *reinterpret_cast<f4*>(x) = *reinterpret_cast<const f4*>(x) + pf_slice_sum(part + (size_t)r * d + i, slice_count(map, i), map.slice_floats);
+}
+
+// RoPE on the q and k thirds of the QKV projection (fp32, slices of [Mb][3d], summed here) at
+// position p0 + r, then q -> fp16 Q[r], k/v -> the KV cache rows of position p0 + r.
+// grid = (Mb), rows >= n idle.
+__global__ __launch_bounds__(LL_WG) void pf_rope_kv_kernel(const float* __restrict__ QKV, SliceMap map,
                                                            const float2* __restrict__ rope,
                                                            const DevState* __restrict__ st,
                                                            half_t* __restrict__ Q,
@@ -80,21 +121,73 @@ __global__ __launch_bounds__(LL_WG) void pf_rope_kv_kernel(const float* __restri
   const int pos = st->pos + r;
   const int hh = head_dim >> 1;
   const float* row = QKV + (size_t)r * 3 * d;
+  auto val = [&](int i) {
+    float v = row[i];
+    const int np = slice_count(map, i);
+    for (int s = 1; s < np; ++s) v += row[s * map.slice_floats + i];
+    return v;
+  };
   for (int p = threadIdx.x; p < d / 2; p += LL_WG) {
     const int head = p / hh, j = p - head * hh;
     const int ia = head * head_dim + j, ib = ia + hh;
     const float2 cs = rope[(size_t)pos * hh + j];
-    const float qa = row[ia], qb = row[ib];
+    const float qa = val(ia), qb = val(ib);
     Q[(size_t)r * d + ia] = (half_t)(qa * cs.x - qb * cs.y);
     Q[(size_t)r * d + ib] = (half_t)(qb * cs.x + qa * cs.y);
-    const float ka = row[d + ia], kb = row[d + ib];
+    const float ka = val(d + ia), kb = val(d + ib);
     half_t* kr = kc + ((size_t)head * max_seq + pos) * head_dim;
     kr[j] = (half_t)(ka * cs.x - kb * cs.y);
     kr[j + hh] = (half_t)(kb * cs.x + ka * cs.y);
     half_t* vr = vc + ((size_t)head * max_seq + pos) * head_dim;
-    vr[j] = (half_t)row[2 * d + ia];
-    vr[j + hh] = (half_t)row[2 * d + ib];
+    vr[j] = (half_t)val(2 * d + ia);
+    vr[j + hh] = (half_t)val(2 * d + ib);
   }
+}
+
+// The same for head_dim % 8 == 0, four rotation pairs per thread with 16-byte loads, every load
+// of a thread issued before the first use.  grid = (Mb, ceil(n_heads * head_dim / 8 / LL_WG)).
+__global__ __launch_bounds__(LL_WG) void pf_rope_kv4_kernel(const float* __restrict__ QKV, SliceMap map,
+                                                            const float2* __restrict__ rope,
+                                                            const DevState* __restrict__ st,
+                                                            half_t* __restrict__ Q,
+                                                            half_t* __restrict__ kc,
+                                                            half_t* __restrict__ vc, int d,
+                                                            int head_dim, int max_seq) {
+  const int r = blockIdx.x;
+  if (r >= st->n_prompt) return;
+  const int hh = head_dim >> 1, per_head = hh >> 2;
+  const int item = blockIdx.y * LL_WG + threadIdx.x;
+  const int head = item / per_head, j = (item - head * per_head) * 4;
+  if (head * head_dim >= d) return;
+  const int pos = st->pos + r;
+  const int ia = head * head_dim + j, ib = ia + hh;
+  const float* row = QKV + (size_t)r * 3 * d;
+  const f4 c01 = *reinterpret_cast<const f4*>(rope + (size_t)pos * hh + j);       // (cos, sin) of pairs j, j + 1
+  const f4 c23 = *reinterpret_cast<const f4*>(rope + (size_t)pos * hh + j + 2);
+  auto val = [&](int i) { return pf_slice_sum(row + i, slice_count(map, i), map.slice_floats); };
+  const f4 qa = val(ia), qb = val(ib), ka = val(d + ia), kb = val(d + ib), va = val(2 * d + ia), vb = val(2 * d + ib);
+  const f4 cs = {c01[0], c01[2], c23[0], c23[2]}, sn = {c01[1], c01[3], c23[1], c23[3]};
+  h4 o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (half_t)(qa[e] * cs[e] - qb[e] * sn[e]);
+  *reinterpret_cast<h4*>(Q + (size_t)r * d + ia) = o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (half_t)(qb[e] * cs[e] + qa[e] * sn[e]);
+  *reinterpret_cast<h4*>(Q + (size_t)r * d + ib) = o;
+  half_t* kr = kc + ((size_t)head * max_seq + pos) * head_dim;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (half_t)(ka[e] * cs[e] - kb[e] * sn[e]);
+  *reinterpret_cast<h4*>(kr + j) = o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (half_t)(kb[e] * cs[e] + ka[e] * sn[e]);
+  *reinterpret_cast<h4*>(kr + j + hh) = o;
+  half_t* vr = vc + ((size_t)head * max_seq + pos) * head_dim;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (half_t)va[e];
+  *reinterpret_cast<h4*>(vr + j) = o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (half_t)vb[e];
+  *reinterpret_cast<h4*>(vr + j + hh) = o;
 }
 
 // Causal attention of one head for a block of 64 queries, on the matrix cores.
@@ -220,8 +313,9 @@ __global__ __launch_bounds__(128) void pf_attn_kernel(const half_t* __restrict__
   }
 }
 
-// Hm[r][i] = silu(G[r][i]) * U[r][i] with GU = [Mb][2F] fp32 (gate | up).  grid = (Mb, ceil(F/1024))
-__global__ __launch_bounds__(LL_WG) void pf_swiglu_kernel(const float* __restrict__ GU,
+// Hm[r][i] = silu(G[r][i]) * U[r][i] with GU = slices of [Mb][2F] fp32 (gate | up), summed here.
+// grid = (Mb, ceil(F/1024))
+__global__ __launch_bounds__(LL_WG) void pf_swiglu_kernel(const float* __restrict__ GU, SliceMap map,
                                                           const DevState* __restrict__ st,
                                                           half_t* __restrict__ Hm, int F) {
   const int r = blockIdx.x;
@@ -229,8 +323,9 @@ __global__ __launch_bounds__(LL_WG) void pf_swiglu_kernel(const float* __restric
   if (i >= F) return;
   h4 o = {0, 0, 0, 0};
   if (r < st->n_prompt) {
-    const f4 g = *reinterpret_cast<const f4*>(GU + (size_t)r * 2 * F + i);
-    const f4 u = *reinterpret_cast<const f4*>(GU + (size_t)r * 2 * F + F + i);
+    const float* row = GU + (size_t)r * 2 * F;
+    const f4 g = pf_slice_sum(row + i, slice_count(map, i), map.slice_floats);
+    const f4 u = pf_slice_sum(row + F + i, slice_count(map, F + i), map.slice_floats);
 #pragma unroll
     for (int j = 0; j < 4; ++j) o[j] = (half_t)(g[j] / (1.0f + expf(-g[j])) * u[j]);
   }
