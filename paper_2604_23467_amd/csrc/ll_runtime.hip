@@ -519,10 +519,10 @@ void enqueue_prefill_skinny(Instance* I, hipStream_t s, int Mb, bool with_head) 
     launch_skinny<SK_QKV>(I, s, a, Mb);
     dim3 agrid(c.n_heads, 1);
     if (c.head_dim == 128)
-      hipLaunchKernelGGL(pf_attn_kernel<128>, agrid, dim3(128), 0, s, Qh, I->kcache(l),
+      hipLaunchKernelGGL((pf_attn_kernel<128, 1>), agrid, dim3(128), PF_ATTN_LDS_BYTES(128, 1), s, Qh, I->kcache(l),
                          I->vcache(l), I->state(), Oh, d, c.max_seq, tb);
     else
-      hipLaunchKernelGGL(pf_attn_kernel<64>, agrid, dim3(128), 0, s, Qh, I->kcache(l),
+      hipLaunchKernelGGL((pf_attn_kernel<64, 1>), agrid, dim3(128), PF_ATTN_LDS_BYTES(64, 1), s, Qh, I->kcache(l),
                          I->vcache(l), I->state(), Oh, d, c.max_seq, tb);
     a.X = Oh; a.W[0] = (const half_t*)W.wo; a.W[1] = a.W[2] = nullptr; a.N = d; a.K = d; a.Xres = X;
     a.gain_next = (const half_t*)W.ffn_norm; a.Xh_next = Xn; a.ss_out = ss_ffn; a.ss_zero = ss_attn;
@@ -536,6 +536,31 @@ void enqueue_prefill_skinny(Instance* I, hipStream_t s, int Mb, bool with_head) 
     launch_skinny<SK_RES>(I, s, a, Mb);
   }
   if (with_head) enqueue_head(I, s, X, 1, 1);
+}
+
+// Prefill attention of layer l for a bucket of Mb >= 64 rows: the longer the prompt, the more
+// key groups share a query block (a chunk of a long prompt attends everything cached before it)
+template <int HD>
+void launch_attn_hd(Instance* I, hipStream_t s, int l, int Mb) {
+  const ll_config& c = I->cfg;
+  dim3 grid(c.n_heads, Mb / 64);
+  const half_t* Qh = I->at<half_t>(I->L.pf_q);
+  half_t* Oh = I->at<half_t>(I->L.pf_o);
+  const int groups = (Mb >= 256 || c.max_seq - 1 > kMaxPromptBucket) ? 4 : Mb >= 128 ? 2 : 1;
+  if (groups == 4)
+    hipLaunchKernelGGL((pf_attn_kernel<HD, 4>), grid, dim3(512), PF_ATTN_LDS_BYTES(HD, 4), s, Qh, I->kcache(l),
+                       I->vcache(l), I->state(), Oh, c.d_model, c.max_seq, 0);
+  else if (groups == 2)
+    hipLaunchKernelGGL((pf_attn_kernel<HD, 2>), grid, dim3(256), PF_ATTN_LDS_BYTES(HD, 2), s, Qh, I->kcache(l),
+                       I->vcache(l), I->state(), Oh, c.d_model, c.max_seq, 0);
+  else
+    hipLaunchKernelGGL((pf_attn_kernel<HD, 1>), grid, dim3(128), PF_ATTN_LDS_BYTES(HD, 1), s, Qh, I->kcache(l),
+                       I->vcache(l), I->state(), Oh, c.d_model, c.max_seq, 0);
+}
+
+void launch_attn(Instance* I, hipStream_t s, int l, int Mb) {
+  if (I->cfg.head_dim == 128) launch_attn_hd<128>(I, s, l, Mb);
+  else launch_attn_hd<64>(I, s, l, Mb);
 }
 
 void enqueue_prefill(Instance* I, hipStream_t s, int Mb, bool with_head = true) {
@@ -565,13 +590,7 @@ void enqueue_prefill(Instance* I, hipStream_t s, int Mb, bool with_head = true) 
       hipLaunchKernelGGL(pf_rope_kv_kernel, dim3(Mb), dim3(LL_WG), 0, s, P, qkv,
                          I->at<float2>(I->L.rope), I->state(), Qh, I->kcache(l), I->vcache(l), d,
                          c.head_dim, c.max_seq);
-    dim3 agrid(c.n_heads, Mb / 64);
-    if (c.head_dim == 128)
-      hipLaunchKernelGGL(pf_attn_kernel<128>, agrid, dim3(128), 0, s, Qh, I->kcache(l),
-                         I->vcache(l), I->state(), Oh, d, c.max_seq, 0);
-    else
-      hipLaunchKernelGGL(pf_attn_kernel<64>, agrid, dim3(128), 0, s, Qh, I->kcache(l),
-                         I->vcache(l), I->state(), Oh, d, c.max_seq, 0);
+    launch_attn(I, s, l, Mb);
     res = launch_gemm(I, s, Oh, W.wo, nullptr, nullptr, 1, d, d, d, Mb);
     res_part = P;
     hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(PF_NORM_THREADS), 0, s, X, (const half_t*)W.ffn_norm,
@@ -816,6 +835,12 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<64, 3, 1>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(64, 3)),
                    "hipFuncSetAttribute(gemm 64)")) return bail(rc);
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_attn_kernel<128, 4>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_ATTN_LDS_BYTES(128, 4)),
+                   "hipFuncSetAttribute(attention 128 x 4)")) return bail(rc);
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_attn_kernel<64, 4>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_ATTN_LDS_BYTES(64, 4)),
+                   "hipFuncSetAttribute(attention 64 x 4)")) return bail(rc);
   if (!hip_or_bail(hipMemset(I->at<unsigned>(L.mk_bar), 0, (size_t)MK_BAR_WORDS * 4), "hipMemset(bar)"))
     return bail(rc);
   {

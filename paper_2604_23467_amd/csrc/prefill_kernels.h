@@ -204,23 +204,35 @@ __global__ __launch_bounds__(LL_WG) void pf_rope_kv4_kernel(const float* __restr
 // k-slot j of lane half hf in k-step s holds key 16 s + 8 (j / 4) + 4 hf + j % 4.
 // The V tile is written to LDS transposed with its keys in exactly that order,
 // so an A fragment of V^T is one 16-byte LDS read.
-template <int HD>
-__global__ __launch_bounds__(128) void pf_attn_kernel(const half_t* __restrict__ Q,
-                                                      const half_t* __restrict__ kc,
-                                                      const half_t* __restrict__ vc,
-                                                      const DevState* __restrict__ st,
-                                                      half_t* __restrict__ O, int d, int max_seq,
-                                                      int frag_tb) {
+//
+// Long prompts make the last query blocks walk many key tiles, one after the other with nothing
+// else on the CU to hide a tile's chain of LDS round trips, matrix instructions and exponentials.
+// So G groups of two waves share a query block: group g takes the key tiles g, g + G, ... with
+// tile buffers of its own, and group 0 merges the groups' (max, sum, O^T) at the end.
+#define PF_ATTN_TILE_HALVES(HD) (32 * ((HD) + 8) + (HD) * 36)
+#define PF_ATTN_LDS_BYTES(HD, G) \
+  ((G) * PF_ATTN_TILE_HALVES(HD) * 2 > ((G) - 1) * 128 * ((HD) / 2 + 2) * 4 \
+       ? (G) * PF_ATTN_TILE_HALVES(HD) * 2 : ((G) - 1) * 128 * ((HD) / 2 + 2) * 4)
+
+template <int HD, int G>
+__global__ __launch_bounds__(128 * G) void pf_attn_kernel(const half_t* __restrict__ Q,
+                                                          const half_t* __restrict__ kc,
+                                                          const half_t* __restrict__ vc,
+                                                          const DevState* __restrict__ st,
+                                                          half_t* __restrict__ O, int d, int max_seq,
+                                                          int frag_tb) {
   constexpr int QB = 64, TK = 32, KS = HD / 16, DT = HD / 32, CPR = HD / 8;
   constexpr int K_STRIDE = HD + 8;   // halves: 16-byte fragment reads of 8 rows hit 8 distinct bank groups
-  constexpr int V_STRIDE = 40;       // halves per d row of V^T (32 keys + pad)
-  __shared__ __attribute__((aligned(16))) half_t Ks[TK * K_STRIDE];
-  __shared__ __attribute__((aligned(16))) half_t Vt[HD * V_STRIDE];
+  constexpr int V_STRIDE = 36;       // halves per d row of V^T (32 keys + pad): rows 18 words apart, see stash()
+  extern __shared__ __attribute__((aligned(16))) half_t pf_attn_lds[];
   const int h = blockIdx.x, q0 = blockIdx.y * QB;
   const int n = st->n_prompt, p0 = st->pos;   // rows of this chunk, positions cached before it
   if (q0 >= n) return;
-  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, ql = lane & 31;
+  const int tid = threadIdx.x & 127, lane = tid & 63, hf = lane >> 5, ql = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = __builtin_amdgcn_readfirstlane(threadIdx.x >> 7);
+  half_t* Ks = pf_attn_lds + grp * PF_ATTN_TILE_HALVES(HD);
+  half_t* Vt = Ks + TK * K_STRIDE;
   const int qi = q0 + wave * 32 + ql;
   const int wave_last_q = q0 + wave * 32 + 31;
   const float scale = 1.0f / sqrtf((float)HD);
@@ -242,21 +254,63 @@ __global__ __launch_bounds__(128) void pf_attn_kernel(const half_t* __restrict__
   const half_t* vh = vc + (size_t)h * max_seq * HD;
   const int last_key = p0 + min(q0 + QB, n) - 1;   // the block's last valid query attends it
 
-  for (int k0 = 0; k0 <= last_key; k0 += TK) {
-    __syncthreads();   // the previous tile has been consumed
-    for (int idx = tid; idx < TK * CPR; idx += 128) {
+  // K/V tiles travel global -> registers -> LDS; the loads run two tiles ahead of the tile being
+  // multiplied, so their latency (the whole cost of a tile otherwise) hides behind two tiles' work
+  constexpr int ITEMS = TK * CPR / 128;      // 16-byte pieces of K (and of V) per thread and tile
+  static_assert(TK * CPR % 128 == 0, "tile pieces divide over the workgroup");
+  // V pieces are dealt differently: a thread takes the same 8 d values of TWO neighbouring keys,
+  // which sit side by side in a V^T row, so the transposed store is 8 dwords instead of 16
+  // halves; and lanes run over 8 column pieces x 8 key pairs, which lands a wave's 64 dwords of
+  // one store in (almost) distinct banks: d rows are 18 words apart, 8 rows (one piece) 144.
+  // (With a key's 16 pieces on neighbouring lanes every store hit two banks 16 ways.)
+  constexpr int VITEMS = TK / 2 * CPR / 128;                  // key pairs x pieces per thread
+  static_assert(TK / 2 * CPR % 128 == 0 && CPR % 8 == 0, "V pieces divide over the workgroup");
+  auto v_item = [&](int it, int& c, int& key) {     // piece and even key (inside the tile) of this thread's item
+    const int x = (tid >> 6) + 2 * it;              // lanes: 8 pieces x 8 key pairs; wave and item: the high parts
+    c = (tid & 7) + 8 * (x % (CPR / 8));
+    key = 2 * (((tid >> 3) & 7) + 8 * (x / (CPR / 8)));
+  };
+  h8 kpre[2][ITEMS], vpre[2][2 * VITEMS];
+  auto fetch = [&](int k0, h8 (&kk)[ITEMS], h8 (&vv)[2 * VITEMS]) {
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+      const int idx = tid + it * 128;
       const int key = idx / CPR, c = idx - key * CPR;
       const int kr = min(k0 + key, p0 + n - 1);
-      *reinterpret_cast<h8*>(Ks + key * K_STRIDE + c * 8) = load_h8(kh + (size_t)kr * HD + c * 8);
-      const h8 v = load_h8(vh + (size_t)kr * HD + c * 8);
+      kk[it] = load_h8(kh + (size_t)kr * HD + c * 8);
+    }
+#pragma unroll
+    for (int it = 0; it < VITEMS; ++it) {
+      int c, key;
+      v_item(it, c, key);
+      vv[2 * it] = load_h8(vh + (size_t)min(k0 + key, p0 + n - 1) * HD + c * 8);
+      vv[2 * it + 1] = load_h8(vh + (size_t)min(k0 + key + 1, p0 + n - 1) * HD + c * 8);
+    }
+  };
+  auto stash = [&](const h8 (&kk)[ITEMS], const h8 (&vv)[2 * VITEMS]) {
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+      const int idx = tid + it * 128;
+      const int key = idx / CPR, c = idx - key * CPR;
+      *reinterpret_cast<h8*>(Ks + key * K_STRIDE + c * 8) = kk[it];
+    }
+#pragma unroll
+    for (int it = 0; it < VITEMS; ++it) {
+      int c, key;
+      v_item(it, c, key);
       // position of this key inside a V^T row: k-step s = key / 16, then half and slot as above
       const int r16 = key & 15;
       const int pos = ((key >> 4) * 2 + ((r16 & 7) >> 2)) * 8 + (r16 >> 3) * 4 + (r16 & 3);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) Vt[(c * 8 + e) * V_STRIDE + pos] = v[e];
+      for (int e = 0; e < 8; ++e) {
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        const h2 pr = {vv[2 * it][e], vv[2 * it + 1][e]};
+        *reinterpret_cast<h2*>(Vt + (c * 8 + e) * V_STRIDE + pos) = pr;
+      }
     }
-    __syncthreads();
-    if (k0 > p0 + wave_last_q) continue;   // whole tile above this wave's diagonal
+  };
+  auto tile = [&](int k0) {
+    if (k0 > p0 + wave_last_q) return;   // whole tile above this wave's diagonal
 
     f16v sc;
 #pragma unroll
@@ -293,9 +347,62 @@ __global__ __launch_bounds__(128) void pf_attn_kernel(const half_t* __restrict__
       for (int e = 0; e < 16; ++e) acc[t][e] *= corr;
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
-        const h8 a = *reinterpret_cast<const h8*>(Vt + (t * 32 + ql) * V_STRIDE + (s2 * 2 + hf) * 8);
+        const half_t* vp = Vt + (t * 32 + ql) * V_STRIDE + (s2 * 2 + hf) * 8;     // 8-byte aligned: rows are 72 bytes
+        const h4 a0 = *reinterpret_cast<const h4*>(vp), a1 = *reinterpret_cast<const h4*>(vp + 4);
+        const h8 a = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[s2], acc[t], 0, 0, 0);
       }
+    }
+  };
+
+  // group g walks tiles g, g + G, ...; every group makes the same number of trips (barriers)
+  constexpr int STEP = G * TK;
+  const int kg = grp * TK;
+  if (kg <= last_key) fetch(kg, kpre[0], vpre[0]);
+  if (kg + STEP <= last_key) fetch(kg + STEP, kpre[1], vpre[1]);
+  for (int kb = 0; kb <= last_key; kb += 2 * STEP) {
+    const int k0 = kb + kg;
+    __syncthreads();   // the previous tile has been consumed
+    if (k0 <= last_key) stash(kpre[0], vpre[0]);
+    __syncthreads();
+    if (k0 + 2 * STEP <= last_key) fetch(k0 + 2 * STEP, kpre[0], vpre[0]);
+    if (k0 <= last_key) tile(k0);
+    if (kb + STEP > last_key) break;
+    __syncthreads();
+    if (k0 + STEP <= last_key) stash(kpre[1], vpre[1]);
+    __syncthreads();
+    if (k0 + 3 * STEP <= last_key) fetch(k0 + 3 * STEP, kpre[1], vpre[1]);
+    if (k0 + STEP <= last_key) tile(k0 + STEP);
+  }
+
+  if constexpr (G > 1) {
+    // merge: groups 1.. leave (m, l, O^T) in LDS, [group - 1][value][thread of the group]
+    float* mg = reinterpret_cast<float*>(pf_attn_lds);
+    constexpr int VALS = DT * 16 + 2;
+    __syncthreads();   // all tiles consumed: the tile buffers are free
+    if (grp > 0) {
+      float* mine = mg + (size_t)(grp - 1) * VALS * 128 + tid;
+      mine[0] = m;
+      mine[128] = l;
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mine[(2 + t * 16 + e) * 128] = acc[t][e];
+    }
+    __syncthreads();
+    if (grp > 0) return;
+#pragma unroll
+    for (int g = 1; g < G; ++g) {
+      const float* other = mg + (size_t)(g - 1) * VALS * 128 + tid;
+      const float mo = other[0], lo = other[128];
+      const float mn = fmaxf(m, mo);                 // finite: group 0 always holds key 0
+      const float ca = __expf(m - mn), cb = __expf(mo - mn);   // a group without an unmasked key has mo = -inf, cb = 0
+      l = l * ca + lo * cb;
+      m = mn;
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[t][e] = acc[t][e] * ca + other[(2 + t * 16 + e) * 128] * cb;
     }
   }
 
