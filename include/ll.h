@@ -176,6 +176,16 @@ const char *ll_last_error(void);
  * blocked a step, captures overlapped with a replay, nanoseconds spent capturing }. */
 int ll_dbg_graph_stats(int64_t *out4);
 
+/* How the prefill projection GEMM out[rows][nmat * N] = A[rows][K] W^T deals its work (prompts of
+ * more than 32 tokens; host arithmetic only, needs no instance and no GPU):
+ * out6 = { rows per tile, row tiles, runs (workgroups per row tile), K slabs per run, K slabs per
+ * column tile as the runs count them (padded when runs end at tile borders), most slices any
+ * column tile is cut into }.  rows is a prompt bucket (64, 128, 256 or 512). */
+int ll_dbg_gemm_plan(int32_t N, int32_t K, int32_t nmat, int32_t rows, int32_t *out6);
+/* Number of slices that hold the partial products of output column col (0 <= col < nmat * N)
+ * under that plan, or a negative LL_E_* code. */
+int ll_dbg_gemm_slice_count(int32_t N, int32_t K, int32_t nmat, int32_t rows, int32_t col);
+
 /* Logits [vocab] of the most recent prefill/decode step, copied to the host. */
 int ll_dbg_get_logits(float *host_out);
 /* Residual stream [d_model] before the final norm of the most recent step. */

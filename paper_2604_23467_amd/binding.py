@@ -26,7 +26,7 @@ LAYER_KEYS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up",
 
 EXPORTS = ("ll_workspace_bytes", "ll_init", "ll_prefill", "ll_decode_step", "ll_decode_n", "ll_reset",
            "ll_set_sampling", "ll_shutdown", "ll_max_prompt", "ll_position", "ll_decode_mode", "ll_last_error", "ll_dbg_get_logits",
-           "ll_dbg_get_hidden", "ll_dbg_graph_stats", "ll_dbg_force_next_token", "ll_dbg_get_kv", "ll_dbg_profile_decode",
+           "ll_dbg_get_hidden", "ll_dbg_graph_stats", "ll_dbg_gemm_plan", "ll_dbg_gemm_slice_count", "ll_dbg_force_next_token", "ll_dbg_get_kv", "ll_dbg_profile_decode",
            "ll_dbg_time_decode", "ll_dbg_time_kernel_class", "ll_dbg_stream_copy", "ll_dbg_trace_decode")
 
 
@@ -85,6 +85,10 @@ def load():
     L.ll_last_error.argtypes = []
     L.ll_dbg_get_logits.restype = C.c_int
     L.ll_dbg_get_logits.argtypes = [C.POINTER(C.c_float)]
+    L.ll_dbg_gemm_plan.restype = C.c_int
+    L.ll_dbg_gemm_plan.argtypes = [C.c_int32] * 4 + [C.POINTER(C.c_int32)]
+    L.ll_dbg_gemm_slice_count.restype = C.c_int
+    L.ll_dbg_gemm_slice_count.argtypes = [C.c_int32] * 5
     L.ll_dbg_graph_stats.restype = C.c_int
     L.ll_dbg_graph_stats.argtypes = [C.POINTER(C.c_int64)]
     L.ll_dbg_get_hidden.restype = C.c_int
@@ -136,6 +140,17 @@ def ll_set_sampling_raw(temperature, top_k, top_p, seed):
     """ll_set_sampling on whatever instance the library holds (an error without one)."""
     return _check(load().ll_set_sampling(C.c_float(temperature), C.c_int32(top_k), C.c_float(top_p),
                                          C.c_uint64(seed)))
+
+
+def ll_dbg_gemm_plan(N, K, nmat, rows):
+    """Work distribution of the prefill projection GEMM (host arithmetic, no GPU needed)."""
+    out = (C.c_int32 * 6)()
+    _check(load().ll_dbg_gemm_plan(N, K, nmat, rows, out))
+    return dict(zip(("row_tile", "row_tiles", "runs", "quota", "tile_slabs", "max_slices"), out))
+
+
+def ll_dbg_gemm_slice_count(N, K, nmat, rows, col):
+    return _check(load().ll_dbg_gemm_slice_count(N, K, nmat, rows, col))
 
 
 def ll_last_error():

@@ -1044,6 +1044,23 @@ int ll_decode_mode(void) {
   return g->use_mega ? LL_MODE_PERSISTENT_GRAPH : LL_MODE_MULTIKERNEL_GRAPH;
 }
 
+int ll_dbg_gemm_plan(int32_t N, int32_t K, int32_t nmat, int32_t rows, int32_t* out6) {
+  if (!out6 || N < 1 || K < 1 || nmat < 1 || nmat > 3 || (rows != 64 && rows != 128 && rows != 256 && rows != 512))
+    return fail(LL_E_BAD_ARG, "ll_dbg_gemm_plan: bad argument");
+  const GemmPlan p = gemm_plan(N, K, nmat, rows, nmat * N);
+  out6[0] = gemm_bm(rows); out6[1] = p.mtiles; out6[2] = p.runs; out6[3] = p.map.quota;
+  out6[4] = p.map.nslabs; out6[5] = p.max_slices;
+  return LL_OK;
+}
+
+int ll_dbg_gemm_slice_count(int32_t N, int32_t K, int32_t nmat, int32_t rows, int32_t col) {
+  if (N < 1 || K < 1 || nmat < 1 || nmat > 3 || (rows != 64 && rows != 128 && rows != 256 && rows != 512) ||
+      col < 0 || col >= nmat * N)
+    return fail(LL_E_BAD_ARG, "ll_dbg_gemm_slice_count: bad argument");
+  const GemmPlan p = gemm_plan(N, K, nmat, rows, nmat * N);
+  return slice_count(p.map, col);
+}
+
 int ll_dbg_graph_stats(int64_t* out4) {
   if (!g) return fail(LL_E_NOT_INIT, "ll_dbg_graph_stats: not initialised");
   if (!out4) return fail(LL_E_BAD_ARG, "ll_dbg_graph_stats: null output");
