@@ -170,6 +170,48 @@ int ll_decode_mode(void);
 /* Text of the most recent failure on this thread ("" if none). */
 const char *ll_last_error(void);
 
+/* ---- batched lock-step decoding over a paged KV cache ----
+ *
+ * The paper stays at batch 1 and takes its KV cache from a paged-attention library (Sec. II-C,
+ * Sec. V-A); these calls open the regime it leaves out on top of an initialised instance: up to 16
+ * sequences advance one token per call, each projection of the step is one 16-row matrix product
+ * over the weights instead of 16 GEMVs, and every sequence keeps its K/V rows in pages of
+ * `page_tokens` positions taken from a common pool, so memory follows the sequences' real lengths.
+ * Greedy selection only.  Available in the default (multi-kernel graph) and eager modes; the step
+ * is one captured graph, like the single-sequence step.
+ *
+ * Ownership: `pool` is device memory of ll_batch_pool_bytes() bytes, 256-byte aligned, owned by the
+ * caller and kept alive until ll_batch_close (or ll_shutdown, which closes the batch).  The calls
+ * share the instance's stream and prefill scratch: ll_batch_add runs the prompt through the
+ * single-sequence prefill, which REPLACES the context of ll_prefill / ll_decode_step.
+ * Errors: negative LL_E_* codes, state unchanged; not thread-safe. */
+
+/* Bytes of `pool` for pages of page_tokens positions, n_pages of them (page 0 is reserved, so
+ * n_pages - 1 are usable); 0 without an instance or for arguments ll_batch_open would reject. */
+size_t ll_batch_pool_bytes(int32_t page_tokens, int32_t n_pages);
+/* Opens batched decoding for up to max_batch (1..16) concurrent sequences.  LL_E_BAD_CONFIG unless
+ * d_model % 16 == 0, d_model <= 4096, ffn_hidden % 8 == 0, vocab % 16 == 0, head_dim 64 or 128. */
+int ll_batch_open(int32_t max_batch, int32_t page_tokens, int32_t n_pages, void *pool, size_t pool_bytes);
+/* Adds a sequence: prefills tokens[0..n) (host pointer), moves its cache rows into freshly taken
+ * pages, stores the first generated token in *first_token and returns the slot (>= 0) the sequence
+ * occupies.  LL_E_CAPACITY when no slot or not enough pages are free, or n + 1 > max_seq. */
+int32_t ll_batch_add(const int32_t *tokens, int32_t n, int32_t *first_token);
+/* One decode step of every sequence in the batch.  out_tokens (host, max_batch entries) receives
+ * the new token of every occupied slot and -1 for free slots.  A sequence that crosses a page border
+ * takes a page first: LL_E_CAPACITY (nothing ran) when the pool is exhausted or a sequence is at
+ * max_seq - remove one and call again. */
+int ll_batch_step(int32_t *out_tokens);
+/* Ends the sequence in `slot` and returns its pages to the pool. */
+int ll_batch_remove(int32_t slot);
+/* Closes batched decoding (graphs and host buffers; the pool goes back to the caller). */
+int ll_batch_close(void);
+/* Test hooks: logits [vocab] of `slot` from the most recent ll_batch_step; override of the token the
+ * slot feeds next; k steps back to back timed on the device (milliseconds in *ms_out; the pages the
+ * k steps write are taken first, LL_E_CAPACITY and nothing run if the pool cannot supply them). */
+int ll_batch_dbg_get_logits(int32_t slot, float *host_out);
+int ll_batch_dbg_force_next_token(int32_t slot, int32_t tok);
+int ll_batch_dbg_time_steps(int32_t k, float *ms_out);
+
 /* ---- measurement and test hooks (not part of the four-call contract) ---- */
 
 /* Per-length graph mode: out4 = { replays that found their graph in the buffer, captures that

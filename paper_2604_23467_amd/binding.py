@@ -26,6 +26,8 @@ LAYER_KEYS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up",
 
 EXPORTS = ("ll_workspace_bytes", "ll_init", "ll_prefill", "ll_decode_step", "ll_decode_n", "ll_reset",
            "ll_set_sampling", "ll_shutdown", "ll_max_prompt", "ll_position", "ll_decode_mode", "ll_last_error", "ll_dbg_get_logits",
+           "ll_batch_pool_bytes", "ll_batch_open", "ll_batch_add", "ll_batch_step", "ll_batch_remove", "ll_batch_close",
+           "ll_batch_dbg_get_logits", "ll_batch_dbg_force_next_token", "ll_batch_dbg_time_steps",
            "ll_dbg_get_hidden", "ll_dbg_graph_stats", "ll_dbg_gemm_plan", "ll_dbg_gemm_slice_count", "ll_dbg_force_next_token", "ll_dbg_get_kv", "ll_dbg_profile_decode",
            "ll_dbg_time_decode", "ll_dbg_time_kernel_class", "ll_dbg_stream_copy", "ll_dbg_trace_decode")
 
@@ -85,6 +87,24 @@ def load():
     L.ll_last_error.argtypes = []
     L.ll_dbg_get_logits.restype = C.c_int
     L.ll_dbg_get_logits.argtypes = [C.POINTER(C.c_float)]
+    L.ll_batch_pool_bytes.restype = C.c_size_t
+    L.ll_batch_pool_bytes.argtypes = [C.c_int32, C.c_int32]
+    L.ll_batch_open.restype = C.c_int
+    L.ll_batch_open.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t]
+    L.ll_batch_add.restype = C.c_int32
+    L.ll_batch_add.argtypes = [C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32)]
+    L.ll_batch_step.restype = C.c_int
+    L.ll_batch_step.argtypes = [C.POINTER(C.c_int32)]
+    L.ll_batch_remove.restype = C.c_int
+    L.ll_batch_remove.argtypes = [C.c_int32]
+    L.ll_batch_close.restype = C.c_int
+    L.ll_batch_close.argtypes = []
+    L.ll_batch_dbg_get_logits.restype = C.c_int
+    L.ll_batch_dbg_get_logits.argtypes = [C.c_int32, C.POINTER(C.c_float)]
+    L.ll_batch_dbg_force_next_token.restype = C.c_int
+    L.ll_batch_dbg_force_next_token.argtypes = [C.c_int32, C.c_int32]
+    L.ll_batch_dbg_time_steps.restype = C.c_int
+    L.ll_batch_dbg_time_steps.argtypes = [C.c_int32, C.POINTER(C.c_float)]
     L.ll_dbg_gemm_plan.restype = C.c_int
     L.ll_dbg_gemm_plan.argtypes = [C.c_int32] * 4 + [C.POINTER(C.c_int32)]
     L.ll_dbg_gemm_slice_count.restype = C.c_int
@@ -255,6 +275,48 @@ class Session:
         out = np.empty(self.cfg["vocab"], dtype=np.float32)
         _check(self.lib.ll_dbg_get_logits(out.ctypes.data_as(C.POINTER(C.c_float))))
         return out
+
+    # ---- batched decoding over a paged KV cache ----
+    def ll_batch_open(self, max_batch, page_tokens, n_pages):
+        nbytes = int(self.lib.ll_batch_pool_bytes(page_tokens, n_pages))
+        if nbytes == 0:
+            raise LLError(LL_E_BAD_ARG, "ll_batch_pool_bytes rejected the arguments")
+        self.pool = self.torch.empty(nbytes + 256, dtype=self.torch.uint8, device=self.device)
+        ptr = (self.pool.data_ptr() + 255) // 256 * 256
+        self.max_batch = max_batch
+        return _check(self.lib.ll_batch_open(max_batch, page_tokens, n_pages, C.c_void_p(ptr), C.c_size_t(nbytes)))
+
+    def ll_batch_add(self, tokens):
+        arr = (C.c_int32 * len(tokens))(*[int(t) for t in tokens])
+        first = C.c_int32(-1)
+        slot = _check(self.lib.ll_batch_add(arr, len(tokens), C.byref(first)))
+        return slot, int(first.value)
+
+    def ll_batch_step(self):
+        out = (C.c_int32 * self.max_batch)()
+        _check(self.lib.ll_batch_step(out))
+        return list(out)
+
+    def ll_batch_remove(self, slot):
+        return _check(self.lib.ll_batch_remove(slot))
+
+    def ll_batch_close(self):
+        rc = _check(self.lib.ll_batch_close())
+        self.pool = None
+        return rc
+
+    def ll_batch_dbg_get_logits(self, slot):
+        out = np.empty(self.cfg["vocab"], dtype=np.float32)
+        _check(self.lib.ll_batch_dbg_get_logits(slot, out.ctypes.data_as(C.POINTER(C.c_float))))
+        return out
+
+    def ll_batch_dbg_force_next_token(self, slot, tok):
+        return _check(self.lib.ll_batch_dbg_force_next_token(slot, int(tok)))
+
+    def ll_batch_dbg_time_steps(self, k):
+        ms = C.c_float(0)
+        _check(self.lib.ll_batch_dbg_time_steps(k, C.byref(ms)))
+        return float(ms.value)
 
     def ll_dbg_graph_stats(self):
         out = (C.c_int64 * 4)()

@@ -1,0 +1,186 @@
+// Batched lock-step decoding over a paged KV cache: the kernels that have no counterpart in the
+// single-sequence path.  The paper embeds a paged-KV attention library for its cache (Sec. II-C,
+// Sec. V-A) and keeps batch 1 (Sec. V-A); this is the batch > 1 regime it leaves open, where the
+// projections of a step become 16-row matrix products (the short-prompt kernels of
+// prefill_skinny.h, one row per sequence) instead of GEMVs.
+//
+// A sequence owns pages of `page_tokens` consecutive cache rows; page_table[slot][i] is the first
+// cache row of its i-th page, so position p of slot b lives in cache row
+// page_table[b][p / page_tokens] + p % page_tokens of the per-layer pools [head][pool rows][head_dim].
+// Free slots point at page 0, which no sequence ever owns: whatever they compute lands there.
+#pragma once
+#include "ll_device.h"
+
+#define BT_MAX_BATCH 16
+
+struct BatchState {
+  int32_t pos[BT_MAX_BATCH];         // cached positions of slot b = position of the token it feeds next
+  int32_t next_token[BT_MAX_BATCH];  // token slot b feeds next
+  int32_t active[BT_MAX_BATCH];      // 0: free slot
+};
+
+// Attention of slot b's new query (position pos[b], already written to the cache) for one head.
+// grid = (heads, BT_MAX_BATCH), 256 threads.  As in the single-sequence kernel a key row is read
+// by HD / 8 adjacent lanes with one 16-byte load each and every lane group keeps an online-softmax
+// state over the keys it is dealt; groups merge by shuffles, waves through LDS.  Output: fp16,
+// in the fragment-major operand layout of the O projection.
+#define BT_ATTN_THREADS 256
+template <int HD>
+__global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
+    const half_t* __restrict__ Q, const half_t* __restrict__ kc, const half_t* __restrict__ vc,
+    const BatchState* __restrict__ bs, const int* __restrict__ page_table, int pt_stride, int page_tokens,
+    half_t* __restrict__ O, int d, int pool_rows) {
+  constexpr int LPR = HD / 8;      // lanes per key row
+  constexpr int GPW = 64 / LPR;    // lane groups per wave
+  constexpr int NW = BT_ATTN_THREADS / 64;
+  constexpr int UK = 4;            // keys in flight per group
+  __shared__ float s_m[NW], s_l[NW], s_acc[NW][HD];
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int gi = lane / LPR, li = lane % LPR;
+  if (!bs->active[b]) {
+    if (tid < HD / 8) *reinterpret_cast<h8*>(O + act_offset(b, h * HD + tid * 8, d, 1)) = h8{0, 0, 0, 0, 0, 0, 0, 0};
+    return;
+  }
+  const int n_keys = bs->pos[b] + 1;
+  const float scale = 1.0f / sqrtf((float)HD);
+  float qv[8];
+  {
+    const h8 q = load_h8(Q + (size_t)b * d + h * HD + li * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) qv[e] = (float)q[e] * scale;
+  }
+  const half_t* kh = kc + (size_t)h * pool_rows * HD + li * 8;
+  const half_t* vh = vc + (size_t)h * pool_rows * HD + li * 8;
+  const int* pt = page_table + b * pt_stride;
+
+  float m = -INFINITY, l = 0.f, acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+  constexpr int STRIDE = NW * GPW;
+  for (int base = wave * GPW; base < n_keys; base += STRIDE * UK) {
+    h8 kk[UK], vv[UK];
+#pragma unroll
+    for (int j = 0; j < UK; ++j) {
+      const int u = min(base + j * STRIDE + gi, n_keys - 1);
+      const int pg = u / page_tokens;
+      const size_t row = (size_t)(pt[pg] + (u - pg * page_tokens));
+      kk[j] = load_h8(kh + row * HD);
+      vv[j] = load_h8(vh + row * HD);
+    }
+#pragma unroll
+    for (int j = 0; j < UK; ++j) {
+      float dot = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dot += qv[e] * (float)kk[j][e];
+      dot = group_sum<LPR>(dot);
+      if (base + j * STRIDE + gi < n_keys) {
+        const float mn = fmaxf(m, dot);
+        const float corr = __expf(m - mn);
+        const float p = __expf(dot - mn);
+        l = l * corr + p;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = acc[e] * corr + p * (float)vv[j][e];
+        m = mn;
+      }
+    }
+  }
+  {
+    float M = m;
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
+    const float w = (M > -INFINITY) ? __expf(m - M) : 0.f;   // empty groups (m = -inf) weigh 0
+    l *= w;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] *= w;
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+      l += __shfl_xor(l, off);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += __shfl_xor(acc[e], off);
+    }
+    if (gi == 0) {
+      if (li == 0) { s_m[wave] = M; s_l[wave] = l; }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s_acc[wave][li * 8 + e] = acc[e];
+    }
+  }
+  __syncthreads();
+  if (tid < HD / 8) {
+    float M = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) M = fmaxf(M, s_m[i]);
+    float L = 0.f, A[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+      const float w = (s_m[i] > -INFINITY) ? __expf(s_m[i] - M) : 0.f;    // M is finite: key 0 is always attended
+      L += s_l[i] * w;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) A[e] += s_acc[i][tid * 8 + e] * w;
+    }
+    const float rl = 1.0f / L;
+    h8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (half_t)(A[e] * rl);
+    *reinterpret_cast<h8*>(O + act_offset(b, h * HD + tid * 8, d, 1)) = o;
+  }
+}
+
+// Greedy token of every slot (lowest index among equal maxima) and the slots' state advance.
+// grid = BT_MAX_BATCH, 1024 threads; out = device-visible host memory, -1 for free slots.
+__global__ __launch_bounds__(1024) void bt_select_kernel(const float* __restrict__ logits, int vocab,
+                                                         BatchState* bs, int* out) {
+  __shared__ float sv[1024];
+  __shared__ int si[1024];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  if (!bs->active[b]) {
+    if (tid == 0) out[b] = -1;
+    return;
+  }
+  const float* row = logits + (size_t)b * vocab;
+  float bv = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int i = tid; i < vocab; i += 1024) {
+    const float v = row[i];
+    if (v > bv) { bv = v; bi = i; }          // i ascends: the first maximum stays
+  }
+  sv[tid] = bv;
+  si[tid] = bi;
+  __syncthreads();
+  for (int off = 512; off > 0; off >>= 1) {
+    if (tid < off) {
+      const float v = sv[tid + off];
+      const int ix = si[tid + off];
+      if (v > sv[tid] || (v == sv[tid] && ix < si[tid])) { sv[tid] = v; si[tid] = ix; }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    int tok = si[0];
+    if (tok == 0x7fffffff) tok = 0;          // every logit NaN: still a valid id
+    bs->next_token[b] = tok;
+    bs->pos[b] = bs->pos[b] + 1;
+    out[b] = tok;
+  }
+}
+
+// After a prompt has been prefilled into the contiguous single-sequence cache: copy its rows
+// 0 .. n - 1 into the pages of slot b.  grid = (n, layers * 2); a workgroup moves one cache row of
+// every head of one layer's K or V.
+__global__ __launch_bounds__(LL_WG) void bt_scatter_kernel(const half_t* __restrict__ src_kv, size_t src_layer_halves,
+                                                           int src_rows, half_t* __restrict__ dst_kv,
+                                                           size_t dst_layer_halves, int dst_rows,
+                                                           const int* __restrict__ page_table, int pt_stride,
+                                                           int page_tokens, int slot, int n_heads, int head_dim) {
+  const int r = blockIdx.x, lk = blockIdx.y;      // lk = layer * 2 + (0: K, 1: V)
+  const int pg = r / page_tokens;
+  const size_t drow = (size_t)(page_table[slot * pt_stride + pg] + (r - pg * page_tokens));
+  const half_t* s = src_kv + (size_t)lk * src_layer_halves;
+  half_t* d = dst_kv + (size_t)lk * dst_layer_halves;
+  const int per_head = head_dim / 8;
+  for (int i = threadIdx.x; i < n_heads * per_head; i += LL_WG) {
+    const int h = i / per_head, c = i - h * per_head;
+    *reinterpret_cast<h8*>(d + ((size_t)h * dst_rows + drow) * head_dim + c * 8) =
+        load_h8(s + ((size_t)h * src_rows + r) * head_dim + c * 8);
+  }
+}

@@ -20,6 +20,7 @@
 #include "prefill_kernels.h"
 #include "prefill_skinny.h"
 #include "prefill_gemm.h"
+#include "batch_kernels.h"
 
 namespace {
 
@@ -187,8 +188,12 @@ Layout make_layout(const ll_config& c) {
   return L;
 }
 
+struct Batch;
+void destroy_batch(Batch* B);
+
 struct Instance {
   ll_config cfg;
+  Batch* batch = nullptr;       // batched decoding over a paged cache, opened on top of the instance
   Layout L;
   std::vector<ll_layer_weights> layers;
   ll_weights w;
@@ -631,6 +636,8 @@ int write_state(Instance* I, int pos, int next_token, int n_prompt, int steps) {
 
 void destroy(Instance* I) {
   if (!I) return;
+  destroy_batch(I->batch);
+  I->batch = nullptr;
   if (I->lg_future.valid()) (void)I->lg_future.get();
   if (I->lg_pending.exec) (void)hipGraphExecDestroy(I->lg_pending.exec);
   if (I->lg_pending.graph) (void)hipGraphDestroy(I->lg_pending.graph);
@@ -735,6 +742,124 @@ int run_decode_steps(Instance* I, int k) {
     else HIPCHK(hipGraphLaunch(I->dec_exec, I->stream));
   }
   if (eager(I)) HIPCHK(hipGetLastError());
+  return LL_OK;
+}
+
+
+// ---- batched lock-step decoding over a paged KV cache (batch_kernels.h) ----
+struct BatchLayout {
+  size_t kv, page_table, state, dstate, logits, total;
+  size_t kv_layer_halves;     // halves per layer per K or V pool
+  int pool_rows, pt_stride;
+};
+
+BatchLayout make_batch_layout(const ll_config& c, int page_tokens, int n_pages) {
+  BatchLayout B{};
+  B.pool_rows = page_tokens * n_pages;
+  B.pt_stride = (c.max_seq + page_tokens - 1) / page_tokens;
+  B.kv_layer_halves = (size_t)c.n_heads * B.pool_rows * c.head_dim;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  B.kv = take((size_t)c.n_layers * 2 * B.kv_layer_halves * 2);
+  B.page_table = take((size_t)BT_MAX_BATCH * B.pt_stride * 4);
+  B.state = take(sizeof(BatchState));
+  B.dstate = take(sizeof(DevState));
+  B.logits = take((size_t)BT_MAX_BATCH * c.vocab * 4);
+  B.total = off;
+  return B;
+}
+
+struct Batch {
+  BatchLayout L;
+  char* pool = nullptr;
+  int max_batch = 0, page_tokens = 0, n_pages = 0;
+  std::vector<int> free_pages;                 // page 0 is never handed out: free slots write there
+  std::vector<std::vector<int>> pages;         // pages of every slot, in order
+  BatchState* h_state = nullptr;               // pinned mirrors of the device state and page table
+  int* h_table = nullptr;
+  int* h_out = nullptr;                        // pinned, device-visible: tokens of the last step
+  int* d_out = nullptr;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+  template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(pool + off); }
+  half_t* kpool(int layer) const { return at<half_t>(L.kv) + (size_t)layer * 2 * L.kv_layer_halves; }
+  half_t* vpool(int layer) const { return kpool(layer) + L.kv_layer_halves; }
+};
+
+void destroy_batch(Batch* B) {
+  if (!B) return;
+  if (B->exec) (void)hipGraphExecDestroy(B->exec);
+  if (B->graph) (void)hipGraphDestroy(B->graph);
+  if (B->h_state) (void)hipHostFree(B->h_state);
+  if (B->h_table) (void)hipHostFree(B->h_table);
+  if (B->h_out) (void)hipHostFree(B->h_out);
+  delete B;
+}
+
+// One decode step of all slots: the 16 rows of the short-prompt kernels are the 16 slots.
+void enqueue_batch_step(Instance* I, hipStream_t s) {
+  Batch* B = I->batch;
+  const ll_config& c = I->cfg;
+  const int d = c.d_model, F = c.ffn_hidden, Mb = BT_MAX_BATCH;
+  float* X = I->at<float>(I->L.pf_x);
+  half_t* Xn = I->at<half_t>(I->L.pf_xn);
+  half_t* Qh = I->at<half_t>(I->L.pf_q);
+  half_t* Oh = I->at<half_t>(I->L.pf_o);
+  half_t* Hm = I->at<half_t>(I->L.pf_h);
+  float* ss_attn = I->at<float>(I->L.pf_ss);
+  float* ss_ffn = ss_attn + 64 * SK_SS_STRIDE;
+  BatchState* bs = B->at<BatchState>(B->L.state);
+  const DevState* st = B->at<DevState>(B->L.dstate);          // n_prompt = 16 rows, pos unused
+  const int* table = B->at<int>(B->L.page_table);
+  hipLaunchKernelGGL(pf_embed_norm_kernel, dim3(Mb), dim3(LL_WG), 0, s, (const half_t*)I->w.tok_emb,
+                     bs->next_token, st, (const half_t*)I->layers[0].attn_norm, X, Xn, ss_attn, ss_ffn, d, 1);
+  for (int l = 0; l < c.n_layers; ++l) {
+    const ll_layer_weights& W = I->layers[l];
+    SkinnyArgs a{};
+    a.st = st; a.head_dim = c.head_dim; a.max_seq = B->L.pool_rows; a.eps = c.rms_eps;
+    a.X = Xn; a.W[0] = (const half_t*)W.wq; a.W[1] = (const half_t*)W.wk; a.W[2] = (const half_t*)W.wv;
+    a.N = d; a.K = d; a.Q = Qh; a.kc = B->kpool(l); a.vc = B->vpool(l); a.rope = I->at<float2>(I->L.rope);
+    a.ss_in = ss_attn;
+    a.row_pos = bs->pos; a.page_table = table; a.pt_stride = B->L.pt_stride; a.page_tokens = B->page_tokens;
+    launch_skinny<SK_QKV>(I, s, a, Mb);
+    dim3 agrid(c.n_heads, Mb);
+    if (c.head_dim == 128)
+      hipLaunchKernelGGL(bt_attn_kernel<128>, agrid, dim3(BT_ATTN_THREADS), 0, s, Qh, B->kpool(l), B->vpool(l), bs,
+                         table, B->L.pt_stride, B->page_tokens, Oh, d, B->L.pool_rows);
+    else
+      hipLaunchKernelGGL(bt_attn_kernel<64>, agrid, dim3(BT_ATTN_THREADS), 0, s, Qh, B->kpool(l), B->vpool(l), bs,
+                         table, B->L.pt_stride, B->page_tokens, Oh, d, B->L.pool_rows);
+    a.row_pos = nullptr; a.page_table = nullptr;
+    a.X = Oh; a.W[0] = (const half_t*)W.wo; a.W[1] = a.W[2] = nullptr; a.N = d; a.K = d; a.Xres = X;
+    a.gain_next = (const half_t*)W.ffn_norm; a.Xh_next = Xn; a.ss_out = ss_ffn; a.ss_zero = ss_attn;
+    launch_skinny<SK_RES>(I, s, a, Mb);
+    a.X = Xn; a.W[0] = (const half_t*)W.w_gate; a.W[1] = (const half_t*)W.w_up; a.N = F; a.K = d; a.Hout = Hm;
+    a.ss_in = ss_ffn;
+    launch_skinny<SK_GATEUP>(I, s, a, Mb);
+    a.X = Hm; a.W[0] = (const half_t*)W.w_down; a.W[1] = nullptr; a.N = d; a.K = F; a.Xres = X;
+    a.gain_next = l + 1 < c.n_layers ? (const half_t*)I->layers[l + 1].attn_norm : (const half_t*)I->w.final_norm;
+    a.Xh_next = Xn; a.ss_out = ss_attn; a.ss_zero = ss_ffn;
+    launch_skinny<SK_RES>(I, s, a, Mb);
+  }
+  {
+    // LM head of all 16 rows: the wide persistent projection with a plain fp32 epilogue
+    SkinnyArgs a{};
+    a.st = st; a.eps = c.rms_eps; a.head_dim = c.head_dim; a.max_seq = c.max_seq;
+    a.X = Xn; a.W[0] = (const half_t*)I->w.lm_head; a.N = c.vocab; a.K = d;
+    a.ss_in = ss_attn; a.logits = B->at<float>(B->L.logits);
+    a.zeros_off = I->at<half_t>(I->L.zeros) - a.X;
+    const int units = skinny_units(SK_LOGITS, c.vocab);
+    hipLaunchKernelGGL((pf_skinny_persist_kernel<SK_LOGITS, 1>), dim3(units < g_num_cus ? units : g_num_cus),
+                       dim3(SK_THREADS), 0, s, a);
+  }
+  hipLaunchKernelGGL(bt_select_kernel, dim3(Mb), dim3(1024), 0, s, B->at<float>(B->L.logits), c.vocab, bs, B->d_out);
+}
+
+int push_batch_state(Instance* I) {
+  Batch* B = I->batch;
+  HIPCHK(hipMemcpyAsync(B->at<BatchState>(B->L.state), B->h_state, sizeof(BatchState), hipMemcpyHostToDevice, I->stream));
+  HIPCHK(hipMemcpyAsync(B->at<int>(B->L.page_table), B->h_table, (size_t)BT_MAX_BATCH * B->L.pt_stride * 4,
+                        hipMemcpyHostToDevice, I->stream));
   return LL_OK;
 }
 
@@ -1036,6 +1161,276 @@ int32_t ll_decode_n(int32_t k, int32_t* out_tokens) {
 }
 
 int32_t ll_decode_step(void) { return ll_decode_n(1, nullptr); }
+
+/* ---- batched lock-step decoding over a paged KV cache ---- */
+
+size_t ll_batch_pool_bytes(int32_t page_tokens, int32_t n_pages) {
+  if (!g || page_tokens < 1 || n_pages < 2) return 0;
+  return make_batch_layout(g->cfg, page_tokens, n_pages).total;
+}
+
+int ll_batch_open(int32_t max_batch, int32_t page_tokens, int32_t n_pages, void* pool, size_t pool_bytes) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_batch_open: not initialised");
+  Instance* I = g;
+  if (I->batch) return fail(LL_E_STATE, "ll_batch_open: already open; call ll_batch_close first");
+  if (max_batch < 1 || max_batch > BT_MAX_BATCH)
+    return fail(LL_E_BAD_ARG, "ll_batch_open: max_batch = %d outside [1, %d]", max_batch, BT_MAX_BATCH);
+  if (page_tokens < 1 || n_pages < 2)
+    return fail(LL_E_BAD_ARG, "ll_batch_open: need page_tokens >= 1 and n_pages >= 2 (page 0 is reserved)");
+  if (!pool) return fail(LL_E_BAD_ARG, "ll_batch_open: null pool");
+  const ll_config& c = I->cfg;
+  const int per_wave = (((c.d_model + 31) >> 5) + SK_WAVES - 1) / SK_WAVES;
+  if (!I->skinny || c.vocab % 16 != 0 || per_wave > SKP_KSTEPS || (c.head_dim != 64 && c.head_dim != 128))
+    return fail(LL_E_BAD_CONFIG, "ll_batch_open: needs d_model %% 16 == 0, d_model <= 4096, ffn_hidden %% 8 == 0, "
+                                 "vocab %% 16 == 0 and head_dim 64 or 128");
+  if (I->use_mega || I->per_length)
+    return fail(LL_E_STATE, "ll_batch_open: available with the multi-kernel graph and eager modes only");
+  const BatchLayout BL = make_batch_layout(c, page_tokens, n_pages);
+  if (pool_bytes < BL.total)
+    return fail(LL_E_WORKSPACE, "ll_batch_open: pool has %zu bytes, %zu needed", pool_bytes, BL.total);
+  if (reinterpret_cast<uintptr_t>(pool) % kAlign)
+    return fail(LL_E_WORKSPACE, "ll_batch_open: pool must be %zu-byte aligned", kAlign);
+
+  Batch* B = new Batch();
+  B->L = BL;
+  B->pool = static_cast<char*>(pool);
+  B->max_batch = max_batch; B->page_tokens = page_tokens; B->n_pages = n_pages;
+  for (int p = n_pages - 1; p >= 1; --p) B->free_pages.push_back(p);
+  B->pages.resize(BT_MAX_BATCH);
+  int rc = LL_OK;
+  auto bail = [&](int code) { I->batch = nullptr; destroy_batch(B); return code; };
+  auto ok = [&](hipError_t e, const char* what) {
+    if (e != hipSuccess) { rc = fail(LL_E_HIP, "%s: %s", what, hipGetErrorString(e)); return false; }
+    return true;
+  };
+  if (!ok(hipHostMalloc((void**)&B->h_state, sizeof(BatchState), hipHostMallocDefault), "hipHostMalloc(batch state)"))
+    return bail(rc);
+  if (!ok(hipHostMalloc((void**)&B->h_table, (size_t)BT_MAX_BATCH * BL.pt_stride * 4, hipHostMallocDefault),
+          "hipHostMalloc(page table)")) return bail(rc);
+  if (!ok(hipHostMalloc((void**)&B->h_out, BT_MAX_BATCH * 4, hipHostMallocMapped), "hipHostMalloc(batch out)"))
+    return bail(rc);
+  if (!ok(hipHostGetDevicePointer((void**)&B->d_out, B->h_out, 0), "hipHostGetDevicePointer(batch out)")) return bail(rc);
+  memset(B->h_state, 0, sizeof(BatchState));
+  memset(B->h_table, 0, (size_t)BT_MAX_BATCH * BL.pt_stride * 4);          // every slot: page 0
+  for (int b = 0; b < BT_MAX_BATCH; ++b) B->h_out[b] = -1;
+  I->batch = B;
+  {
+    DevState* hs = reinterpret_cast<DevState*>(I->host_stage);
+    memset(hs, 0, sizeof(DevState));
+    hs->n_prompt = BT_MAX_BATCH;
+    if (!ok(hipMemcpyAsync(B->at<DevState>(BL.dstate), hs, sizeof(DevState), hipMemcpyHostToDevice, I->stream),
+            "hipMemcpy(batch rows)")) return bail(rc);
+    if (!ok(hipStreamSynchronize(I->stream), "batch init sync")) return bail(rc);
+  }
+  // page 0 must hold finite numbers: free slots attend nothing, but their K/V rows are written there
+  if (!ok(hipMemsetAsync(B->at<char>(BL.kv), 0, (size_t)c.n_layers * 2 * BL.kv_layer_halves * 2, I->stream),
+          "hipMemset(pool)")) return bail(rc);
+  if ((rc = push_batch_state(I)) != LL_OK) return bail(rc);
+  enqueue_batch_step(I, I->stream);                                         // warm-up on empty slots
+  if (!ok(hipStreamSynchronize(I->stream), "batch warm-up")) return bail(rc);
+  if (!ok(hipGetLastError(), "batch warm-up launch")) return bail(rc);
+  if (!eager(I)) {
+    hipError_t e = hipStreamBeginCapture(I->stream, hipStreamCaptureModeThreadLocal);
+    if (e != hipSuccess) return bail(fail(LL_E_HIP, "hipStreamBeginCapture: %s", hipGetErrorString(e)));
+    enqueue_batch_step(I, I->stream);
+    e = hipStreamEndCapture(I->stream, &B->graph);
+    if (e != hipSuccess) return bail(fail(LL_E_HIP, "hipStreamEndCapture: %s", hipGetErrorString(e)));
+    if (!ok(hipGraphInstantiate(&B->exec, B->graph, nullptr, nullptr, 0), "hipGraphInstantiate(batch)")) return bail(rc);
+  }
+  return LL_OK;
+}
+
+int ll_batch_close(void) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_batch_close: not initialised");
+  if (!g->batch) return fail(LL_E_STATE, "ll_batch_close: not open");
+  (void)hipStreamSynchronize(g->stream);
+  destroy_batch(g->batch);
+  g->batch = nullptr;
+  return LL_OK;
+}
+
+int32_t ll_batch_add(const int32_t* tokens, int32_t n, int32_t* first_token) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_batch_add: not initialised");
+  Instance* I = g;
+  Batch* B = I->batch;
+  if (!B) return fail(LL_E_STATE, "ll_batch_add: call ll_batch_open first");
+  if (!tokens || !first_token) return fail(LL_E_BAD_ARG, "ll_batch_add: null argument");
+  if (n < 1) return fail(LL_E_BAD_ARG, "ll_batch_add: n = %d < 1", n);
+  if (n + 1 > I->cfg.max_seq) return fail(LL_E_CAPACITY, "ll_batch_add: n + 1 = %d > max_seq = %d", n + 1, I->cfg.max_seq);
+  int slot = -1;
+  for (int b = 0; b < B->max_batch && slot < 0; ++b)
+    if (!B->h_state->active[b]) slot = b;
+  if (slot < 0) return fail(LL_E_CAPACITY, "ll_batch_add: all %d slots are taken", B->max_batch);
+  const int need = (n + 1 + B->page_tokens - 1) / B->page_tokens;       // the prompt and the first generated position
+  if ((int)B->free_pages.size() < need)
+    return fail(LL_E_CAPACITY, "ll_batch_add: %d pages needed, %zu free", need, B->free_pages.size());
+
+  // the prompt runs through the single-sequence prefill (whose context it replaces) ...
+  int rc = ll_reset();
+  if (rc != LL_OK) return rc;
+  const int32_t t1 = ll_prefill(tokens, n);
+  if (t1 < 0) return t1;
+  // ... and its cache rows move into the slot's pages
+  for (int i = 0; i < need; ++i) {
+    const int pg = B->free_pages.back();
+    B->free_pages.pop_back();
+    B->pages[slot].push_back(pg);
+    B->h_table[slot * B->L.pt_stride + i] = pg * B->page_tokens;
+  }
+  B->h_state->pos[slot] = n;
+  B->h_state->next_token[slot] = t1;
+  B->h_state->active[slot] = 1;
+  if ((rc = push_batch_state(I)) != LL_OK) return rc;
+  const ll_config& c = I->cfg;
+  hipLaunchKernelGGL(bt_scatter_kernel, dim3(n, c.n_layers * 2), dim3(LL_WG), 0, I->stream, I->kcache(0),
+                     I->L.kv_layer_halves, c.max_seq, B->kpool(0), B->L.kv_layer_halves, B->L.pool_rows,
+                     B->at<int>(B->L.page_table), B->L.pt_stride, B->page_tokens, slot, c.n_heads, c.head_dim);
+  HIPCHK(hipGetLastError());
+  HIPCHK(hipStreamSynchronize(I->stream));
+  *first_token = t1;
+  return slot;
+}
+
+int ll_batch_remove(int32_t slot) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_batch_remove: not initialised");
+  Batch* B = g->batch;
+  if (!B) return fail(LL_E_STATE, "ll_batch_remove: call ll_batch_open first");
+  if (slot < 0 || slot >= B->max_batch || !B->h_state->active[slot])
+    return fail(LL_E_BAD_ARG, "ll_batch_remove: slot %d holds no sequence", slot);
+  for (int pg : B->pages[slot]) B->free_pages.push_back(pg);
+  B->pages[slot].clear();
+  for (int i = 0; i < B->L.pt_stride; ++i) B->h_table[slot * B->L.pt_stride + i] = 0;
+  B->h_state->pos[slot] = 0;
+  B->h_state->next_token[slot] = 0;
+  B->h_state->active[slot] = 0;
+  int rc = push_batch_state(g);
+  if (rc != LL_OK) return rc;
+  HIPCHK(hipStreamSynchronize(g->stream));
+  return LL_OK;
+}
+
+int ll_batch_step(int32_t* out_tokens) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_batch_step: not initialised");
+  Instance* I = g;
+  Batch* B = I->batch;
+  if (!B) return fail(LL_E_STATE, "ll_batch_step: call ll_batch_open first");
+  if (!out_tokens) return fail(LL_E_BAD_ARG, "ll_batch_step: null output");
+  // this step writes position pos[b] of every active slot: check capacity and pages before anything runs
+  int fresh = 0, live = 0;
+  for (int b = 0; b < B->max_batch; ++b) {
+    if (!B->h_state->active[b]) continue;
+    ++live;
+    const int p = B->h_state->pos[b];
+    if (p + 1 > I->cfg.max_seq)
+      return fail(LL_E_CAPACITY, "ll_batch_step: slot %d holds %d positions, max_seq = %d", b, p, I->cfg.max_seq);
+    if (p / B->page_tokens >= (int)B->pages[b].size()) ++fresh;
+  }
+  if (!live) return fail(LL_E_STATE, "ll_batch_step: no sequence in the batch");
+  if (fresh > (int)B->free_pages.size())
+    return fail(LL_E_CAPACITY, "ll_batch_step: %d new pages needed, %zu free", fresh, B->free_pages.size());
+  if (fresh) {
+    for (int b = 0; b < B->max_batch; ++b) {
+      if (!B->h_state->active[b]) continue;
+      const int i = B->h_state->pos[b] / B->page_tokens;
+      if (i < (int)B->pages[b].size()) continue;
+      const int pg = B->free_pages.back();
+      B->free_pages.pop_back();
+      B->pages[b].push_back(pg);
+      B->h_table[b * B->L.pt_stride + i] = pg * B->page_tokens;
+    }
+    HIPCHK(hipMemcpyAsync(B->at<int>(B->L.page_table), B->h_table, (size_t)BT_MAX_BATCH * B->L.pt_stride * 4,
+                          hipMemcpyHostToDevice, I->stream));
+  }
+  if (eager(I)) {
+    enqueue_batch_step(I, I->stream);
+    HIPCHK(hipGetLastError());
+  } else {
+    HIPCHK(hipGraphLaunch(B->exec, I->stream));
+  }
+  HIPCHK(hipStreamSynchronize(I->stream));
+  for (int b = 0; b < BT_MAX_BATCH; ++b) {
+    const int t = b < B->max_batch ? B->h_out[b] : -1;
+    if (b < B->max_batch) out_tokens[b] = t;
+    if (b < B->max_batch && B->h_state->active[b]) {       // the host mirror follows the device state
+      B->h_state->pos[b] += 1;
+      B->h_state->next_token[b] = t;
+    }
+  }
+  return LL_OK;
+}
+
+int ll_batch_dbg_get_logits(int32_t slot, float* host_out) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_batch_dbg_get_logits: not initialised");
+  Batch* B = g->batch;
+  if (!B) return fail(LL_E_STATE, "ll_batch_dbg_get_logits: call ll_batch_open first");
+  if (slot < 0 || slot >= B->max_batch || !host_out) return fail(LL_E_BAD_ARG, "ll_batch_dbg_get_logits: bad argument");
+  HIPCHK(hipStreamSynchronize(g->stream));
+  HIPCHK(hipMemcpy(host_out, B->at<float>(B->L.logits) + (size_t)slot * g->cfg.vocab, (size_t)g->cfg.vocab * 4,
+                   hipMemcpyDeviceToHost));
+  return LL_OK;
+}
+
+int ll_batch_dbg_force_next_token(int32_t slot, int32_t tok) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_batch_dbg_force_next_token: not initialised");
+  Batch* B = g->batch;
+  if (!B) return fail(LL_E_STATE, "ll_batch_dbg_force_next_token: call ll_batch_open first");
+  if (slot < 0 || slot >= B->max_batch || !B->h_state->active[slot] || tok < 0 || tok >= g->cfg.vocab)
+    return fail(LL_E_BAD_ARG, "ll_batch_dbg_force_next_token: bad argument");
+  B->h_state->next_token[slot] = tok;
+  int rc = push_batch_state(g);
+  if (rc != LL_OK) return rc;
+  HIPCHK(hipStreamSynchronize(g->stream));
+  return LL_OK;
+}
+
+int ll_batch_dbg_time_steps(int32_t k, float* ms_out) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_batch_dbg_time_steps: not initialised");
+  Instance* I = g;
+  Batch* B = I->batch;
+  if (!B) return fail(LL_E_STATE, "ll_batch_dbg_time_steps: call ll_batch_open first");
+  if (k < 1 || !ms_out) return fail(LL_E_BAD_ARG, "ll_batch_dbg_time_steps: bad argument");
+  // k steps back to back: the pages those steps will write are taken up front
+  int fresh = 0;
+  for (int b = 0; b < B->max_batch; ++b) {
+    if (!B->h_state->active[b]) continue;
+    if (B->h_state->pos[b] + k > I->cfg.max_seq)
+      return fail(LL_E_CAPACITY, "ll_batch_dbg_time_steps: slot %d would pass max_seq", b);
+    const int want = (B->h_state->pos[b] + k - 1) / B->page_tokens + 1;
+    if (want > (int)B->pages[b].size()) fresh += want - (int)B->pages[b].size();
+  }
+  if (fresh > (int)B->free_pages.size())
+    return fail(LL_E_CAPACITY, "ll_batch_dbg_time_steps: %d new pages needed, %zu free", fresh, B->free_pages.size());
+  if (fresh) {
+    for (int b = 0; b < B->max_batch; ++b) {
+      if (!B->h_state->active[b]) continue;
+      const int want = (B->h_state->pos[b] + k - 1) / B->page_tokens + 1;
+      while ((int)B->pages[b].size() < want) {
+        const int pg = B->free_pages.back();
+        B->free_pages.pop_back();
+        B->h_table[b * B->L.pt_stride + (int)B->pages[b].size()] = pg * B->page_tokens;
+        B->pages[b].push_back(pg);
+      }
+    }
+    HIPCHK(hipMemcpyAsync(B->at<int>(B->L.page_table), B->h_table, (size_t)BT_MAX_BATCH * B->L.pt_stride * 4,
+                          hipMemcpyHostToDevice, I->stream));
+  }
+  hipEvent_t e0, e1;
+  HIPCHK(hipEventCreate(&e0));
+  HIPCHK(hipEventCreate(&e1));
+  HIPCHK(hipEventRecord(e0, I->stream));
+  for (int i = 0; i < k; ++i) {
+    if (eager(I)) enqueue_batch_step(I, I->stream);
+    else HIPCHK(hipGraphLaunch(B->exec, I->stream));
+  }
+  HIPCHK(hipEventRecord(e1, I->stream));
+  HIPCHK(hipStreamSynchronize(I->stream));
+  HIPCHK(hipEventElapsedTime(ms_out, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  for (int b = 0; b < B->max_batch; ++b)
+    if (B->h_state->active[b]) { B->h_state->pos[b] += k; B->h_state->next_token[b] = B->h_out[b]; }
+  return LL_OK;
+}
 
 int ll_decode_mode(void) {
   if (!g) return fail(LL_E_NOT_INIT, "ll_decode_mode: not initialised");

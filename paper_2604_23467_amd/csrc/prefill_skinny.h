@@ -37,7 +37,7 @@
 #pragma once
 #include "ll_device.h"
 
-enum SkinnyMode { SK_QKV = 0, SK_RES = 1, SK_GATEUP = 2 };
+enum SkinnyMode { SK_QKV = 0, SK_RES = 1, SK_GATEUP = 2, SK_LOGITS = 3 };
 
 struct SkinnyArgs {
   const half_t* X;        // 16 TB token rows x K fp16 activations, fragment-major; rows >= n hold anything
@@ -59,7 +59,22 @@ struct SkinnyArgs {
   long zeros_off;         // element offset from X of >= 16 bytes of zeros (same allocation as X)
                           // positions: row r of the prompt chunk sits at position st->pos + r
   int head_dim, max_seq;
+  // batched decode (rows = sequences of a batch instead of rows of one prompt):
+  const int* row_pos;     // QKV: position of row r (null: st->pos + r)
+  const int* page_table;  // QKV: [rows][pt_stride] first cache row of each page of row r's sequence (null: cache row = position)
+  int pt_stride, page_tokens;
+  float* logits;          // LOGITS: [rows][N] fp32, normalised like QKV / GATEUP outputs
 };
+
+// position of row tok, and the cache row that holds a position of row tok's sequence
+__device__ __forceinline__ int sk_row_pos(const SkinnyArgs& a, int p0, int tok) {
+  return a.row_pos ? a.row_pos[tok] : p0 + tok;
+}
+__device__ __forceinline__ int sk_cache_row(const SkinnyArgs& a, int tok, int pos) {
+  if (!a.page_table) return pos;
+  const int pg = pos / a.page_tokens;
+  return a.page_table[tok * a.pt_stride + pg] + (pos - pg * a.page_tokens);
+}
 
 #define SK_WAVES 8
 #define SK_THREADS (SK_WAVES * 64)
@@ -250,12 +265,14 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_kernel(SkinnyArgs a) 
           const int c0 = v * 16, head = c0 / a.head_dim, e = c0 - head * a.head_dim;   // 16 rows of one head
 #pragma unroll
           for (int j = 0; j < 8; ++j) { o0[j] = (half_t)lo[j]; o1[j] = (half_t)hi[j]; }
-          half_t* vr = a.vc + ((size_t)head * a.max_seq + p0 + tok) * a.head_dim + e;
+          const int pos = sk_row_pos(a, p0, tok);
+          half_t* vr = a.vc + ((size_t)head * a.max_seq + sk_cache_row(a, tok, pos)) * a.head_dim + e;
           *reinterpret_cast<h8*>(vr) = o0;
           *reinterpret_cast<h8*>(vr + 8) = o1;
         } else {
           const int bph = hh / 8, head = v / bph, j0 = (v - head * bph) * 8;
-          const float2* cs = a.rope + (size_t)(p0 + tok) * hh + j0;   // row tok of the chunk sits at position p0 + tok
+          const int pos = sk_row_pos(a, p0, tok);                     // row tok of a prompt chunk sits at position p0 + tok
+          const float2* cs = a.rope + (size_t)pos * hh + j0;
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             const float2 t2 = cs[j];
@@ -263,7 +280,7 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_kernel(SkinnyArgs a) 
             o1[j] = (half_t)(hi[j] * t2.x + lo[j] * t2.y);
           }
           half_t* dst = z == 0 ? a.Q + (size_t)tok * N + head * a.head_dim
-                               : a.kc + ((size_t)head * a.max_seq + p0 + tok) * a.head_dim;
+                               : a.kc + ((size_t)head * a.max_seq + sk_cache_row(a, tok, pos)) * a.head_dim;
           *reinterpret_cast<h8*>(dst + j0) = o0;
           *reinterpret_cast<h8*>(dst + j0 + hh) = o1;
         }
@@ -304,6 +321,7 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
   // weight row of this lane in row block u
   auto row_ptr = [&](int u) -> const half_t* {
     if (MODE == SK_GATEUP) return a.W[r >> 3] + (size_t)(u * 8 + (r & 7)) * K;
+    if (MODE == SK_LOGITS) return a.W[0] + (size_t)(u * 16 + r) * K;
     const int per = N / 16, z = u / per, v = u - z * per;
     int row;
     if (z == 2) {
@@ -395,18 +413,26 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
 #pragma unroll
         for (int j = 0; j < 8; ++j) o0[j] = (half_t)(lo[j] / (1.0f + expf(-lo[j])) * hi[j]);
         *reinterpret_cast<h8*>(a.Hout + act_offset(tok, u * 8, N, TB)) = o0;
+      } else if (MODE == SK_LOGITS) {
+        float* lp = a.logits + (size_t)tok * N + u * 16;
+        *reinterpret_cast<f4*>(lp) = f4{lo[0], lo[1], lo[2], lo[3]};
+        *reinterpret_cast<f4*>(lp + 4) = f4{lo[4], lo[5], lo[6], lo[7]};
+        *reinterpret_cast<f4*>(lp + 8) = f4{hi[0], hi[1], hi[2], hi[3]};
+        *reinterpret_cast<f4*>(lp + 12) = f4{hi[4], hi[5], hi[6], hi[7]};
       } else {
         const int per = N / 16, z = u / per, v = u - z * per;
         if (z == 2) {
           const int c0 = v * 16, head = c0 / a.head_dim, e = c0 - head * a.head_dim;
 #pragma unroll
           for (int j = 0; j < 8; ++j) { o0[j] = (half_t)lo[j]; o1[j] = (half_t)hi[j]; }
-          half_t* vr = a.vc + ((size_t)head * a.max_seq + p0 + tok) * a.head_dim + e;
+          const int pos = sk_row_pos(a, p0, tok);
+          half_t* vr = a.vc + ((size_t)head * a.max_seq + sk_cache_row(a, tok, pos)) * a.head_dim + e;
           *reinterpret_cast<h8*>(vr) = o0;
           *reinterpret_cast<h8*>(vr + 8) = o1;
         } else {
           const int bph = hh / 8, head = v / bph, j0 = (v - head * bph) * 8;
-          const float2* cs = a.rope + (size_t)(p0 + tok) * hh + j0;
+          const int pos = sk_row_pos(a, p0, tok);
+          const float2* cs = a.rope + (size_t)pos * hh + j0;
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             const float2 t2 = cs[j];
@@ -414,7 +440,7 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
             o1[j] = (half_t)(hi[j] * t2.x + lo[j] * t2.y);
           }
           half_t* dst = z == 0 ? a.Q + (size_t)tok * N + head * a.head_dim
-                               : a.kc + ((size_t)head * a.max_seq + p0 + tok) * a.head_dim;
+                               : a.kc + ((size_t)head * a.max_seq + sk_cache_row(a, tok, pos)) * a.head_dim;
           *reinterpret_cast<h8*>(dst + j0) = o0;
           *reinterpret_cast<h8*>(dst + j0 + hh) = o1;
         }

@@ -85,3 +85,20 @@ def test_binding_has_no_oracle_dependency():
                 src = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"^\s*(from|import)\s+oracle\b", src, flags=re.M), f
                 assert "liboracle" not in src, f
+
+
+def test_batch_calls_need_an_instance():
+    """No ll_init, no GPU: every batched-decoding call reports LL_E_NOT_INIT (the size query: 0)."""
+    import ctypes as C
+    from paper_2604_23467_amd import binding as b
+    lib = b.load()
+    assert lib.ll_batch_pool_bytes(16, 8) == 0
+    out = (C.c_int32 * 16)()
+    first = C.c_int32(0)
+    ms = C.c_float(0)
+    logits = (C.c_float * 4)()
+    for rc in (lib.ll_batch_open(4, 16, 8, C.c_void_p(256), 1 << 20), lib.ll_batch_add(out, 1, C.byref(first)),
+               lib.ll_batch_step(out), lib.ll_batch_remove(0), lib.ll_batch_close(),
+               lib.ll_batch_dbg_get_logits(0, logits), lib.ll_batch_dbg_force_next_token(0, 0),
+               lib.ll_batch_dbg_time_steps(1, C.byref(ms))):
+        assert rc == b.LL_E_NOT_INIT
