@@ -332,6 +332,32 @@ def main():
         log("[bench] prompt 10, 100 steps, one graph per KV length (buffer of 8, capture overlapped with replay): "
             "p50 %.1f us p99 %.1f us, %.2f ms of host time per captured graph"
             % (per_length["p50_us"], per_length["p99_us"], per_length["capture_ms_per_graph"]))
+        # batched lock-step decoding over the paged KV cache: 16 sequences, prompts of the sweep's lengths
+        bsess = binding.Session(cfg, w_t)
+        blens = [10, 25, 50, 100, 250, 500, 10, 25, 50, 100, 250, 500, 10, 25, 50, 100]
+        page_tokens, bsteps = 16, 100
+        n_pages = sum((n + 5 + bsteps + 20) // page_tokens + 2 for n in blens) + 1    # 5 + bsteps + 20 steps each
+        bsess.ll_batch_open(16, page_tokens, n_pages)
+        for i, n in enumerate(blens):
+            bsess.ll_batch_add(wl.make_tokens(n, cfg["vocab"], seed=7000 + i))
+        for _ in range(5):
+            bsess.ll_batch_step()
+        kv0 = sum(n + 5 for n in blens)
+        b_ms = bsess.ll_batch_dbg_time_steps(bsteps) / bsteps
+        hl = np.empty(20)
+        for i in range(20):
+            t0 = time.perf_counter()
+            bsess.ll_batch_step()
+            hl[i] = time.perf_counter() - t0
+        bsess.ll_batch_close()
+        bsess.close()
+        # weights once per step whatever the batch; K/V rows of all 16 sequences (mean over the timed steps)
+        b_bytes = step_bytes(cfg, 0) + cfg["n_layers"] * 2 * cfg["d_model"] * 2 * (kv0 + 16 * (bsteps + 1) // 2 + 16 + 15)
+        batched = dict(batch=16, prompt_lengths=blens, page_tokens=page_tokens, steps=bsteps, ms_per_step=b_ms,
+                       tokens_per_s=16e3 / b_ms, host_p50_us=pct(hl, 50) * 1e6,
+                       hbm_tb_per_s=b_bytes / (b_ms * 1e-3) / 1e12)
+        log("[bench] batch of 16 (prompts 10..500, pages of 16): %.3f ms per step = %.0f tokens/s, %.2f TB/s; "
+            "host p50 %.1f us" % (b_ms, batched["tokens_per_s"], batched["hbm_tb_per_s"], batched["host_p50_us"]))
         ps = binding.Session(cfg, w_t, flags=binding.LL_FLAG_PERSISTENT)
         ps.ll_prefill(prompt[:10])
         ps.ll_decode_n(10)
@@ -344,7 +370,7 @@ def main():
         eager = dict(prompt=10, steps=100, eager_p50_us=pct(el, 50) * 1e6, eager_p99_us=pct(el, 99) * 1e6,
                      graph_p50_us=pct(gl, 50) * 1e6, graph_p99_us=pct(gl, 99) * 1e6,
                      persistent_kernel_p50_us=pct(pl, 50) * 1e6, persistent_kernel_p99_us=pct(pl, 99) * 1e6,
-                     sampling=sampling, per_length_graphs=per_length)
+                     sampling=sampling, per_length_graphs=per_length, batched_decode=batched)
         log("[bench] prompt 10, 100 steps: graph p50 %.1f us p99 %.1f us | eager p50 %.1f us p99 %.1f us | "
             "one persistent kernel p50 %.1f us p99 %.1f us"
             % (eager["graph_p50_us"], eager["graph_p99_us"], eager["eager_p50_us"], eager["eager_p99_us"],

@@ -20,11 +20,11 @@ struct BatchState {
 };
 
 // Attention of slot b's new query (position pos[b], already written to the cache) for one head.
-// grid = (heads, BT_MAX_BATCH), 256 threads.  As in the single-sequence kernel a key row is read
+// grid = (heads, BT_MAX_BATCH), 1024 threads (256 keys in flight: a 500-key sequence takes two trips).  As in the single-sequence kernel a key row is read
 // by HD / 8 adjacent lanes with one 16-byte load each and every lane group keeps an online-softmax
 // state over the keys it is dealt; groups merge by shuffles, waves through LDS.  Output: fp16,
 // in the fragment-major operand layout of the O projection.
-#define BT_ATTN_THREADS 256
+#define BT_ATTN_THREADS 1024
 template <int HD>
 __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
     const half_t* __restrict__ Q, const half_t* __restrict__ kc, const half_t* __restrict__ vc,
@@ -140,9 +140,11 @@ __global__ __launch_bounds__(1024) void bt_select_kernel(const float* __restrict
   const float* row = logits + (size_t)b * vocab;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
-  for (int i = tid; i < vocab; i += 1024) {
-    const float v = row[i];
-    if (v > bv) { bv = v; bi = i; }          // i ascends: the first maximum stays
+  for (int i = tid * 4; i < vocab; i += 4096) {     // vocab % 16 == 0 (checked when the batch is opened)
+    const f4 v = *reinterpret_cast<const f4*>(row + i);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (v[e] > bv) { bv = v[e]; bi = i + e; }     // indices ascend: the first maximum stays
   }
   sv[tid] = bv;
   si[tid] = bi;
