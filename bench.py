@@ -71,16 +71,16 @@ def pct(v, p):
     return float(v[k])
 
 
-def batched_leg(cfg, w_t):
-    """Batched lock-step decoding over the paged KV cache: 16 sequences with prompts of the sweep's
+def batched_leg(cfg, w_t, batch=16):
+    """Batched lock-step decoding over the paged KV cache: `batch` sequences with prompts of the sweep's
     lengths, 100 timed steps back to back (device time), then 20 single steps (host wall time)."""
     import numpy as np
     from paper_2604_23467_amd import binding, workloads as wl
     bsess = binding.Session(cfg, w_t)
-    blens = [10, 25, 50, 100, 250, 500, 10, 25, 50, 100, 250, 500, 10, 25, 50, 100]
+    blens = [PROMPT_LENGTHS[i % len(PROMPT_LENGTHS)] for i in range(batch)]
     page_tokens, bsteps = 16, 100
     n_pages = sum((n + 5 + bsteps + 20) // page_tokens + 2 for n in blens) + 1    # 5 + bsteps + 20 steps each
-    bsess.ll_batch_open(16, page_tokens, n_pages)
+    bsess.ll_batch_open(batch, page_tokens, n_pages)
     for i, n in enumerate(blens):
         bsess.ll_batch_add(wl.make_tokens(n, cfg["vocab"], seed=7000 + i))
     for _ in range(5):
@@ -94,13 +94,13 @@ def batched_leg(cfg, w_t):
         hl[i] = time.perf_counter() - t0
     bsess.ll_batch_close()
     bsess.close()
-    # weights once per step whatever the batch; K/V rows of all 16 sequences (mean over the timed steps)
-    b_bytes = step_bytes(cfg, 0) + cfg["n_layers"] * 2 * cfg["d_model"] * 2 * (kv0 + 16 * (bsteps + 1) // 2 + 16 + 15)
-    batched = dict(batch=16, prompt_lengths=blens, page_tokens=page_tokens, steps=bsteps, ms_per_step=b_ms,
-                   tokens_per_s=16e3 / b_ms, host_p50_us=pct(hl, 50) * 1e6,
+    # weights once per step whatever the batch; K/V rows of all sequences (mean over the timed steps)
+    b_bytes = step_bytes(cfg, 0) + cfg["n_layers"] * 2 * cfg["d_model"] * 2 * (kv0 + batch * (bsteps + 1) // 2 + 2 * batch - 1)
+    batched = dict(batch=batch, prompt_lengths=blens, page_tokens=page_tokens, steps=bsteps, ms_per_step=b_ms,
+                   tokens_per_s=batch * 1e3 / b_ms, host_p50_us=pct(hl, 50) * 1e6,
                    hbm_tb_per_s=b_bytes / (b_ms * 1e-3) / 1e12)
-    log("[bench] batch of 16 (prompts 10..500, pages of 16): %.3f ms per step = %.0f tokens/s, %.2f TB/s; "
-        "host p50 %.1f us" % (b_ms, batched["tokens_per_s"], batched["hbm_tb_per_s"], batched["host_p50_us"]))
+    log("[bench] batch of %d (prompts 10..500, pages of 16): %.3f ms per step = %.0f tokens/s, %.2f TB/s; "
+        "host p50 %.1f us" % (batch, b_ms, batched["tokens_per_s"], batched["hbm_tb_per_s"], batched["host_p50_us"]))
     return batched
 
 
@@ -125,7 +125,7 @@ def main():
                     help="context only: time torch.matmul (the vendor GEMM library) on the four projection "
                          "shapes at M = 64..512 rows, weights rotated over 8 copies so they stream from HBM")
     ap.add_argument("--batched", action="store_true",
-                    help="only the batched-decoding leg (16 sequences over the paged KV cache): one JSON line")
+                    help="only the batched-decoding legs (16 and 32 sequences over the paged KV cache): one JSON line")
     ap.add_argument("--sweep", type=int, default=0, metavar="REPS",
                     help="latency sweep instead of the default run: for every prompt length in "
                          "{10,25,50,100,250,500}, REPS repetitions (token seed 1000*len + rep) of reset + "
@@ -175,8 +175,8 @@ def main():
     prompt = wl.make_tokens(n_prompt, cfg["vocab"], seed=0)
 
     if args.batched:
-        print(json.dumps(dict(metric="batched decode step, 16 sequences over a paged KV cache", unit="ms",
-                              n_gpus=1, dtype="f16", data="synthetic", **batched_leg(cfg, w_t))))
+        print(json.dumps(dict(metric="batched decode step over a paged KV cache", unit="ms", n_gpus=1, dtype="f16",
+                              data="synthetic", legs=[batched_leg(cfg, w_t, 16), batched_leg(cfg, w_t, 32)])))
         return 0
 
     if args.counters:
@@ -372,7 +372,7 @@ def main():
         log("[bench] prompt 10, 100 steps, one graph per KV length (buffer of 8, capture overlapped with replay): "
             "p50 %.1f us p99 %.1f us, %.2f ms of host time per captured graph"
             % (per_length["p50_us"], per_length["p99_us"], per_length["capture_ms_per_graph"]))
-        batched = batched_leg(cfg, w_t)
+        batched = [batched_leg(cfg, w_t, 16), batched_leg(cfg, w_t, 32)]
         ps = binding.Session(cfg, w_t, flags=binding.LL_FLAG_PERSISTENT)
         ps.ll_prefill(prompt[:10])
         ps.ll_decode_n(10)

@@ -173,9 +173,9 @@ const char *ll_last_error(void);
 /* ---- batched lock-step decoding over a paged KV cache ----
  *
  * The paper stays at batch 1 and takes its KV cache from a paged-attention library (Sec. II-C,
- * Sec. V-A); these calls open the regime it leaves out on top of an initialised instance: up to 16
- * sequences advance one token per call, each projection of the step is one 16-row matrix product
- * over the weights instead of 16 GEMVs, and every sequence keeps its K/V rows in pages of
+ * Sec. V-A); these calls open the regime it leaves out on top of an initialised instance: up to 32
+ * sequences advance one token per call, each projection of the step is one 16- or 32-row matrix
+ * product over the weights instead of that many GEMVs, and every sequence keeps its K/V rows in pages of
  * `page_tokens` positions taken from a common pool, so memory follows the sequences' real lengths.
  * Greedy selection only.  Available in the default (multi-kernel graph) and eager modes; the step
  * is one captured graph, like the single-sequence step.
@@ -189,7 +189,8 @@ const char *ll_last_error(void);
 /* Bytes of `pool` for pages of page_tokens positions, n_pages of them (page 0 is reserved, so
  * n_pages - 1 are usable); 0 without an instance or for arguments ll_batch_open would reject. */
 size_t ll_batch_pool_bytes(int32_t page_tokens, int32_t n_pages);
-/* Opens batched decoding for up to max_batch (1..16) concurrent sequences.  LL_E_BAD_CONFIG unless
+/* Opens batched decoding for up to max_batch (1..32) concurrent sequences (a step computes 16 rows
+ * up to 16 slots, 32 beyond).  LL_E_BAD_CONFIG unless
  * d_model % 16 == 0, d_model <= 4096, ffn_hidden % 8 == 0, vocab % 16 == 0, head_dim 64 or 128. */
 int ll_batch_open(int32_t max_batch, int32_t page_tokens, int32_t n_pages, void *pool, size_t pool_bytes);
 /* Adds a sequence: prefills tokens[0..n) (host pointer), moves its cache rows into freshly taken

@@ -1,7 +1,7 @@
 // Batched lock-step decoding over a paged KV cache: the kernels that have no counterpart in the
 // single-sequence path.  The paper embeds a paged-KV attention library for its cache (Sec. II-C,
 // Sec. V-A) and keeps batch 1 (Sec. V-A); this is the batch > 1 regime it leaves open, where the
-// projections of a step become 16-row matrix products (the short-prompt kernels of
+// projections of a step become 16- or 32-row matrix products (the short-prompt kernels of
 // prefill_skinny.h, one row per sequence) instead of GEMVs.
 //
 // A sequence owns pages of `page_tokens` consecutive cache rows; page_table[slot][i] is the first
@@ -11,7 +11,7 @@
 #pragma once
 #include "ll_device.h"
 
-#define BT_MAX_BATCH 16
+#define BT_MAX_BATCH 32
 
 struct BatchState {
   int32_t pos[BT_MAX_BATCH];         // cached positions of slot b = position of the token it feeds next
@@ -20,7 +20,8 @@ struct BatchState {
 };
 
 // Attention of slot b's new query (position pos[b], already written to the cache) for one head.
-// grid = (heads, BT_MAX_BATCH), 1024 threads (256 keys in flight: a 500-key sequence takes two trips).  As in the single-sequence kernel a key row is read
+// grid = (heads, rows of the step = 16 or 32), 1024 threads (256 keys in flight: a 500-key sequence
+// takes two trips); tb = rows / 16 selects the output's fragment-major layout.  As in the single-sequence kernel a key row is read
 // by HD / 8 adjacent lanes with one 16-byte load each and every lane group keeps an online-softmax
 // state over the keys it is dealt; groups merge by shuffles, waves through LDS.  Output: fp16,
 // in the fragment-major operand layout of the O projection.
@@ -29,7 +30,7 @@ template <int HD>
 __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
     const half_t* __restrict__ Q, const half_t* __restrict__ kc, const half_t* __restrict__ vc,
     const BatchState* __restrict__ bs, const int* __restrict__ page_table, int pt_stride, int page_tokens,
-    half_t* __restrict__ O, int d, int pool_rows) {
+    half_t* __restrict__ O, int d, int pool_rows, int tb) {
   constexpr int LPR = HD / 8;      // lanes per key row
   constexpr int GPW = 64 / LPR;    // lane groups per wave
   constexpr int NW = BT_ATTN_THREADS / 64;
@@ -39,7 +40,7 @@ __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int gi = lane / LPR, li = lane % LPR;
   if (!bs->active[b]) {
-    if (tid < HD / 8) *reinterpret_cast<h8*>(O + act_offset(b, h * HD + tid * 8, d, 1)) = h8{0, 0, 0, 0, 0, 0, 0, 0};
+    if (tid < HD / 8) *reinterpret_cast<h8*>(O + act_offset(b, h * HD + tid * 8, d, tb)) = h8{0, 0, 0, 0, 0, 0, 0, 0};
     return;
   }
   const int n_keys = bs->pos[b] + 1;
@@ -122,12 +123,12 @@ __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
     h8 o;
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = (half_t)(A[e] * rl);
-    *reinterpret_cast<h8*>(O + act_offset(b, h * HD + tid * 8, d, 1)) = o;
+    *reinterpret_cast<h8*>(O + act_offset(b, h * HD + tid * 8, d, tb)) = o;
   }
 }
 
 // Greedy token of every slot (lowest index among equal maxima) and the slots' state advance.
-// grid = BT_MAX_BATCH, 1024 threads; out = device-visible host memory, -1 for free slots.
+// grid = rows of the step, 1024 threads; out = device-visible host memory, -1 for free slots.
 __global__ __launch_bounds__(1024) void bt_select_kernel(const float* __restrict__ logits, int vocab,
                                                          BatchState* bs, int* out) {
   __shared__ float sv[1024];

@@ -773,6 +773,7 @@ struct Batch {
   BatchLayout L;
   char* pool = nullptr;
   int max_batch = 0, page_tokens = 0, n_pages = 0;
+  int rows = 16;                               // rows of a step: 16 up to 16 slots, else 32
   std::vector<int> free_pages;                 // page 0 is never handed out: free slots write there
   std::vector<std::vector<int>> pages;         // pages of every slot, in order
   BatchState* h_state = nullptr;               // pinned mirrors of the device state and page table
@@ -796,11 +797,11 @@ void destroy_batch(Batch* B) {
   delete B;
 }
 
-// One decode step of all slots: the 16 rows of the short-prompt kernels are the 16 slots.
+// One decode step of all slots: the 16 or 32 rows of the short-prompt kernels are the slots.
 void enqueue_batch_step(Instance* I, hipStream_t s) {
   Batch* B = I->batch;
   const ll_config& c = I->cfg;
-  const int d = c.d_model, F = c.ffn_hidden, Mb = BT_MAX_BATCH;
+  const int d = c.d_model, F = c.ffn_hidden, Mb = B->rows, tb = Mb / 16;
   float* X = I->at<float>(I->L.pf_x);
   half_t* Xn = I->at<half_t>(I->L.pf_xn);
   half_t* Qh = I->at<half_t>(I->L.pf_q);
@@ -809,10 +810,10 @@ void enqueue_batch_step(Instance* I, hipStream_t s) {
   float* ss_attn = I->at<float>(I->L.pf_ss);
   float* ss_ffn = ss_attn + 64 * SK_SS_STRIDE;
   BatchState* bs = B->at<BatchState>(B->L.state);
-  const DevState* st = B->at<DevState>(B->L.dstate);          // n_prompt = 16 rows, pos unused
+  const DevState* st = B->at<DevState>(B->L.dstate);          // n_prompt = rows of the step, pos unused
   const int* table = B->at<int>(B->L.page_table);
   hipLaunchKernelGGL(pf_embed_norm_kernel, dim3(Mb), dim3(LL_WG), 0, s, (const half_t*)I->w.tok_emb,
-                     bs->next_token, st, (const half_t*)I->layers[0].attn_norm, X, Xn, ss_attn, ss_ffn, d, 1);
+                     bs->next_token, st, (const half_t*)I->layers[0].attn_norm, X, Xn, ss_attn, ss_ffn, d, tb);
   for (int l = 0; l < c.n_layers; ++l) {
     const ll_layer_weights& W = I->layers[l];
     SkinnyArgs a{};
@@ -825,10 +826,10 @@ void enqueue_batch_step(Instance* I, hipStream_t s) {
     dim3 agrid(c.n_heads, Mb);
     if (c.head_dim == 128)
       hipLaunchKernelGGL(bt_attn_kernel<128>, agrid, dim3(BT_ATTN_THREADS), 0, s, Qh, B->kpool(l), B->vpool(l), bs,
-                         table, B->L.pt_stride, B->page_tokens, Oh, d, B->L.pool_rows);
+                         table, B->L.pt_stride, B->page_tokens, Oh, d, B->L.pool_rows, tb);
     else
       hipLaunchKernelGGL(bt_attn_kernel<64>, agrid, dim3(BT_ATTN_THREADS), 0, s, Qh, B->kpool(l), B->vpool(l), bs,
-                         table, B->L.pt_stride, B->page_tokens, Oh, d, B->L.pool_rows);
+                         table, B->L.pt_stride, B->page_tokens, Oh, d, B->L.pool_rows, tb);
     a.row_pos = nullptr; a.page_table = nullptr;
     a.X = Oh; a.W[0] = (const half_t*)W.wo; a.W[1] = a.W[2] = nullptr; a.N = d; a.K = d; a.Xres = X;
     a.gain_next = (const half_t*)W.ffn_norm; a.Xh_next = Xn; a.ss_out = ss_ffn; a.ss_zero = ss_attn;
@@ -842,15 +843,16 @@ void enqueue_batch_step(Instance* I, hipStream_t s) {
     launch_skinny<SK_RES>(I, s, a, Mb);
   }
   {
-    // LM head of all 16 rows: the wide persistent projection with a plain fp32 epilogue
+    // LM head of all rows: the wide persistent projection with a plain fp32 epilogue
     SkinnyArgs a{};
     a.st = st; a.eps = c.rms_eps; a.head_dim = c.head_dim; a.max_seq = c.max_seq;
     a.X = Xn; a.W[0] = (const half_t*)I->w.lm_head; a.N = c.vocab; a.K = d;
     a.ss_in = ss_attn; a.logits = B->at<float>(B->L.logits);
     a.zeros_off = I->at<half_t>(I->L.zeros) - a.X;
     const int units = skinny_units(SK_LOGITS, c.vocab);
-    hipLaunchKernelGGL((pf_skinny_persist_kernel<SK_LOGITS, 1>), dim3(units < g_num_cus ? units : g_num_cus),
-                       dim3(SK_THREADS), 0, s, a);
+    dim3 grid(units < g_num_cus ? units : g_num_cus);
+    if (tb == 1) hipLaunchKernelGGL((pf_skinny_persist_kernel<SK_LOGITS, 1>), grid, dim3(SK_THREADS), 0, s, a);
+    else hipLaunchKernelGGL((pf_skinny_persist_kernel<SK_LOGITS, 2>), grid, dim3(SK_THREADS), 0, s, a);
   }
   hipLaunchKernelGGL(bt_select_kernel, dim3(Mb), dim3(1024), 0, s, B->at<float>(B->L.logits), c.vocab, bs, B->d_out);
 }
@@ -1195,6 +1197,7 @@ int ll_batch_open(int32_t max_batch, int32_t page_tokens, int32_t n_pages, void*
   B->L = BL;
   B->pool = static_cast<char*>(pool);
   B->max_batch = max_batch; B->page_tokens = page_tokens; B->n_pages = n_pages;
+  B->rows = max_batch <= 16 ? 16 : 32;
   for (int p = n_pages - 1; p >= 1; --p) B->free_pages.push_back(p);
   B->pages.resize(BT_MAX_BATCH);
   int rc = LL_OK;
@@ -1217,7 +1220,7 @@ int ll_batch_open(int32_t max_batch, int32_t page_tokens, int32_t n_pages, void*
   {
     DevState* hs = reinterpret_cast<DevState*>(I->host_stage);
     memset(hs, 0, sizeof(DevState));
-    hs->n_prompt = BT_MAX_BATCH;
+    hs->n_prompt = B->rows;
     if (!ok(hipMemcpyAsync(B->at<DevState>(BL.dstate), hs, sizeof(DevState), hipMemcpyHostToDevice, I->stream),
             "hipMemcpy(batch rows)")) return bail(rc);
     if (!ok(hipStreamSynchronize(I->stream), "batch init sync")) return bail(rc);

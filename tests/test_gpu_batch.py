@@ -110,6 +110,24 @@ def test_batch_of_16_on_a_7b_shaped_layer(torch_cuda, oracle32):
     print("7B-layer batch worst rel-L2 %.2e" % worst)
 
 
+def test_32_slot_batch_on_the_tiny_model(torch_cuda, oracle32):
+    """More than 16 slots: the step runs 32 rows (two token blocks); 20 sequences, 12 free slots."""
+    cfg = wl.tiny_cfg(max_seq=64)
+    w = wl.make_weights_numpy(cfg, seed=4)
+    with _session(cfg, w) as s:
+        s.ll_batch_open(32, 4, 20 * 12 + 1)
+        seqs = [Seq(s, oracle32, cfg, w, wl.make_tokens(1 + (7 * i) % 23, cfg["vocab"], seed=300 + i), "s%d" % i)
+                for i in range(20)]
+        assert [q.slot for q in seqs] == list(range(20))
+        worst = 0.0
+        for _ in range(9):
+            worst = max(worst, max(x[1] for x in _step_all(s, seqs)))
+        s.ll_batch_close()
+    for q in seqs:
+        q.om.close()
+    print("32-slot batch worst rel-L2 %.2e" % worst)
+
+
 def test_batch_capacity_and_error_paths(torch_cuda):
     from paper_2604_23467_amd import binding as b
     cfg = wl.tiny_cfg(max_seq=40)
@@ -121,7 +139,7 @@ def test_batch_capacity_and_error_paths(torch_cuda):
             with pytest.raises(b.LLError) as e:
                 call()
             assert e.value.code == b.LL_E_STATE
-        for bad in ((0, 8, 4), (17, 8, 4), (2, 0, 4), (2, 8, 1)):
+        for bad in ((0, 8, 4), (33, 8, 4), (2, 0, 4), (2, 8, 1)):
             with pytest.raises(b.LLError):
                 s.ll_batch_open(*bad)
         s.ll_batch_open(2, 8, 4)                       # 3 usable pages of 8 positions
