@@ -187,3 +187,15 @@ __global__ __launch_bounds__(LL_WG) void bt_scatter_kernel(const half_t* __restr
         load_h8(s + ((size_t)h * src_rows + r) * head_dim + c * 8);
   }
 }
+
+// Page-table entries that changed since the last step, passed by value: one small launch in
+// front of the step instead of a host-to-device copy of the table.
+struct PageUpdates {
+  int n;
+  int index[BT_MAX_BATCH];      // slot * pt_stride + page number
+  int row[BT_MAX_BATCH];        // first cache row of the page
+};
+__global__ __launch_bounds__(64) void bt_page_update_kernel(int* __restrict__ page_table, PageUpdates u) {
+  const int i = threadIdx.x;
+  if (i < u.n) page_table[u.index[i]] = u.row[i];
+}

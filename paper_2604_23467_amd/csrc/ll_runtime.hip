@@ -587,14 +587,9 @@ void enqueue_prefill(Instance* I, hipStream_t s, int Mb, bool with_head = true) 
     hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(PF_NORM_THREADS), 0, s, X, (const half_t*)W.attn_norm,
                        Xn, d, c.rms_eps, I->state(), res_part, res, 0);
     const SliceMap qkv = launch_gemm(I, s, Xn, W.wq, W.wk, W.wv, 3, 3 * d, d, d, Mb);
-    if (c.head_dim % 8 == 0)
-      hipLaunchKernelGGL(pf_rope_kv4_kernel, dim3(Mb, (d / 8 + LL_WG - 1) / LL_WG), dim3(LL_WG), 0, s, P, qkv,
-                         I->at<float2>(I->L.rope), I->state(), Qh, I->kcache(l), I->vcache(l), d,
-                         c.head_dim, c.max_seq);
-    else
-      hipLaunchKernelGGL(pf_rope_kv_kernel, dim3(Mb), dim3(LL_WG), 0, s, P, qkv,
-                         I->at<float2>(I->L.rope), I->state(), Qh, I->kcache(l), I->vcache(l), d,
-                         c.head_dim, c.max_seq);
+    hipLaunchKernelGGL(pf_rope_kv_kernel, dim3(Mb, (d / 8 + LL_WG - 1) / LL_WG), dim3(LL_WG), 0, s, P, qkv,
+                       I->at<float2>(I->L.rope), I->state(), Qh, I->kcache(l), I->vcache(l), d,
+                       c.head_dim, c.max_seq);
     launch_attn(I, s, l, Mb);
     res = launch_gemm(I, s, Oh, W.wo, nullptr, nullptr, 1, d, d, d, Mb);
     res_part = P;
@@ -1332,6 +1327,7 @@ int ll_batch_step(int32_t* out_tokens) {
   if (fresh > (int)B->free_pages.size())
     return fail(LL_E_CAPACITY, "ll_batch_step: %d new pages needed, %zu free", fresh, B->free_pages.size());
   if (fresh) {
+    PageUpdates up{};                              // at most one new page per slot and step
     for (int b = 0; b < B->max_batch; ++b) {
       if (!B->h_state->active[b]) continue;
       const int i = B->h_state->pos[b] / B->page_tokens;
@@ -1340,9 +1336,11 @@ int ll_batch_step(int32_t* out_tokens) {
       B->free_pages.pop_back();
       B->pages[b].push_back(pg);
       B->h_table[b * B->L.pt_stride + i] = pg * B->page_tokens;
+      up.index[up.n] = b * B->L.pt_stride + i;
+      up.row[up.n++] = pg * B->page_tokens;
     }
-    HIPCHK(hipMemcpyAsync(B->at<int>(B->L.page_table), B->h_table, (size_t)BT_MAX_BATCH * B->L.pt_stride * 4,
-                          hipMemcpyHostToDevice, I->stream));
+    hipLaunchKernelGGL(bt_page_update_kernel, dim3(1), dim3(64), 0, I->stream, B->at<int>(B->L.page_table), up);
+    HIPCHK(hipGetLastError());
   }
   if (eager(I)) {
     enqueue_batch_step(I, I->stream);

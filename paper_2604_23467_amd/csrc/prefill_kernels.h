@@ -107,46 +107,10 @@ __global__ __launch_bounds__(LL_WG) void pf_fold_kernel(float* __restrict__ X, c
 }
 
 // RoPE on the q and k thirds of the QKV projection (fp32, slices of [Mb][3d], summed here) at
-// position p0 + r, then q -> fp16 Q[r], k/v -> the KV cache rows of position p0 + r.
-// grid = (Mb), rows >= n idle.
+// position p0 + r, then q -> fp16 Q[r], k/v -> the KV cache rows of position p0 + r.  Four rotation
+// pairs per thread with 16-byte loads, every load of a thread issued before the first use
+// (head_dim % 8 == 0).  grid = (Mb, ceil(n_heads * head_dim / 8 / LL_WG)), rows >= n idle.
 __global__ __launch_bounds__(LL_WG) void pf_rope_kv_kernel(const float* __restrict__ QKV, SliceMap map,
-                                                           const float2* __restrict__ rope,
-                                                           const DevState* __restrict__ st,
-                                                           half_t* __restrict__ Q,
-                                                           half_t* __restrict__ kc,
-                                                           half_t* __restrict__ vc, int d,
-                                                           int head_dim, int max_seq) {
-  const int r = blockIdx.x;
-  if (r >= st->n_prompt) return;
-  const int pos = st->pos + r;
-  const int hh = head_dim >> 1;
-  const float* row = QKV + (size_t)r * 3 * d;
-  auto val = [&](int i) {
-    float v = row[i];
-    const int np = slice_count(map, i);
-    for (int s = 1; s < np; ++s) v += row[s * map.slice_floats + i];
-    return v;
-  };
-  for (int p = threadIdx.x; p < d / 2; p += LL_WG) {
-    const int head = p / hh, j = p - head * hh;
-    const int ia = head * head_dim + j, ib = ia + hh;
-    const float2 cs = rope[(size_t)pos * hh + j];
-    const float qa = val(ia), qb = val(ib);
-    Q[(size_t)r * d + ia] = (half_t)(qa * cs.x - qb * cs.y);
-    Q[(size_t)r * d + ib] = (half_t)(qb * cs.x + qa * cs.y);
-    const float ka = val(d + ia), kb = val(d + ib);
-    half_t* kr = kc + ((size_t)head * max_seq + pos) * head_dim;
-    kr[j] = (half_t)(ka * cs.x - kb * cs.y);
-    kr[j + hh] = (half_t)(kb * cs.x + ka * cs.y);
-    half_t* vr = vc + ((size_t)head * max_seq + pos) * head_dim;
-    vr[j] = (half_t)val(2 * d + ia);
-    vr[j + hh] = (half_t)val(2 * d + ib);
-  }
-}
-
-// The same for head_dim % 8 == 0, four rotation pairs per thread with 16-byte loads, every load
-// of a thread issued before the first use.  grid = (Mb, ceil(n_heads * head_dim / 8 / LL_WG)).
-__global__ __launch_bounds__(LL_WG) void pf_rope_kv4_kernel(const float* __restrict__ QKV, SliceMap map,
                                                             const float2* __restrict__ rope,
                                                             const DevState* __restrict__ st,
                                                             half_t* __restrict__ Q,
