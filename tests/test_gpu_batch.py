@@ -169,3 +169,9 @@ def test_batch_capacity_and_error_paths(torch_cuda):
             s.ll_batch_add(list(wl.make_tokens(40, cfg["vocab"], seed=4)))   # 41 positions > max_seq
         assert e.value.code == b.LL_E_CAPACITY
         s.ll_batch_close()
+    for flags in (b.LL_FLAG_PERSISTENT, b.LL_FLAG_PER_LENGTH_GRAPHS):      # step graphs of their own: not combined
+        with _session(cfg, w, flags) as s:
+            with pytest.raises(b.LLError) as e:
+                s.ll_batch_open(2, 8, 4)
+            assert e.value.code == b.LL_E_STATE
+
