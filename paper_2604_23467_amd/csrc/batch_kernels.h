@@ -36,6 +36,7 @@ __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
   constexpr int NW = BT_ATTN_THREADS / 64;
   constexpr int UK = 4;            // keys in flight per group
   __shared__ float s_m[NW], s_l[NW], s_acc[NW][HD];
+  extern __shared__ int s_pt[];    // this slot's page-table row: a key's address then costs no global round trip
   const int h = blockIdx.x, b = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int gi = lane / LPR, li = lane % LPR;
@@ -44,6 +45,8 @@ __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
     return;
   }
   const int n_keys = bs->pos[b] + 1;
+  for (int i = tid; i * page_tokens < n_keys; i += BT_ATTN_THREADS) s_pt[i] = page_table[b * pt_stride + i];
+  __syncthreads();
   const float scale = 1.0f / sqrtf((float)HD);
   float qv[8];
   {
@@ -53,7 +56,6 @@ __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
   }
   const half_t* kh = kc + (size_t)h * pool_rows * HD + li * 8;
   const half_t* vh = vc + (size_t)h * pool_rows * HD + li * 8;
-  const int* pt = page_table + b * pt_stride;
 
   float m = -INFINITY, l = 0.f, acc[8];
 #pragma unroll
@@ -65,7 +67,7 @@ __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
     for (int j = 0; j < UK; ++j) {
       const int u = min(base + j * STRIDE + gi, n_keys - 1);
       const int pg = u / page_tokens;
-      const size_t row = (size_t)(pt[pg] + (u - pg * page_tokens));
+      const size_t row = (size_t)(s_pt[pg] + (u - pg * page_tokens));
       kk[j] = load_h8(kh + row * HD);
       vv[j] = load_h8(vh + row * HD);
     }

@@ -820,10 +820,10 @@ void enqueue_batch_step(Instance* I, hipStream_t s) {
     launch_skinny<SK_QKV>(I, s, a, Mb);
     dim3 agrid(c.n_heads, Mb);
     if (c.head_dim == 128)
-      hipLaunchKernelGGL(bt_attn_kernel<128>, agrid, dim3(BT_ATTN_THREADS), 0, s, Qh, B->kpool(l), B->vpool(l), bs,
+      hipLaunchKernelGGL(bt_attn_kernel<128>, agrid, dim3(BT_ATTN_THREADS), (size_t)B->L.pt_stride * 4, s, Qh, B->kpool(l), B->vpool(l), bs,
                          table, B->L.pt_stride, B->page_tokens, Oh, d, B->L.pool_rows, tb);
     else
-      hipLaunchKernelGGL(bt_attn_kernel<64>, agrid, dim3(BT_ATTN_THREADS), 0, s, Qh, B->kpool(l), B->vpool(l), bs,
+      hipLaunchKernelGGL(bt_attn_kernel<64>, agrid, dim3(BT_ATTN_THREADS), (size_t)B->L.pt_stride * 4, s, Qh, B->kpool(l), B->vpool(l), bs,
                          table, B->L.pt_stride, B->page_tokens, Oh, d, B->L.pool_rows, tb);
     a.row_pos = nullptr; a.page_table = nullptr;
     a.X = Oh; a.W[0] = (const half_t*)W.wo; a.W[1] = a.W[2] = nullptr; a.N = d; a.K = d; a.Xres = X;
@@ -1183,6 +1183,9 @@ int ll_batch_open(int32_t max_batch, int32_t page_tokens, int32_t n_pages, void*
   if (I->use_mega || I->per_length)
     return fail(LL_E_STATE, "ll_batch_open: available with the multi-kernel graph and eager modes only");
   const BatchLayout BL = make_batch_layout(c, page_tokens, n_pages);
+  if (BL.pt_stride > 8192)
+    return fail(LL_E_BAD_ARG, "ll_batch_open: max_seq / page_tokens = %d pages per sequence, at most 8192 "
+                              "(the attention kernel keeps a sequence's page list in LDS)", BL.pt_stride);
   if (pool_bytes < BL.total)
     return fail(LL_E_WORKSPACE, "ll_batch_open: pool has %zu bytes, %zu needed", pool_bytes, BL.total);
   if (reinterpret_cast<uintptr_t>(pool) % kAlign)
