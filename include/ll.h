@@ -177,8 +177,9 @@ const char *ll_last_error(void);
  * sequences advance one token per call, each projection of the step is one 16- or 32-row matrix
  * product over the weights instead of that many GEMVs, and every sequence keeps its K/V rows in pages of
  * `page_tokens` positions taken from a common pool, so memory follows the sequences' real lengths.
- * Greedy selection only.  Available in the default (multi-kernel graph) and eager modes; the step
- * is one captured graph, like the single-sequence step.
+ * Tokens are selected as ll_set_sampling says (greedy by default); every slot draws with its own
+ * index, so a sequence sees the same stream in a batch as alone.  Available in the default
+ * (multi-kernel graph) and eager modes; the step is one captured graph, like the single-sequence step.
  *
  * Ownership: `pool` is device memory of ll_batch_pool_bytes() bytes, 256-byte aligned, owned by the
  * caller and kept alive until ll_batch_close (or ll_shutdown, which closes the batch).  The calls

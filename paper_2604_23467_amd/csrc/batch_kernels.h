@@ -10,6 +10,7 @@
 // Free slots point at page 0, which no sequence ever owns: whatever they compute lands there.
 #pragma once
 #include "ll_device.h"
+#include "sample_kernels.h"
 
 #define BT_MAX_BATCH 32
 
@@ -17,6 +18,7 @@ struct BatchState {
   int32_t pos[BT_MAX_BATCH];         // cached positions of slot b = position of the token it feeds next
   int32_t next_token[BT_MAX_BATCH];  // token slot b feeds next
   int32_t active[BT_MAX_BATCH];      // 0: free slot
+  int32_t steps[BT_MAX_BATCH];       // tokens slot b's sequence has produced (the draw index of stochastic selection)
 };
 
 // Attention of slot b's new query (position pos[b], already written to the cache) for one head.
@@ -129,42 +131,55 @@ __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
   }
 }
 
-// Greedy token of every slot (lowest index among equal maxima) and the slots' state advance.
-// grid = rows of the step, 1024 threads; out = device-visible host memory, -1 for free slots.
-__global__ __launch_bounds__(1024) void bt_select_kernel(const float* __restrict__ logits, int vocab,
-                                                         BatchState* bs, int* out) {
-  __shared__ float sv[1024];
-  __shared__ int si[1024];
+// Token of every slot and the slots' state advance: greedy (lowest index among equal maxima), or
+// the stochastic selection of sample_kernels.h with the slot's own draw index, so a sequence draws
+// the same stream in a batch as alone.  grid = rows of the step, SMP_THREADS threads, SMP_Z_WORDS
+// words of dynamic LDS; out = device-visible host memory, -1 for free slots.
+__global__ __launch_bounds__(SMP_THREADS) void bt_select_kernel(const float* __restrict__ logits, int vocab,
+                                                                const SampleCfg* __restrict__ cfg,
+                                                                BatchState* bs, int* out) {
+  extern __shared__ float bt_z[];
+  __shared__ float sv[SMP_THREADS];
+  __shared__ int si[SMP_THREADS];
+  __shared__ uint32_t sk[SMP_THREADS];
+  __shared__ float red[2 * 3 * (SMP_THREADS / 64)];
+  __shared__ int found;
   const int b = blockIdx.x, tid = threadIdx.x;
   if (!bs->active[b]) {
     if (tid == 0) out[b] = -1;
     return;
   }
   const float* row = logits + (size_t)b * vocab;
-  float bv = -INFINITY;
-  int bi = 0x7fffffff;
-  for (int i = tid * 4; i < vocab; i += 4096) {     // vocab % 16 == 0 (checked when the batch is opened)
-    const f4 v = *reinterpret_cast<const f4*>(row + i);
+  int tok;
+  if (cfg->inv_temp == 0.f || vocab > SMP_MAX_VOCAB) {
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int i = tid * 4; i < vocab; i += SMP_THREADS * 4) {     // vocab % 16 == 0 (checked when the batch is opened)
+      const f4 v = *reinterpret_cast<const f4*>(row + i);
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (v[e] > bv) { bv = v[e]; bi = i + e; }     // indices ascend: the first maximum stays
-  }
-  sv[tid] = bv;
-  si[tid] = bi;
-  __syncthreads();
-  for (int off = 512; off > 0; off >>= 1) {
-    if (tid < off) {
-      const float v = sv[tid + off];
-      const int ix = si[tid + off];
-      if (v > sv[tid] || (v == sv[tid] && ix < si[tid])) { sv[tid] = v; si[tid] = ix; }
+      for (int e = 0; e < 4; ++e)
+        if (v[e] > bv) { bv = v[e]; bi = i + e; }                // indices ascend: the first maximum stays
     }
+    sv[tid] = bv;
+    si[tid] = bi;
     __syncthreads();
+    for (int off = SMP_THREADS / 2; off > 0; off >>= 1) {
+      if (tid < off) {
+        const float v = sv[tid + off];
+        const int ix = si[tid + off];
+        if (v > sv[tid] || (v == sv[tid] && ix < si[tid])) { sv[tid] = v; si[tid] = ix; }
+      }
+      __syncthreads();
+    }
+    tok = si[0];
+    if (tok == 0x7fffffff) tok = 0;          // every logit NaN: still a valid id
+  } else {
+    tok = smp_draw_token(row, vocab, cfg, (uint32_t)bs->steps[b], bt_z, si, sk, red, &found);
   }
   if (tid == 0) {
-    int tok = si[0];
-    if (tok == 0x7fffffff) tok = 0;          // every logit NaN: still a valid id
     bs->next_token[b] = tok;
     bs->pos[b] = bs->pos[b] + 1;
+    bs->steps[b] = bs->steps[b] + 1;
     out[b] = tok;
   }
 }

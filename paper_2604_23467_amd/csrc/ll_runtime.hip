@@ -849,7 +849,8 @@ void enqueue_batch_step(Instance* I, hipStream_t s) {
     if (tb == 1) hipLaunchKernelGGL((pf_skinny_persist_kernel<SK_LOGITS, 1>), grid, dim3(SK_THREADS), 0, s, a);
     else hipLaunchKernelGGL((pf_skinny_persist_kernel<SK_LOGITS, 2>), grid, dim3(SK_THREADS), 0, s, a);
   }
-  hipLaunchKernelGGL(bt_select_kernel, dim3(Mb), dim3(1024), 0, s, B->at<float>(B->L.logits), c.vocab, bs, B->d_out);
+  hipLaunchKernelGGL(bt_select_kernel, dim3(Mb), dim3(SMP_THREADS), SMP_Z_WORDS * 4, s, B->at<float>(B->L.logits),
+                     c.vocab, I->at<SampleCfg>(I->L.sample_cfg), bs, B->d_out);
 }
 
 int push_batch_state(Instance* I) {
@@ -951,6 +952,9 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&sample_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, SMP_Z_WORDS * 4),
                    "hipFuncSetAttribute(sample)")) return bail(rc);
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&bt_select_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, SMP_Z_WORDS * 4),
+                   "hipFuncSetAttribute(batch select)")) return bail(rc);
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128, 3, 2>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128, 3)),
                    "hipFuncSetAttribute(gemm 128)")) return bail(rc);
@@ -1281,6 +1285,7 @@ int32_t ll_batch_add(const int32_t* tokens, int32_t n, int32_t* first_token) {
   B->h_state->pos[slot] = n;
   B->h_state->next_token[slot] = t1;
   B->h_state->active[slot] = 1;
+  B->h_state->steps[slot] = 1;                  // the prefill drew with index 0
   if ((rc = push_batch_state(I)) != LL_OK) return rc;
   const ll_config& c = I->cfg;
   hipLaunchKernelGGL(bt_scatter_kernel, dim3(n, c.n_layers * 2), dim3(LL_WG), 0, I->stream, I->kcache(0),
@@ -1304,6 +1309,7 @@ int ll_batch_remove(int32_t slot) {
   B->h_state->pos[slot] = 0;
   B->h_state->next_token[slot] = 0;
   B->h_state->active[slot] = 0;
+  B->h_state->steps[slot] = 0;
   int rc = push_batch_state(g);
   if (rc != LL_OK) return rc;
   HIPCHK(hipStreamSynchronize(g->stream));
@@ -1357,6 +1363,7 @@ int ll_batch_step(int32_t* out_tokens) {
     if (b < B->max_batch) out_tokens[b] = t;
     if (b < B->max_batch && B->h_state->active[b]) {       // the host mirror follows the device state
       B->h_state->pos[b] += 1;
+      B->h_state->steps[b] += 1;
       B->h_state->next_token[b] = t;
     }
   }
@@ -1432,7 +1439,7 @@ int ll_batch_dbg_time_steps(int32_t k, float* ms_out) {
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
   for (int b = 0; b < B->max_batch; ++b)
-    if (B->h_state->active[b]) { B->h_state->pos[b] += k; B->h_state->next_token[b] = B->h_out[b]; }
+    if (B->h_state->active[b]) { B->h_state->pos[b] += k; B->h_state->steps[b] += k; B->h_state->next_token[b] = B->h_out[b]; }
   return LL_OK;
 }
 

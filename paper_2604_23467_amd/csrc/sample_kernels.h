@@ -271,6 +271,82 @@ __device__ __forceinline__ int smp_nucleus_and_draw(uint32_t (&key)[PER], float 
   return *found < 0 ? 0 : *found;
 }
 
+// One draw from logits[0 .. vocab) by a workgroup of SMP_THREADS threads (all of them call this;
+// vocab <= SMP_MAX_VOCAB, cfg->inv_temp != 0).  smp_z: SMP_Z_WORDS words of LDS; si, sk: SMP_THREADS
+// words each; red: 6 words per wave; found: one word.  Returns the token in every thread.
+__device__ __forceinline__ int smp_draw_token(const float* __restrict__ logits, int vocab,
+                                              const SampleCfg* __restrict__ cfg, uint32_t draw_index,
+                                              float* smp_z, int* si, uint32_t* sk, float* red, int* found) {
+  const int tid = threadIdx.x;
+  const float inv_temp = cfg->inv_temp;
+  int phase = 0;
+  int tok;
+  // Thread t holds tokens 32 t .. 32 t + 31.  The logits are read once, coalesced, into LDS rows of
+  // 32 padded to 33 words, from which a thread takes its row without bank conflicts (read straight
+  // from global memory, every load instruction of a wave would touch 64 cache lines).
+  for (int i = tid; i < vocab; i += SMP_THREADS) smp_z[i + (i >> 5)] = logits[i];
+  __syncthreads();
+  const int base = tid * SMP_PER;
+  uint32_t key[SMP_PER];
+  float zmax = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < SMP_PER; ++j) {
+    const int i = base + j;
+    const float z = i < vocab ? __fmul_rn(smp_z[base + tid + j], inv_temp) + 0.f : 0.f;   // + 0: -0 and +0 are one value
+    key[j] = i < vocab ? order_key(z) : 0u;
+    if (i < vocab) zmax = fmaxf(zmax, z);
+  }
+  zmax = smp_block_max(zmax, red, phase);
+
+  uint32_t ctr[4] = {draw_index, 0u, 0u, 0u};
+  philox4x32_10(ctr, cfg->seed_lo, cfg->seed_hi);
+  const float u = (float)(ctr[0] >> 8) * (1.0f / 16777216.0f);
+  const int top_k = (cfg->top_k >= 1 && cfg->top_k < vocab) ? cfg->top_k : 0;
+
+  // (1) With a top-k cut of at most one candidate per thread, almost all of the vocabulary can be
+  // discarded cheaply first: the k-th largest of the threads' own maxima is a lower bound of the
+  // k-th largest key (at least k keys reach it), found with one slot per thread.  What reaches the
+  // bound is packed, in index order, one per thread, and every later pass costs one slot, not 32.
+  bool done = false;
+  if (top_k > 0 && top_k <= SMP_THREADS) {
+    uint32_t tmax[1] = {0u};
+#pragma unroll
+    for (int j = 0; j < SMP_PER; ++j) tmax[0] = key[j] > tmax[0] ? key[j] : tmax[0];
+    const uint32_t bound = smp_kth_largest<1>(tmax, top_k, red, phase);
+    int reach = 0;
+#pragma unroll
+    for (int j = 0; j < SMP_PER; ++j) reach += key[j] >= bound;
+    float all;
+    int at = (int)(smp_block_scan_excl((float)reach, red, phase, &all) + 0.5f);
+    const int nreach = (int)(all + 0.5f);
+    if (bound != 0u && nreach <= SMP_THREADS) {            // uniform: `all` is the same in every thread
+#pragma unroll
+      for (int j = 0; j < SMP_PER; ++j) {
+        if (key[j] >= bound) {
+          sk[at] = key[j];
+          si[at] = base + j;
+          ++at;
+        }
+      }
+      __syncthreads();
+      uint32_t k1[1] = {tid < nreach ? sk[tid] : 0u};
+      float e1[1];
+      const int id = tid < nreach ? si[tid] : 0;
+      __syncthreads();
+      smp_apply_topk<1>(k1, e1, top_k, zmax, red, phase);
+      tok = smp_nucleus_and_draw<1>(k1, e1, id, cfg->top_p, u, red, phase, found);
+      done = true;
+    }
+  }
+  // (2) otherwise: the cut (if any), the nucleus and the draw over all 32 slots per thread
+  if (!done) {
+    float e[SMP_PER];
+    smp_apply_topk<SMP_PER>(key, e, top_k, zmax, red, phase);
+    tok = smp_nucleus_and_draw<SMP_PER>(key, e, base, cfg->top_p, u, red, phase, found);
+  }
+  return tok;
+}
+
 //   prefill = 1: pos += n_prompt (rows of the last prompt chunk), steps := 1, ring[0] := token (draw index 0)
 //   prefill = 0: pos += 1, ring[steps] := token, steps += 1   (draw index = steps before the step)
 __global__ __launch_bounds__(SMP_THREADS) void sample_kernel(const float* __restrict__ pval,
@@ -284,7 +360,6 @@ __global__ __launch_bounds__(SMP_THREADS) void sample_kernel(const float* __rest
   __shared__ int si[SMP_THREADS];
   __shared__ uint32_t sk[SMP_THREADS];
   __shared__ float red[2 * 3 * (SMP_THREADS / 64)];
-  int phase = 0;
   __shared__ int found;
   const int tid = threadIdx.x;
   const float inv_temp = cfg->inv_temp;
@@ -313,69 +388,7 @@ __global__ __launch_bounds__(SMP_THREADS) void sample_kernel(const float* __rest
     tok = si[0];
     if (tok == 0x7fffffff) tok = 0;   // every logit NaN: still a valid id
   } else {
-    // ---- stochastic: thread t holds tokens 32 t .. 32 t + 31.  The logits are read once, coalesced,
-    // into LDS rows of 32 padded to 33 words, from which a thread takes its row without bank conflicts
-    // (read straight from global memory, every load instruction of a wave would touch 64 cache lines).
-    for (int i = tid; i < vocab; i += SMP_THREADS) smp_z[i + (i >> 5)] = logits[i];
-    __syncthreads();
-    const int base = tid * SMP_PER;
-    uint32_t key[SMP_PER];
-    float zmax = -INFINITY;
-#pragma unroll
-    for (int j = 0; j < SMP_PER; ++j) {
-      const int i = base + j;
-      const float z = i < vocab ? __fmul_rn(smp_z[base + tid + j], inv_temp) + 0.f : 0.f;   // + 0: -0 and +0 are one value
-      key[j] = i < vocab ? order_key(z) : 0u;
-      if (i < vocab) zmax = fmaxf(zmax, z);
-    }
-    zmax = smp_block_max(zmax, red, phase);
-
-    uint32_t ctr[4] = {(uint32_t)(prefill ? 0 : st->steps), 0u, 0u, 0u};
-    philox4x32_10(ctr, cfg->seed_lo, cfg->seed_hi);
-    const float u = (float)(ctr[0] >> 8) * (1.0f / 16777216.0f);
-    const int top_k = (cfg->top_k >= 1 && cfg->top_k < vocab) ? cfg->top_k : 0;
-
-    // (1) With a top-k cut of at most one candidate per thread, almost all of the vocabulary can be
-    // discarded cheaply first: the k-th largest of the threads' own maxima is a lower bound of the
-    // k-th largest key (at least k keys reach it), found with one slot per thread.  What reaches the
-    // bound is packed, in index order, one per thread, and every later pass costs one slot, not 32.
-    bool done = false;
-    if (top_k > 0 && top_k <= SMP_THREADS) {
-      uint32_t tmax[1] = {0u};
-#pragma unroll
-      for (int j = 0; j < SMP_PER; ++j) tmax[0] = key[j] > tmax[0] ? key[j] : tmax[0];
-      const uint32_t bound = smp_kth_largest<1>(tmax, top_k, red, phase);
-      int reach = 0;
-#pragma unroll
-      for (int j = 0; j < SMP_PER; ++j) reach += key[j] >= bound;
-      float all;
-      int at = (int)(smp_block_scan_excl((float)reach, red, phase, &all) + 0.5f);
-      const int nreach = (int)(all + 0.5f);
-      if (bound != 0u && nreach <= SMP_THREADS) {            // uniform: `all` is the same in every thread
-#pragma unroll
-        for (int j = 0; j < SMP_PER; ++j) {
-          if (key[j] >= bound) {
-            sk[at] = key[j];
-            si[at] = base + j;
-            ++at;
-          }
-        }
-        __syncthreads();
-        uint32_t k1[1] = {tid < nreach ? sk[tid] : 0u};
-        float e1[1];
-        const int id = tid < nreach ? si[tid] : 0;
-        __syncthreads();
-        smp_apply_topk<1>(k1, e1, top_k, zmax, red, phase);
-        tok = smp_nucleus_and_draw<1>(k1, e1, id, cfg->top_p, u, red, phase, &found);
-        done = true;
-      }
-    }
-    // (2) otherwise: the cut (if any), the nucleus and the draw over all 32 slots per thread
-    if (!done) {
-      float e[SMP_PER];
-      smp_apply_topk<SMP_PER>(key, e, top_k, zmax, red, phase);
-      tok = smp_nucleus_and_draw<SMP_PER>(key, e, base, cfg->top_p, u, red, phase, &found);
-    }
+    tok = smp_draw_token(logits, vocab, cfg, (uint32_t)(prefill ? 0 : st->steps), smp_z, si, sk, red, &found);
   }
 
   if (tid == 0) {

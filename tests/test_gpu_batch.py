@@ -128,6 +128,58 @@ def test_32_slot_batch_on_the_tiny_model(torch_cuda, oracle32):
     print("32-slot batch worst rel-L2 %.2e" % worst)
 
 
+def test_stochastic_selection_per_slot(torch_cuda):
+    """ll_set_sampling applies to the batch as well: every slot draws with its own index (tokens its
+    sequence has produced), so a sequence that joins later starts its stream at index 1 while the
+    others are further along.  Checked like the single-sequence sampler: the oracle's draw on the
+    GPU's own logits, with the rounding-aware acceptance rule."""
+    from oracle import sampling as sp
+    from test_gpu_sampling import _accept
+    cfg = wl.tiny_cfg(max_seq=64)
+    w = wl.make_weights_numpy(cfg, seed=3)
+    w["lm_head"] = w["lm_head"] * 40.0
+    T, k, p, seed = 0.9, 30, 0.9, 42
+    with _session(cfg, w) as s:
+        s.ll_set_sampling(T, k, p, seed)
+        s.ll_batch_open(3, 8, 30)
+        drawn = {}
+        exact = total = 0
+
+        def add(prompt):
+            slot, tok = s.ll_batch_add(prompt)
+            ok, same = _accept(tok, s.ll_dbg_get_logits(), T, k, p, sp.uniform(seed, 0))   # the prefill's draw: index 0
+            assert ok, ("first token", slot, tok)
+            drawn[slot] = 1
+            return slot
+
+        def step():
+            nonlocal exact, total
+            toks = s.ll_batch_step()
+            for slot in list(drawn):
+                ok, same = _accept(toks[slot], s.ll_batch_dbg_get_logits(slot), T, k, p, sp.uniform(seed, drawn[slot]))
+                assert ok, ("slot %d draw %d: token %d is not a valid draw" % (slot, drawn[slot], toks[slot]))
+                exact += same
+                total += 1
+                drawn[slot] += 1
+            return toks
+
+        a = add(wl.make_tokens(9, cfg["vocab"], seed=9))
+        b = add(wl.make_tokens(4, cfg["vocab"], seed=10))
+        first = [step() for _ in range(6)]
+        c = add(wl.make_tokens(13, cfg["vocab"], seed=11))
+        for _ in range(10):
+            step()
+        assert exact >= 0.95 * total, (exact, total)
+        assert len({t[a] for t in first} | {t[b] for t in first}) > 3          # not a constant stream
+        # greedy again: the setting is read from device memory by the same captured step
+        s.ll_set_sampling(0.0, 0, 1.0, 0)
+        toks = s.ll_batch_step()
+        for slot in (a, b, c):
+            lg = s.ll_batch_dbg_get_logits(slot)
+            assert toks[slot] == int(np.flatnonzero(lg == lg.max())[0])
+        s.ll_batch_close()
+
+
 def test_batch_capacity_and_error_paths(torch_cuda):
     from paper_2604_23467_amd import binding as b
     cfg = wl.tiny_cfg(max_seq=40)
