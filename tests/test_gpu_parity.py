@@ -266,7 +266,7 @@ def test_error_paths_on_device(torch_cuda):
 
 
 # ------------------------------------------------------------ config 2: one 7B-shaped layer
-@pytest.mark.parametrize("kv_len", [10, 25, 128, 500])
+@pytest.mark.parametrize("kv_len", [10, 25, 50, 128, 250, 500])      # one length per prefill bucket
 def test_one_7b_layer_decode_step(torch_cuda, oracle32, kv_len):
     """d=4096, 32x128 heads, FFN 11008, fp16 N(0,0.02) weights.  The cache is
     filled by prefilling kv_len random hidden states (token i's embedding is an
