@@ -157,7 +157,7 @@ int ll_set_sampling(float temperature, int32_t top_k, float top_p, uint64_t seed
 int ll_shutdown(void);
 
 /* Longest prompt ll_prefill() accepts for the current instance: max_seq - 1.  Prompts of more
- * than 512 tokens are fed through the prefill kernels in chunks of 512 (the "longer contexts"
+ * than 1024 tokens are fed through the prefill kernels in chunks of 1024 (the "longer contexts"
  * direction of Sec. VI-E); the chunking is invisible to the caller. */
 int32_t ll_max_prompt(void);
 
@@ -224,7 +224,7 @@ int ll_dbg_graph_stats(int64_t *out4);
  * more than 32 tokens; host arithmetic only, needs no instance and no GPU):
  * out6 = { rows per tile, row tiles, runs (workgroups per row tile), K slabs per run, K slabs per
  * column tile as the runs count them (padded when runs end at tile borders), most slices any
- * column tile is cut into }.  rows is a prompt bucket (64, 128, 256 or 512). */
+ * column tile is cut into }.  rows is a prompt bucket (64, 128, 256, 512 or 1024). */
 int ll_dbg_gemm_plan(int32_t N, int32_t K, int32_t nmat, int32_t rows, int32_t *out6);
 /* Number of slices that hold the partial products of output column col (0 <= col < nmat * N)
  * under that plan, or a negative LL_E_* code. */

@@ -47,7 +47,7 @@ int fail(int code, const char* fmt, ...) {
 constexpr int kGemvU = 8;          // 512-element chunks of a weight row in flight per lane and row
 constexpr int kGemvWgsPerCu = 4;   // measured best of 2/3/4 on the 7B shapes
 constexpr int kAttnMaxSplits = 16;
-constexpr int kMaxPromptBucket = 512;
+constexpr int kMaxPromptBucket = 1024;   // rows of the largest prefill graph; longer prompts go through in chunks of it
 constexpr int kGemmWantWgs = 256;
 constexpr int kGemmMinSlabs = 8;
 constexpr size_t kAlign = 256;
@@ -67,7 +67,7 @@ bool config_ok(const ll_config* c, const char** why) {
   return w == nullptr;
 }
 
-int prompt_bucket(int n) {   // smallest of {64,128,256,512} holding n rows
+int prompt_bucket(int n) {   // smallest of {64,128,256,512,1024} holding n rows
   int b = 64;
   while (b < n) b <<= 1;
   return b;
@@ -80,8 +80,9 @@ bool skinny_ok(const ll_config& c) {
 
 // Row tile of the projection GEMM and how its K loops are dealt out: the 64-wide slabs of all
 // 256-column tiles form one sequence, cut into runs of `quota` slabs; with `mtiles` row tiles
-// the grid has runs x mtiles workgroups, at most one per CU (a second, partial round would cost
-// as much as a full one), and a run is at least kGemmMinSlabs long.
+// the grid has runs x mtiles workgroups.  Whatever splits a tile stays within one workgroup per CU
+// (a second, partial round would cost as much as a full one) and keeps runs of at least
+// kGemmMinSlabs slabs; whole tiles may take several rounds when they fill them well.
 int gemm_bm(int Mb) { return Mb >= 128 ? 128 : 64; }
 
 struct GemmPlan {
@@ -1451,7 +1452,7 @@ int ll_decode_mode(void) {
 }
 
 int ll_dbg_gemm_plan(int32_t N, int32_t K, int32_t nmat, int32_t rows, int32_t* out6) {
-  if (!out6 || N < 1 || K < 1 || nmat < 1 || nmat > 3 || (rows != 64 && rows != 128 && rows != 256 && rows != 512))
+  if (!out6 || N < 1 || K < 1 || nmat < 1 || nmat > 3 || (rows != 64 && rows != 128 && rows != 256 && rows != 512 && rows != 1024))
     return fail(LL_E_BAD_ARG, "ll_dbg_gemm_plan: bad argument");
   const GemmPlan p = gemm_plan(N, K, nmat, rows, nmat * N);
   out6[0] = gemm_bm(rows); out6[1] = p.mtiles; out6[2] = p.runs; out6[3] = p.map.quota;
@@ -1460,7 +1461,7 @@ int ll_dbg_gemm_plan(int32_t N, int32_t K, int32_t nmat, int32_t rows, int32_t* 
 }
 
 int ll_dbg_gemm_slice_count(int32_t N, int32_t K, int32_t nmat, int32_t rows, int32_t col) {
-  if (N < 1 || K < 1 || nmat < 1 || nmat > 3 || (rows != 64 && rows != 128 && rows != 256 && rows != 512) ||
+  if (N < 1 || K < 1 || nmat < 1 || nmat > 3 || (rows != 64 && rows != 128 && rows != 256 && rows != 512 && rows != 1024) ||
       col < 0 || col >= nmat * N)
     return fail(LL_E_BAD_ARG, "ll_dbg_gemm_slice_count: bad argument");
   const GemmPlan p = gemm_plan(N, K, nmat, rows, nmat * N);

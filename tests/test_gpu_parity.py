@@ -166,10 +166,11 @@ def test_graph_replay_equals_eager_and_decode_n(torch_cuda):
 
 
 @pytest.mark.parametrize("flags", [0, 1], ids=["graph", "eager"])
-@pytest.mark.parametrize("n_prompt,max_seq", [(513, 1200), (540, 1200), (600, 2000), (1100, 3500)])
+@pytest.mark.parametrize("n_prompt,max_seq", [(600, 1200), (1025, 1200), (1052, 2000), (1112, 2000), (2124, 3500)])
 def test_chunked_prefill_of_long_prompts(torch_cuda, oracle32, n_prompt, max_seq, flags):
-    """Prompts beyond the largest 512-row bucket are fed in chunks: 512 + a 1-row, a 28-row
-    (short-prompt kernels at a position offset), an 88-row and two full chunks + 76 rows, in instances of different capacity."""
+    """600 tokens fill part of the largest (1024-row) bucket; prompts beyond it are fed in chunks:
+    1024 + a 1-row, a 28-row (short-prompt kernels at a position offset) and an 88-row chunk, and two
+    full chunks + 76 rows, in instances of different capacity."""
     cfg = wl.custom_cfg(2, 2, 64, 136, 200, max_seq)
     w = wl.weights_astype(wl.make_weights_numpy(cfg, seed=61, gain_jitter=0.1, emb_std=0.5), np.float16)
     prompt = wl.make_tokens(n_prompt, cfg["vocab"], seed=n_prompt)
