@@ -77,3 +77,25 @@ def test_plan_rejects_bad_arguments():
         assert e.value.code == binding.LL_E_BAD_ARG
     with pytest.raises(binding.LLError):
         binding.ll_dbg_gemm_slice_count(64, 64, 1, 64, 64)
+
+
+def test_plan_invariants_on_random_shapes():
+    """The same coverage property on 300 seeded random shapes (N, K multiples of 8, as the library
+    requires of d_model and ffn_hidden)."""
+    import numpy as np
+    rng = np.random.default_rng(2024)
+    for _ in range(300):
+        N = int(rng.integers(1, 3000)) * 8
+        K = int(rng.integers(1, 2500)) * 8
+        nmat = int(rng.integers(1, 4))
+        rows = int(rng.choice([64, 128, 256, 512, 1024]))
+        plan = binding.ll_dbg_gemm_plan(N, K, nmat, rows)
+        s_real = -(-K // 64)
+        seen = {}
+        for tile, sl, first, cnt in walk(plan, N, K, nmat):
+            seen.setdefault(tile, []).append((sl, first, cnt))
+        assert len(seen) == -(-N // 256) * nmat
+        for tile, ps in seen.items():
+            assert sorted(s for _, first, cnt in ps for s in range(first, first + cnt)) == list(range(s_real)), (N, K, nmat, rows, tile)
+            assert sorted(sl for sl, _, _ in ps) == list(range(len(ps)))
+            assert len(ps) <= plan["max_slices"]
