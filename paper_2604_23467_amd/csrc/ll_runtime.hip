@@ -143,8 +143,8 @@ Layout make_layout(const ll_config& c) {
   Layout L{};
   const size_t d = c.d_model, F = c.ffn_hidden, V = c.vocab;
   // 1024-thread workgroups per head: two (merged for free by the O projection) up to 2 K
-  // positions, eight plus a small merge kernel in long-context instances
-  L.attn_splits = c.n_heads * 2 > 512 ? 1 : c.max_seq <= 2048 ? 2 : 8;
+  // positions, four plus a small merge kernel in long-context instances (measured best of 2..16)
+  L.attn_splits = c.n_heads * 2 > 512 ? 1 : c.max_seq <= 2048 ? 2 : 4;
   L.lm_wgs = gemv_grid((c.vocab + 1) / 2);
   L.max_prompt = c.max_seq - 1;                   // longer than the largest bucket: fed in chunks
   L.mb_max = prompt_bucket(L.max_prompt < kMaxPromptBucket ? L.max_prompt : kMaxPromptBucket);
