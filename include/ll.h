@@ -23,8 +23,15 @@
  * binary16 [d_model]; tok_emb and lm_head are [vocab, d_model] and not tied.
  *
  * Errors: every call returns >= 0 on success and a negative LL_E_* code on
- * failure; ll_last_error() then describes it.  A failed call leaves the
- * decoder state unchanged.  No exception crosses this boundary.
+ * failure; ll_last_error() then describes it.  A call that fails its argument,
+ * state or capacity checks (every error but LL_E_HIP) has run nothing and
+ * leaves the decoder state unchanged.  After LL_E_HIP (a launch, copy or
+ * synchronisation failed part-way, e.g. in the second chunk of a long prompt)
+ * the context is undefined: call ll_reset().  No exception crosses this boundary.
+ *
+ * Reproducibility: no kernel on any path accumulates in arrival order (there
+ * are no floating-point atomics), so the same call sequence on the same
+ * weights gives the same bits, run after run.
  */
 #ifndef LL_H
 #define LL_H

@@ -177,7 +177,7 @@ Layout make_layout(const ll_config& c) {
   }
   L.pf_part = take(part * 4);
   L.pf_h = take(M * ((F + 31) / 32 * 32) * 2);
-  L.pf_ss = take(2 * 64 * SK_SS_STRIDE * 4);
+  L.pf_ss = take((size_t)2 * 32 * sk_ss_stride(c.d_model) * 4);
   L.zeros = take(256);
   L.sample_cfg = take(sizeof(SampleCfg));
   L.mk_layers = take((size_t)c.n_layers * sizeof(MkLayer));
@@ -189,6 +189,24 @@ Layout make_layout(const ll_config& c) {
   return L;
 }
 
+// Buffers of a prefill call (and of the head of a decode step) that hold nothing the caller needs once
+// the call has returned: activations, partial sums, logits, selection candidates.  The KV rows, the
+// state block and the token ring are the call's outputs and live elsewhere.
+struct PfBuffers {
+  float* X;          // residual stream [rows][d] fp32
+  half_t* Xn;        // normalised operand of the next projection (fragment-major for <= 32 rows)
+  half_t* Q;         // rotated queries [rows][d]
+  half_t* O;         // attention output
+  half_t* H;         // SwiGLU output [rows][F]
+  float* part;       // slices of the prefill GEMM (prompts of more than 32 tokens)
+  float* ss;         // two sets of per-token partial sums of squares
+  int* tokens;       // prompt ids of the chunk in flight
+  float* logits;     // [vocab]
+  float* amax_val;   // per-workgroup argmax candidates of the LM head
+  int* amax_idx;
+  half_t* zeros;     // 256 bytes of zeros
+};
+
 struct Batch;
 void destroy_batch(Batch* B);
 
@@ -199,6 +217,9 @@ struct Instance {
   std::vector<ll_layer_weights> layers;
   ll_weights w;
   char* ws = nullptr;
+  PfBuffers pf{};               // the workspace's set of these buffers
+  const float* last_logits = nullptr;   // where the most recent step left its logits / residual rows
+  const float* last_rows = nullptr;
   hipStream_t stream = nullptr;
   bool own_stream = false;
   hipGraph_t dec_graph = nullptr;
@@ -280,7 +301,7 @@ void launch_gemv(const GemvArgs& a, int pairs, int grid_override, hipStream_t s)
 }
 
 // final RMSNorm + LM head + argmax + state advance, shared by decode and prefill
-void enqueue_head(Instance* I, hipStream_t s, const float* xin, int from_prompt_row, int prefill) {
+void enqueue_head(Instance* I, hipStream_t s, const PfBuffers& B, const float* xin, int from_prompt_row, int prefill) {
   const ll_config& c = I->cfg;
   if (I->runs(LL_KC_LMHEAD)) {
     ProfScope ps(I, s, LL_KC_LMHEAD);
@@ -288,20 +309,20 @@ void enqueue_head(Instance* I, hipStream_t s, const float* xin, int from_prompt_
     a.w0 = (const half_t*)I->w.lm_head;
     a.xin = xin;
     a.gain = (const half_t*)I->w.final_norm;
-    a.out = I->at<float>(I->L.logits);
+    a.out = B.logits;
     a.N = c.vocab;
     a.K = c.d_model;
     a.eps = c.rms_eps;
     a.st = I->state();
-    a.amax_val = I->at<float>(I->L.amax_val);
-    a.amax_idx = I->at<int>(I->L.amax_idx);
+    a.amax_val = B.amax_val;
+    a.amax_idx = B.amax_idx;
     a.x_row_from_prompt = from_prompt_row;
     launch_gemv<GM_LMHEAD>(a, (c.vocab + 1) / 2, I->L.lm_wgs, s);
   }
   if (I->runs(LL_KC_SAMPLE)) {
     ProfScope ps(I, s, LL_KC_SAMPLE);
-    hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(SMP_THREADS), SMP_Z_WORDS * 4, s, I->at<float>(I->L.amax_val),
-                       I->at<int>(I->L.amax_idx), I->L.lm_wgs, I->at<float>(I->L.logits), c.vocab,
+    hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(SMP_THREADS), SMP_Z_WORDS * 4, s, B.amax_val,
+                       B.amax_idx, I->L.lm_wgs, B.logits, c.vocab,
                        I->at<SampleCfg>(I->L.sample_cfg), I->state(), I->dev_ring, I->ring_size, prefill);
   }
 }
@@ -373,7 +394,7 @@ void enqueue_decode_multi(Instance* I, hipStream_t s) {
       else launch_gemv<GM_DOWN>(a, d / 2, 0, s);   // short rows, or too long to split over one workgroup
     }
   }
-  enqueue_head(I, s, x, 0, 0);
+  enqueue_head(I, s, I->pf, x, 0, 0);
 }
 
 // Can the whole step run as one persistent kernel on this device / shape?
@@ -447,15 +468,15 @@ void enqueue_decode(Instance* I, hipStream_t s) {
 
 // Projection GEMM A W_z^T into the slice buffer; the returned map tells the consuming kernel
 // which slices to add up for which column.
-SliceMap launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0, const void* w1,
+SliceMap launch_gemm(Instance* I, hipStream_t s, const PfBuffers& B, const half_t* A, const void* w0, const void* w1,
                      const void* w2, int nmat, int ldc, int N, int K, int Mb) {
   const GemmPlan p = gemm_plan(N, K, nmat, Mb, ldc);
   GemmArgs ga{};
   ga.A = A;
   ga.W[0] = (const half_t*)w0; ga.W[1] = (const half_t*)w1; ga.W[2] = (const half_t*)w2;
-  ga.C = I->at<float>(I->L.pf_part);
+  ga.C = B.part;
   ga.st = I->state();
-  ga.zeros = I->at<half_t>(I->L.zeros);
+  ga.zeros = B.zeros;
   ga.N = N; ga.K = K; ga.ldc = ldc; ga.nmat = nmat;
   ga.mtiles = p.mtiles; ga.runs = p.runs; ga.map = p.map;
   dim3 grid((p.runs + 7) / 8 * 8 * p.mtiles);      // runs are dealt to the 8 XCDs
@@ -469,8 +490,8 @@ SliceMap launch_gemm(Instance* I, hipStream_t s, const half_t* A, const void* w0
 int g_num_cus = 256;
 
 template <int MODE>
-void launch_skinny(Instance* I, hipStream_t s, SkinnyArgs a, int Mb) {
-  a.zeros_off = I->at<half_t>(I->L.zeros) - a.X;
+void launch_skinny(hipStream_t s, const PfBuffers& B, SkinnyArgs a, int Mb) {
+  a.zeros_off = B.zeros - a.X;
   if constexpr (MODE != SK_RES) {
     const int per_wave = (((a.K + 31) >> 5) + SK_WAVES - 1) / SK_WAVES;
     if (per_wave <= SKP_KSTEPS) {
@@ -501,28 +522,25 @@ void launch_skinny(Instance* I, hipStream_t s, SkinnyArgs a, int Mb) {
 
 // Prompts of at most 32 tokens: five kernels per layer, every projection streams its weights
 // once and finishes its own epilogue; the norms ride on the projections around them.
-void enqueue_prefill_skinny(Instance* I, hipStream_t s, int Mb, bool with_head) {
+void enqueue_prefill_skinny(Instance* I, hipStream_t s, const PfBuffers& B, int Mb, bool with_head) {
   const ll_config& c = I->cfg;
   const int d = c.d_model, F = c.ffn_hidden;
-  float* X = I->at<float>(I->L.pf_x);
-  half_t* Xn = I->at<half_t>(I->L.pf_xn);
-  half_t* Qh = I->at<half_t>(I->L.pf_q);
-  half_t* Oh = I->at<half_t>(I->L.pf_o);
-  half_t* Hm = I->at<half_t>(I->L.pf_h);
-  float* ss_attn = I->at<float>(I->L.pf_ss);      // sum of squares in front of the attention block
-  float* ss_ffn = ss_attn + 64 * SK_SS_STRIDE;                  // ... and in front of the FFN
+  float* X = B.X;
+  half_t *Xn = B.Xn, *Qh = B.Q, *Oh = B.O, *Hm = B.H;
+  const int sst = sk_ss_stride(d), parts = d / 16;
+  float* ss_attn = B.ss;                          // sums of squares in front of the attention block
+  float* ss_ffn = ss_attn + (size_t)32 * sst;     // ... and in front of the FFN
   const int tb = Mb / 16;       // token blocks: the activations' fragment-major layout depends on it
   hipLaunchKernelGGL(pf_embed_norm_kernel, dim3(Mb), dim3(LL_WG), 0, s, (const half_t*)I->w.tok_emb,
-                     I->at<int>(I->L.tokens), I->state(), (const half_t*)I->layers[0].attn_norm, X, Xn,
-                     ss_attn, ss_ffn, d, tb);
+                     B.tokens, I->state(), (const half_t*)I->layers[0].attn_norm, X, Xn, ss_attn, sst, d, tb);
   for (int l = 0; l < c.n_layers; ++l) {
     const ll_layer_weights& W = I->layers[l];
     SkinnyArgs a{};
-    a.st = I->state(); a.head_dim = c.head_dim; a.max_seq = c.max_seq; a.eps = c.rms_eps;
+    a.st = I->state(); a.head_dim = c.head_dim; a.max_seq = c.max_seq; a.eps = c.rms_eps; a.ss_stride = sst;
     a.X = Xn; a.W[0] = (const half_t*)W.wq; a.W[1] = (const half_t*)W.wk; a.W[2] = (const half_t*)W.wv;
     a.N = d; a.K = d; a.Q = Qh; a.kc = I->kcache(l); a.vc = I->vcache(l); a.rope = I->at<float2>(I->L.rope);
-    a.ss_in = ss_attn;
-    launch_skinny<SK_QKV>(I, s, a, Mb);
+    a.ss_in = ss_attn; a.ss_parts = l == 0 ? 1 : parts;     // the embedding gather leaves whole sums in slot 0
+    launch_skinny<SK_QKV>(s, B, a, Mb);
     dim3 agrid(c.n_heads, 1);
     if (c.head_dim == 128)
       hipLaunchKernelGGL((pf_attn_kernel<128, 1>), agrid, dim3(128), PF_ATTN_LDS_BYTES(128, 1), s, Qh, I->kcache(l),
@@ -531,27 +549,27 @@ void enqueue_prefill_skinny(Instance* I, hipStream_t s, int Mb, bool with_head) 
       hipLaunchKernelGGL((pf_attn_kernel<64, 1>), agrid, dim3(128), PF_ATTN_LDS_BYTES(64, 1), s, Qh, I->kcache(l),
                          I->vcache(l), I->state(), Oh, d, c.max_seq, tb);
     a.X = Oh; a.W[0] = (const half_t*)W.wo; a.W[1] = a.W[2] = nullptr; a.N = d; a.K = d; a.Xres = X;
-    a.gain_next = (const half_t*)W.ffn_norm; a.Xh_next = Xn; a.ss_out = ss_ffn; a.ss_zero = ss_attn;
-    launch_skinny<SK_RES>(I, s, a, Mb);
+    a.gain_next = (const half_t*)W.ffn_norm; a.Xh_next = Xn; a.ss_out = ss_ffn;
+    launch_skinny<SK_RES>(s, B, a, Mb);
     a.X = Xn; a.W[0] = (const half_t*)W.w_gate; a.W[1] = (const half_t*)W.w_up; a.N = F; a.K = d; a.Hout = Hm;
-    a.ss_in = ss_ffn;
-    launch_skinny<SK_GATEUP>(I, s, a, Mb);
+    a.ss_in = ss_ffn; a.ss_parts = parts;
+    launch_skinny<SK_GATEUP>(s, B, a, Mb);
     a.X = Hm; a.W[0] = (const half_t*)W.w_down; a.W[1] = nullptr; a.N = d; a.K = F; a.Xres = X;
     a.gain_next = l + 1 < c.n_layers ? (const half_t*)I->layers[l + 1].attn_norm : nullptr;
-    a.Xh_next = Xn; a.ss_out = ss_attn; a.ss_zero = ss_ffn;
-    launch_skinny<SK_RES>(I, s, a, Mb);
+    a.Xh_next = Xn; a.ss_out = ss_attn;
+    launch_skinny<SK_RES>(s, B, a, Mb);
   }
-  if (with_head) enqueue_head(I, s, X, 1, 1);
+  if (with_head) enqueue_head(I, s, B, X, 1, 1);
 }
 
 // Prefill attention of layer l for a bucket of Mb >= 64 rows: the longer the prompt, the more
 // key groups share a query block (a chunk of a long prompt attends everything cached before it)
 template <int HD>
-void launch_attn_hd(Instance* I, hipStream_t s, int l, int Mb) {
+void launch_attn_hd(Instance* I, hipStream_t s, const PfBuffers& B, int l, int Mb) {
   const ll_config& c = I->cfg;
   dim3 grid(c.n_heads, Mb / 64);
-  const half_t* Qh = I->at<half_t>(I->L.pf_q);
-  half_t* Oh = I->at<half_t>(I->L.pf_o);
+  const half_t* Qh = B.Q;
+  half_t* Oh = B.O;
   const int groups = (Mb >= 256 || c.max_seq - 1 > kMaxPromptBucket) ? 4 : Mb >= 128 ? 2 : 1;
   if (groups == 4)
     hipLaunchKernelGGL((pf_attn_kernel<HD, 4>), grid, dim3(512), PF_ATTN_LDS_BYTES(HD, 4), s, Qh, I->kcache(l),
@@ -564,47 +582,45 @@ void launch_attn_hd(Instance* I, hipStream_t s, int l, int Mb) {
                        I->vcache(l), I->state(), Oh, c.d_model, c.max_seq, 0);
 }
 
-void launch_attn(Instance* I, hipStream_t s, int l, int Mb) {
-  if (I->cfg.head_dim == 128) launch_attn_hd<128>(I, s, l, Mb);
-  else launch_attn_hd<64>(I, s, l, Mb);
+void launch_attn(Instance* I, hipStream_t s, const PfBuffers& B, int l, int Mb) {
+  if (I->cfg.head_dim == 128) launch_attn_hd<128>(I, s, B, l, Mb);
+  else launch_attn_hd<64>(I, s, B, l, Mb);
 }
 
 void enqueue_prefill(Instance* I, hipStream_t s, int Mb, bool with_head = true) {
-  if (Mb <= 32 && I->skinny) return enqueue_prefill_skinny(I, s, Mb, with_head);
+  const PfBuffers& B = I->pf;
+  if (Mb <= 32 && I->skinny) return enqueue_prefill_skinny(I, s, B, Mb, with_head);
   const ll_config& c = I->cfg;
   const int d = c.d_model, F = c.ffn_hidden;
-  float* X = I->at<float>(I->L.pf_x);
-  half_t* Xn = I->at<half_t>(I->L.pf_xn);
-  half_t* Qh = I->at<half_t>(I->L.pf_q);
-  half_t* Oh = I->at<half_t>(I->L.pf_o);
-  half_t* Hm = I->at<half_t>(I->L.pf_h);
-  const float* P = I->at<float>(I->L.pf_part);     // slices of the GEMM that ran last
+  float* X = B.X;
+  half_t *Xn = B.Xn, *Qh = B.Q, *Oh = B.O, *Hm = B.H;
+  const float* P = B.part;                         // slices of the GEMM that ran last
   hipLaunchKernelGGL(pf_embed_kernel, dim3(Mb, (d + LL_WG * 8 - 1) / (LL_WG * 8)), dim3(LL_WG), 0, s,
-                     (const half_t*)I->w.tok_emb, I->at<int>(I->L.tokens), I->state(), X, d);
+                     (const half_t*)I->w.tok_emb, B.tokens, I->state(), X, d);
   SliceMap res{};                                  // the residual GEMM whose slices are still to be added to X
   const float* res_part = nullptr;
   for (int l = 0; l < c.n_layers; ++l) {
     const ll_layer_weights& W = I->layers[l];
     hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(PF_NORM_THREADS), 0, s, X, (const half_t*)W.attn_norm,
                        Xn, d, c.rms_eps, I->state(), res_part, res, 0);
-    const SliceMap qkv = launch_gemm(I, s, Xn, W.wq, W.wk, W.wv, 3, 3 * d, d, d, Mb);
+    const SliceMap qkv = launch_gemm(I, s, B, Xn, W.wq, W.wk, W.wv, 3, 3 * d, d, d, Mb);
     hipLaunchKernelGGL(pf_rope_kv_kernel, dim3(Mb, (d / 8 + LL_WG - 1) / LL_WG), dim3(LL_WG), 0, s, P, qkv,
                        I->at<float2>(I->L.rope), I->state(), Qh, I->kcache(l), I->vcache(l), d,
                        c.head_dim, c.max_seq);
-    launch_attn(I, s, l, Mb);
-    res = launch_gemm(I, s, Oh, W.wo, nullptr, nullptr, 1, d, d, d, Mb);
+    launch_attn(I, s, B, l, Mb);
+    res = launch_gemm(I, s, B, Oh, W.wo, nullptr, nullptr, 1, d, d, d, Mb);
     res_part = P;
     hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(PF_NORM_THREADS), 0, s, X, (const half_t*)W.ffn_norm,
                        Xn, d, c.rms_eps, I->state(), res_part, res, 0);
-    const SliceMap gu = launch_gemm(I, s, Xn, W.w_gate, W.w_up, nullptr, 2, 2 * F, F, d, Mb);
+    const SliceMap gu = launch_gemm(I, s, B, Xn, W.w_gate, W.w_up, nullptr, 2, 2 * F, F, d, Mb);
     hipLaunchKernelGGL(pf_swiglu_kernel, dim3(Mb, (F + LL_WG * 4 - 1) / (LL_WG * 4)), dim3(LL_WG), 0,
                        s, P, gu, I->state(), Hm, F);
-    res = launch_gemm(I, s, Hm, W.w_down, nullptr, nullptr, 1, d, d, F, Mb);
+    res = launch_gemm(I, s, B, Hm, W.w_down, nullptr, nullptr, 1, d, d, F, Mb);
   }
   if (with_head && res_part)    // (a chunk that is not the prompt's last needs nothing of X any more)
     hipLaunchKernelGGL(pf_fold_kernel, dim3(Mb, (d + LL_WG * 4 - 1) / (LL_WG * 4)), dim3(LL_WG), 0, s, X,
                        I->state(), P, res, d);
-  if (with_head) enqueue_head(I, s, X, 1, 1);
+  if (with_head) enqueue_head(I, s, B, X, 1, 1);
 }
 
 int capture_on(Instance* I, hipStream_t cs, hipGraph_t* graph, hipGraphExec_t* exec, int prefill_bucket,
@@ -796,29 +812,28 @@ void destroy_batch(Batch* B) {
 // One decode step of all slots: the 16 or 32 rows of the short-prompt kernels are the slots.
 void enqueue_batch_step(Instance* I, hipStream_t s) {
   Batch* B = I->batch;
+  const PfBuffers& P = I->pf;
   const ll_config& c = I->cfg;
   const int d = c.d_model, F = c.ffn_hidden, Mb = B->rows, tb = Mb / 16;
-  float* X = I->at<float>(I->L.pf_x);
-  half_t* Xn = I->at<half_t>(I->L.pf_xn);
-  half_t* Qh = I->at<half_t>(I->L.pf_q);
-  half_t* Oh = I->at<half_t>(I->L.pf_o);
-  half_t* Hm = I->at<half_t>(I->L.pf_h);
-  float* ss_attn = I->at<float>(I->L.pf_ss);
-  float* ss_ffn = ss_attn + 64 * SK_SS_STRIDE;
+  float* X = P.X;
+  half_t *Xn = P.Xn, *Qh = P.Q, *Oh = P.O, *Hm = P.H;
+  const int sst = sk_ss_stride(d), parts = d / 16;
+  float* ss_attn = P.ss;
+  float* ss_ffn = ss_attn + (size_t)32 * sst;
   BatchState* bs = B->at<BatchState>(B->L.state);
   const DevState* st = B->at<DevState>(B->L.dstate);          // n_prompt = rows of the step, pos unused
   const int* table = B->at<int>(B->L.page_table);
   hipLaunchKernelGGL(pf_embed_norm_kernel, dim3(Mb), dim3(LL_WG), 0, s, (const half_t*)I->w.tok_emb,
-                     bs->next_token, st, (const half_t*)I->layers[0].attn_norm, X, Xn, ss_attn, ss_ffn, d, tb);
+                     bs->next_token, st, (const half_t*)I->layers[0].attn_norm, X, Xn, ss_attn, sst, d, tb);
   for (int l = 0; l < c.n_layers; ++l) {
     const ll_layer_weights& W = I->layers[l];
     SkinnyArgs a{};
-    a.st = st; a.head_dim = c.head_dim; a.max_seq = B->L.pool_rows; a.eps = c.rms_eps;
+    a.st = st; a.head_dim = c.head_dim; a.max_seq = B->L.pool_rows; a.eps = c.rms_eps; a.ss_stride = sst;
     a.X = Xn; a.W[0] = (const half_t*)W.wq; a.W[1] = (const half_t*)W.wk; a.W[2] = (const half_t*)W.wv;
     a.N = d; a.K = d; a.Q = Qh; a.kc = B->kpool(l); a.vc = B->vpool(l); a.rope = I->at<float2>(I->L.rope);
-    a.ss_in = ss_attn;
+    a.ss_in = ss_attn; a.ss_parts = l == 0 ? 1 : parts;
     a.row_pos = bs->pos; a.page_table = table; a.pt_stride = B->L.pt_stride; a.page_tokens = B->page_tokens;
-    launch_skinny<SK_QKV>(I, s, a, Mb);
+    launch_skinny<SK_QKV>(s, P, a, Mb);
     dim3 agrid(c.n_heads, Mb);
     if (c.head_dim == 128)
       hipLaunchKernelGGL(bt_attn_kernel<128>, agrid, dim3(BT_ATTN_THREADS), (size_t)B->L.pt_stride * 4, s, Qh, B->kpool(l), B->vpool(l), bs,
@@ -828,23 +843,23 @@ void enqueue_batch_step(Instance* I, hipStream_t s) {
                          table, B->L.pt_stride, B->page_tokens, Oh, d, B->L.pool_rows, tb);
     a.row_pos = nullptr; a.page_table = nullptr;
     a.X = Oh; a.W[0] = (const half_t*)W.wo; a.W[1] = a.W[2] = nullptr; a.N = d; a.K = d; a.Xres = X;
-    a.gain_next = (const half_t*)W.ffn_norm; a.Xh_next = Xn; a.ss_out = ss_ffn; a.ss_zero = ss_attn;
-    launch_skinny<SK_RES>(I, s, a, Mb);
+    a.gain_next = (const half_t*)W.ffn_norm; a.Xh_next = Xn; a.ss_out = ss_ffn;
+    launch_skinny<SK_RES>(s, P, a, Mb);
     a.X = Xn; a.W[0] = (const half_t*)W.w_gate; a.W[1] = (const half_t*)W.w_up; a.N = F; a.K = d; a.Hout = Hm;
-    a.ss_in = ss_ffn;
-    launch_skinny<SK_GATEUP>(I, s, a, Mb);
+    a.ss_in = ss_ffn; a.ss_parts = parts;
+    launch_skinny<SK_GATEUP>(s, P, a, Mb);
     a.X = Hm; a.W[0] = (const half_t*)W.w_down; a.W[1] = nullptr; a.N = d; a.K = F; a.Xres = X;
     a.gain_next = l + 1 < c.n_layers ? (const half_t*)I->layers[l + 1].attn_norm : (const half_t*)I->w.final_norm;
-    a.Xh_next = Xn; a.ss_out = ss_attn; a.ss_zero = ss_ffn;
-    launch_skinny<SK_RES>(I, s, a, Mb);
+    a.Xh_next = Xn; a.ss_out = ss_attn;
+    launch_skinny<SK_RES>(s, P, a, Mb);
   }
   {
     // LM head of all rows: the wide persistent projection with a plain fp32 epilogue
     SkinnyArgs a{};
     a.st = st; a.eps = c.rms_eps; a.head_dim = c.head_dim; a.max_seq = c.max_seq;
     a.X = Xn; a.W[0] = (const half_t*)I->w.lm_head; a.N = c.vocab; a.K = d;
-    a.ss_in = ss_attn; a.logits = B->at<float>(B->L.logits);
-    a.zeros_off = I->at<half_t>(I->L.zeros) - a.X;
+    a.ss_in = ss_attn; a.ss_stride = sst; a.ss_parts = parts; a.logits = B->at<float>(B->L.logits);
+    a.zeros_off = P.zeros - a.X;
     const int units = skinny_units(SK_LOGITS, c.vocab);
     dim3 grid(units < g_num_cus ? units : g_num_cus);
     if (tb == 1) hipLaunchKernelGGL((pf_skinny_persist_kernel<SK_LOGITS, 1>), grid, dim3(SK_THREADS), 0, s, a);
@@ -903,6 +918,10 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   I->w = *w;
   I->w.layers = I->layers.data();
   I->ws = static_cast<char*>(workspace);
+  I->pf = PfBuffers{I->at<float>(L.pf_x), I->at<half_t>(L.pf_xn), I->at<half_t>(L.pf_q), I->at<half_t>(L.pf_o),
+                    I->at<half_t>(L.pf_h), I->at<float>(L.pf_part), I->at<float>(L.pf_ss), I->at<int>(L.tokens),
+                    I->at<float>(L.logits), I->at<float>(L.amax_val), I->at<int>(L.amax_idx), I->at<half_t>(L.zeros)};
+  I->last_logits = I->pf.logits;
   int rc = LL_OK;
   auto bail = [&](int code) { destroy(I); return code; };
 
@@ -1092,17 +1111,32 @@ int32_t ll_position(void) {
   return g->pos;
 }
 
+}  // extern "C"
+
+namespace {
+
+// Checks shared by the two prefill entry points
+int prefill_check(Instance* I, const char* who, const int32_t* tokens, int32_t n) {
+  if (!tokens) return fail(LL_E_BAD_ARG, "%s: null tokens", who);
+  if (n < 1) return fail(LL_E_BAD_ARG, "%s: n = %d < 1", who, n);
+  if (I->pos != 0) return fail(LL_E_STATE, "%s: context holds %d positions; call ll_reset", who, I->pos);
+  if (n + 1 > I->cfg.max_seq) return fail(LL_E_CAPACITY, "%s: n + 1 = %d > max_seq = %d", who, n + 1, I->cfg.max_seq);
+  if (n > I->L.max_prompt) return fail(LL_E_CAPACITY, "%s: n = %d > ll_max_prompt() = %d", who, n, I->L.max_prompt);
+  for (int i = 0; i < n; ++i)
+    if (tokens[i] < 0 || tokens[i] >= I->cfg.vocab)
+      return fail(LL_E_BAD_ARG, "%s: tokens[%d] = %d outside [0, %d)", who, i, tokens[i], I->cfg.vocab);
+  return LL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
 int32_t ll_prefill(const int32_t* tokens, int32_t n) {
   if (!g) return fail(LL_E_NOT_INIT, "ll_prefill: not initialised");
   Instance* I = g;
-  if (!tokens) return fail(LL_E_BAD_ARG, "ll_prefill: null tokens");
-  if (n < 1) return fail(LL_E_BAD_ARG, "ll_prefill: n = %d < 1", n);
-  if (I->pos != 0) return fail(LL_E_STATE, "ll_prefill: context holds %d positions; call ll_reset", I->pos);
-  if (n + 1 > I->cfg.max_seq) return fail(LL_E_CAPACITY, "ll_prefill: n + 1 = %d > max_seq = %d", n + 1, I->cfg.max_seq);
-  if (n > I->L.max_prompt) return fail(LL_E_CAPACITY, "ll_prefill: n = %d > ll_max_prompt() = %d", n, I->L.max_prompt);
-  for (int i = 0; i < n; ++i)
-    if (tokens[i] < 0 || tokens[i] >= I->cfg.vocab)
-      return fail(LL_E_BAD_ARG, "ll_prefill: tokens[%d] = %d outside [0, %d)", i, tokens[i], I->cfg.vocab);
+  const int chk = prefill_check(I, "ll_prefill", tokens, n);
+  if (chk != LL_OK) return chk;
 
   // prompt ids and the state block travel in one pinned staging buffer.  A prompt longer than the
   // largest bucket goes through in chunks of that size: every chunk but the last runs the layers
@@ -1118,7 +1152,7 @@ int32_t ll_prefill(const int32_t* tokens, int32_t n) {
     hs->n_prompt = m;
     memcpy(htok, tokens + p0, (size_t)m * 4);
     HIPCHK(hipMemcpyAsync(I->state(), hs, sizeof(DevState), hipMemcpyHostToDevice, I->stream));
-    HIPCHK(hipMemcpyAsync(I->at<int>(I->L.tokens), htok, (size_t)m * 4, hipMemcpyHostToDevice, I->stream));
+    HIPCHK(hipMemcpyAsync(I->pf.tokens, htok, (size_t)m * 4, hipMemcpyHostToDevice, I->stream));
     if (eager(I)) {
       enqueue_prefill(I, I->stream, Mb, last);
       HIPCHK(hipGetLastError());
@@ -1136,6 +1170,8 @@ int32_t ll_prefill(const int32_t* tokens, int32_t n) {
   I->pos = n;
   I->steps = 1;
   I->last_was_prefill = true;
+  I->last_logits = I->pf.logits;
+  I->last_rows = I->pf.X;
   return I->host_ring[0];
 }
 
@@ -1159,6 +1195,7 @@ int32_t ll_decode_n(int32_t k, int32_t* out_tokens) {
   I->pos += k;
   I->steps += k;
   I->last_was_prefill = false;
+  I->last_logits = I->pf.logits;
   return I->host_ring[I->steps - 1];
 }
 
@@ -1479,7 +1516,7 @@ int ll_dbg_get_logits(float* host_out) {
   if (!g) return fail(LL_E_NOT_INIT, "ll_dbg_get_logits: not initialised");
   if (!host_out) return fail(LL_E_BAD_ARG, "ll_dbg_get_logits: null output");
   HIPCHK(hipStreamSynchronize(g->stream));
-  HIPCHK(hipMemcpy(host_out, g->at<float>(g->L.logits), (size_t)g->cfg.vocab * 4, hipMemcpyDeviceToHost));
+  HIPCHK(hipMemcpy(host_out, g->last_logits, (size_t)g->cfg.vocab * 4, hipMemcpyDeviceToHost));
   return LL_OK;
 }
 
@@ -1489,7 +1526,7 @@ int ll_dbg_get_hidden(float* host_out) {
   if (g->pos == 0) return fail(LL_E_STATE, "ll_dbg_get_hidden: no step has run");
   HIPCHK(hipStreamSynchronize(g->stream));
   const float* src = g->last_was_prefill
-                         ? g->at<float>(g->L.pf_x) + (size_t)(g->last_chunk_rows - 1) * g->cfg.d_model
+                         ? g->last_rows + (size_t)(g->last_chunk_rows - 1) * g->cfg.d_model
                          : g->at<float>(g->L.x);
   HIPCHK(hipMemcpy(host_out, src, (size_t)g->cfg.d_model * 4, hipMemcpyDeviceToHost));
   return LL_OK;
@@ -1558,6 +1595,7 @@ int ll_dbg_profile_decode(int32_t steps, float* us_out, int32_t* launches_out) {
   I->pos += steps;
   I->steps += steps;
   I->last_was_prefill = false;
+  I->last_logits = I->pf.logits;
   for (int i = 0; i < LL_KC_COUNT; ++i) {
     us_out[i] = cnt[i] ? (float)(sum[i] / cnt[i]) : 0.f;
     if (launches_out) launches_out[i] = (int32_t)(cnt[i] / steps);
@@ -1582,6 +1620,7 @@ int ll_dbg_trace_decode(uint64_t* ticks_out, int32_t max_phases) {
   I->pos += 1;
   I->steps += 1;
   I->last_was_prefill = false;
+  I->last_logits = I->pf.logits;
   return phases;
 }
 
@@ -1648,6 +1687,7 @@ int ll_dbg_time_decode(int32_t k, float* ms_out) {
   I->pos += k;
   I->steps += k;
   I->last_was_prefill = false;
+  I->last_logits = I->pf.logits;
   return LL_OK;
 }
 

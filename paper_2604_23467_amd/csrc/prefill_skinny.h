@@ -30,10 +30,12 @@
 //
 // RMSNorm costs no kernel of its own.  The kernel that finishes a residual
 // update (SK_RES, or the embedding gather for layer 0) also stores the fp16
-// operand x * gain of the NEXT projection and adds each token's sum of squares
-// into a small buffer; the consuming projection (SK_QKV / SK_GATEUP) multiplies
-// its finished sums by rsqrt(mean x^2 + eps), which commutes with the
-// contraction: W (x g) s = s W (x g).
+// operand x * gain of the NEXT projection and, per token, the sum of squares of
+// the 16 columns its workgroup owns into a slot of its own; the consuming
+// projection (SK_QKV / SK_GATEUP) adds a token's slots in a fixed order and
+// multiplies its finished sums by rsqrt(mean x^2 + eps), which commutes with
+// the contraction: W (x g) s = s W (x g).  No atomics: every run of the same
+// input gives the same bits.
 #pragma once
 #include "ll_device.h"
 
@@ -47,9 +49,11 @@ struct SkinnyArgs {
   float* Xres;            // RES: residual stream [rows][N] fp32, updated in place for rows < n
   const half_t* gain_next;// RES: gain of the norm in front of the next projection (null: none follows)
   half_t* Xh_next;        // RES: fp16 x * gain_next, fragment-major, operand of the next projection
-  float* ss_out;          // RES: [16 TB] per-token sum of squares of the updated residual (atomic adds)
-  float* ss_zero;         // RES: [16 TB] buffer to clear for the projection after the next
-  const float* ss_in;     // QKV / GATEUP: per-token sum of squares of the operand's source
+  float* ss_out;          // RES: [16 TB][ss_stride] per-token sums of squares of the updated residual, slot
+                          //      blockIdx.x = the 16 columns of this workgroup
+  const float* ss_in;     // QKV / GATEUP / LOGITS: [16 TB][ss_stride], slots 0 .. ss_parts - 1 of a token add up
+                          //      to the sum of squares of the operand's source row
+  int ss_stride, ss_parts;
   float eps;
   half_t* Hout;           // GATEUP: 16 TB rows x N fp16, fragment-major
   half_t* Q;              // QKV: [rows][N] fp16 rotated queries
@@ -79,7 +83,39 @@ __device__ __forceinline__ int sk_cache_row(const SkinnyArgs& a, int tok, int po
 #define SK_WAVES 8
 #define SK_THREADS (SK_WAVES * 64)
 #define SK_PSTRIDE 20      // floats per (wave, token) row of partials: 16 + pad, keeps 16-byte alignment
-#define SK_SS_STRIDE 64    // floats between two tokens' sums of squares: one L2 channel each for the atomics
+
+// floats between two tokens' slots of partial sums of squares: one slot per 16-column block of a
+// d_model-wide residual row, rounded up to whole 64-byte groups
+__host__ __device__ inline int sk_ss_stride(int d_model) { return ((d_model + 15) / 16 + 15) / 16 * 16; }
+
+// rsqrt(mean x^2 + eps) of the 16 TB token rows into LDS: 16 lanes per token add its slots in a
+// fixed order (strided partial sums, then a DPP tree).  Needs 256 TB threads.  Two steps, so that
+// the loads can be put in flight ahead of a kernel's weight stream and their values used after
+// it has started: the wait for them then leaves the younger weight loads in flight.  The
+// caller's next workgroup barrier publishes s_scale.
+struct SkSsLoads { float v[16]; float tail; };
+template <int TB>
+__device__ __forceinline__ void sk_ss_issue(const float* ss_in, int ss_stride, int ss_parts, int tid, SkSsLoads& L) {
+  L.tail = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) L.v[i] = 0.f;
+  if (tid < TB * 256) {
+    const int tok = tid >> 4, j = tid & 15;
+    const float* p = ss_in + (size_t)tok * ss_stride;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      if (j + 16 * i < ss_parts) L.v[i] = *as_global(p + j + 16 * i);
+    for (int i = j + 256; i < ss_parts; i += 16) L.tail += *as_global(p + i);   // d_model > 4096 only
+  }
+}
+template <int TB>
+__device__ __forceinline__ void sk_ss_finish(const SkSsLoads& L, int K, float eps, float* s_scale, int tid) {
+  float s = L.tail;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s += L.v[i];
+  s = group_sum<16>(s);
+  if (tid < TB * 256 && (tid & 15) == 0) s_scale[tid >> 4] = 1.0f / sqrtf(s / (float)K + eps);
+}
 
 // number of 16-row blocks the kernel's grid has to cover
 __host__ __device__ inline int skinny_units(int mode, int N) {
@@ -92,6 +128,7 @@ template <int MODE, int TB, int NB>
 __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_kernel(SkinnyArgs a) {
   constexpr int RB = 1;
   __shared__ __attribute__((aligned(16))) float part[SK_WAVES * TB * 16 * SK_PSTRIDE];
+  __shared__ float s_scale[TB * 16];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 15, g = lane >> 4;
@@ -137,6 +174,11 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_kernel(SkinnyArgs a) 
     ex0 = *as_global(reinterpret_cast<const f4*>(xp));
     ex1 = *as_global(reinterpret_cast<const f4*>(xp + 4));
     if (a.gain_next) egain = load_h8(a.gain_next + c0);
+  }
+  if (MODE != SK_RES) {
+    SkSsLoads sl;
+    sk_ss_issue<TB>(a.ss_in, a.ss_stride, a.ss_parts, tid, sl);
+    sk_ss_finish<TB>(sl, K, a.eps, s_scale, tid);
   }
   __builtin_amdgcn_sched_barrier(0);
 
@@ -240,15 +282,14 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_kernel(SkinnyArgs a) 
     }
     if (tid < TB * 32) {
       ss += dpp_mov<0xB1>(ss);                     // the token's other half sits in the neighbouring lane
-      if (efin && (tid & 1) == 0 && a.gain_next) unsafeAtomicAdd(a.ss_out + (tid >> 1) * SK_SS_STRIDE, ss);
+      if (efin && (tid & 1) == 0 && a.gain_next) a.ss_out[(size_t)(tid >> 1) * a.ss_stride + blockIdx.x] = ss;
     }
-    if (blockIdx.x == 0 && tid < TB * 16 && a.ss_zero) a.ss_zero[tid * SK_SS_STRIDE] = 0.f;
   } else {
     for (int o = tid; o < RB * TB * 16; o += SK_THREADS) {
       const int tok = o % (TB * 16), b = o / (TB * 16);
       const int u = blockIdx.x * RB + b;
       if (u >= units || tok >= n) continue;
-      const float rs = 1.0f / sqrtf(a.ss_in[tok * SK_SS_STRIDE] / (float)K + a.eps);
+      const float rs = s_scale[tok];
       float lo[8], hi[8];
       sum8(b, tok, 0, lo);
       sum8(b, tok, 1, hi);
@@ -302,6 +343,7 @@ template <int MODE, int TB>
 __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(SkinnyArgs a) {
   static_assert(MODE != SK_RES, "wide projections only");
   __shared__ __attribute__((aligned(16))) float part[2][SK_WAVES * TB * 16 * SK_PSTRIDE];
+  __shared__ float s_scale[TB * 16];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 15, g = lane >> 4;
@@ -338,7 +380,10 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
 #pragma unroll
   for (int i = 0; i < SKP_KSTEPS; ++i) koff[i] = in[i] ? (s_begin + i) * 32 + g * 8 : 0;
 
-  // the weight stream starts first, the (cached) activations follow
+  // a few small loads for the tokens' norm factors, then the weight stream, then the (cached) activations
+  SkSsLoads sl;
+  sk_ss_issue<TB>(a.ss_in, a.ss_stride, a.ss_parts, tid, sl);
+  __builtin_amdgcn_sched_barrier(0);
   int u = blockIdx.x;
   h8 fa0[HALF], fa1[HALF];
   {
@@ -353,6 +398,8 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
 #pragma unroll
     for (int t = 0; t < TB; ++t)
       fb[i][t] = load_h8(a.X + (in[i] ? ((long)((s_begin + i) * TB + t) * 64 + lane) * 8 : a.zeros_off));
+  __builtin_amdgcn_sched_barrier(0);
+  sk_ss_finish<TB>(sl, K, a.eps, s_scale, tid);   // published by the first block's barrier
   __builtin_amdgcn_sched_barrier(0);
   int round = 0;
   for (; u < units; u += gridDim.x, ++round) {
@@ -394,7 +441,7 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
 
     if (wave == (round & (SK_WAVES - 1)) && lane < TB * 16 && lane < n) {
       const int tok = lane;
-      const float scale = 1.0f / sqrtf(a.ss_in[tok * SK_SS_STRIDE] / (float)K + a.eps);
+      const float scale = s_scale[tok];
       f4 s[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
       for (int w = 0; w < SK_WAVES; ++w) {
@@ -450,14 +497,14 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
 }
 
 // Layer-0 front end of the short-prompt path: X[r] = float(E[tokens[r]]) (zero for r >= n),
-// Xh = fp16 (x * gain) fragment-major, ss[r] = sum x^2; also clears the other sum buffer.
+// Xh = fp16 (x * gain) fragment-major, slot 0 of ss[r] = sum x^2 (the first projection adds one slot).
 // grid = 16 TB rows, one workgroup per row.
 __global__ __launch_bounds__(LL_WG) void pf_embed_norm_kernel(const half_t* __restrict__ emb,
                                                               const int* __restrict__ tokens,
                                                               const DevState* __restrict__ st,
                                                               const half_t* __restrict__ gain,
                                                               float* __restrict__ X, half_t* __restrict__ Xh,
-                                                              float* __restrict__ ss, float* __restrict__ ss_other,
+                                                              float* __restrict__ ss, int ss_stride,
                                                               int d, int tb) {
   __shared__ float red[LL_WG / 64];
   const int r = blockIdx.x, tid = threadIdx.x;
@@ -480,8 +527,5 @@ __global__ __launch_bounds__(LL_WG) void pf_embed_norm_kernel(const half_t* __re
   acc = wave_sum(acc);
   if ((tid & 63) == 0) red[tid >> 6] = acc;
   __syncthreads();
-  if (tid == 0) {
-    ss[r * SK_SS_STRIDE] = red[0] + red[1] + red[2] + red[3];
-    ss_other[r * SK_SS_STRIDE] = 0.f;
-  }
+  if (tid == 0) ss[(size_t)r * ss_stride] = red[0] + red[1] + red[2] + red[3];
 }

@@ -128,6 +128,22 @@ def test_32_slot_batch_on_the_tiny_model(torch_cuda, oracle32):
     print("32-slot batch worst rel-L2 %.2e" % worst)
 
 
+def test_batched_steps_are_bit_reproducible(torch_cuda):
+    """The batched step sums in a fixed order too: two identical batches give identical logits."""
+    cfg = wl.custom_cfg(1, 32, 128, 1024, 512, 64)
+    w = wl.weights_astype(wl.make_weights_numpy(cfg, seed=8), np.float16)
+    prompts = [wl.make_tokens(n, cfg["vocab"], seed=50 + n) for n in (3, 11, 20, 6, 15)]
+    runs = []
+    with _session(cfg, w) as s:
+        for rep in range(2):
+            s.ll_batch_open(8, 8, 60)
+            slots = [s.ll_batch_add(p)[0] for p in prompts]
+            toks = [s.ll_batch_step() for _ in range(5)]
+            runs.append((toks, [s.ll_batch_dbg_get_logits(b).tobytes() for b in slots]))
+            s.ll_batch_close()
+    assert runs[0] == runs[1]
+
+
 def test_stochastic_selection_per_slot(torch_cuda):
     """ll_set_sampling applies to the batch as well: every slot draws with its own index (tokens its
     sequence has produced), so a sequence that joins later starts its stream at index 1 while the

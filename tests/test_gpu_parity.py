@@ -165,6 +165,28 @@ def test_graph_replay_equals_eager_and_decode_n(torch_cuda):
     assert max_abs(m[1], e[1]) < 1e-4 and max_abs(g[1], e[1]) < 1e-4 and max_abs(g[1], g[3]) < 1e-4
 
 
+@pytest.mark.parametrize("n_prompt", [9, 27, 200])
+def test_runs_are_bit_reproducible(torch_cuda, n_prompt):
+    """No kernel on the path accumulates in arrival order (no floating-point atomics): the same
+    prompt gives the same bits, run after run and instance after instance; one 7B-shaped layer, so
+    that the short-prompt projections run with their full 256 workgroups."""
+    from paper_2604_23467_amd import binding
+    cfg = wl.llama7b_cfg(n_layers=1, vocab=512, max_seq=256)
+    w_t = wl.make_weights_torch(cfg, seed=5, device="cuda:0", emb_std=1.0)
+    prompt = wl.make_tokens(n_prompt, cfg["vocab"], seed=n_prompt)
+    runs = []
+    for inst in range(2):
+        with binding.Session(cfg, w_t) as s:
+            for rep in range(3):
+                s.ll_reset()
+                t1 = s.ll_prefill(prompt)
+                lp, hp = s.ll_dbg_get_logits(), s.ll_dbg_get_hidden()
+                toks = s.ll_decode_n(3).tolist()
+                runs.append((t1, toks, lp.tobytes(), hp.tobytes(), s.ll_dbg_get_logits().tobytes(),
+                             s.ll_dbg_get_kv(0, 0, n_prompt + 3).tobytes()))
+    assert all(r == runs[0] for r in runs[1:])
+
+
 @pytest.mark.parametrize("flags", [0, 1], ids=["graph", "eager"])
 @pytest.mark.parametrize("n_prompt,max_seq", [(600, 1200), (1025, 1200), (1052, 2000), (1112, 2000), (2124, 3500)])
 def test_chunked_prefill_of_long_prompts(torch_cuda, oracle32, n_prompt, max_seq, flags):
