@@ -128,6 +128,21 @@ int ll_init(const ll_config *cfg, const ll_weights *w, void *workspace, size_t w
  * ll_reset), else LL_E_STATE.  Blocks until the token is on the host. */
 int32_t ll_prefill(const int32_t *tokens, int32_t n);
 
+/* ll_prefill() for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc) and so cannot bring the prefill's share of a
+ * workspace: the same kernels, launched one by one, with everything a short prefill needs besides its
+ * inputs and outputs (activations, per-token partial sums, logits, selection candidates, the staged
+ * ids) in a static device array of the library (4 MiB, one copy per GPU, held until the process
+ * ends) instead of the workspace.  Same arguments, result, state change and errors as ll_prefill;
+ * the KV rows, the state block and the token go where ll_prefill puts them, so ll_decode_step()
+ * continues from either.  Limits, LL_E_CAPACITY beyond them: n <= 32 tokens, and a model whose
+ * short-prompt buffers fit the array (about 336 d_model + 64 ffn_hidden + 4 vocab bytes <= 4 MiB;
+ * the 7B shape takes 2.2 MiB); LL_E_BAD_CONFIG unless d_model % 16 == 0 and ffn_hidden % 8 == 0.
+ * Calls no hipMalloc / hipFree or other allocating routine.  Every call on a GPU shares that GPU's
+ * array, which keeps the last call's contents (the call clears what must start at zero): calls that
+ * overlap on one GPU race. */
+int32_t ll_prefill_static(const int32_t *tokens, int32_t n);
+
 /* One decoding step (Alg. 1 loop body): feeds the previous step's token at the
  * next position, appends its key/value rows, returns the next token (greedy by
  * default, see ll_set_sampling).

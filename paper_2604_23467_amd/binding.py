@@ -24,7 +24,7 @@ LL_MODE_PERSISTENT_GRAPH, LL_MODE_MULTIKERNEL_GRAPH, LL_MODE_EAGER, LL_MODE_PER_
 KERNEL_CLASSES = ("embed", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "sample")
 LAYER_KEYS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
 
-EXPORTS = ("ll_workspace_bytes", "ll_init", "ll_prefill", "ll_decode_step", "ll_decode_n", "ll_reset",
+EXPORTS = ("ll_workspace_bytes", "ll_init", "ll_prefill", "ll_prefill_static", "ll_decode_step", "ll_decode_n", "ll_reset",
            "ll_set_sampling", "ll_shutdown", "ll_max_prompt", "ll_position", "ll_decode_mode", "ll_last_error", "ll_dbg_get_logits",
            "ll_batch_pool_bytes", "ll_batch_open", "ll_batch_add", "ll_batch_step", "ll_batch_remove", "ll_batch_close",
            "ll_batch_dbg_get_logits", "ll_batch_dbg_force_next_token", "ll_batch_dbg_time_steps",
@@ -71,6 +71,8 @@ def load():
     L.ll_init.argtypes = [C.POINTER(LLConfig), C.POINTER(LLWeights), C.c_void_p, C.c_size_t, C.c_void_p]
     L.ll_prefill.restype = C.c_int32
     L.ll_prefill.argtypes = [C.POINTER(C.c_int32), C.c_int32]
+    L.ll_prefill_static.restype = C.c_int32
+    L.ll_prefill_static.argtypes = [C.POINTER(C.c_int32), C.c_int32]
     L.ll_decode_step.restype = C.c_int32
     L.ll_decode_step.argtypes = []
     L.ll_decode_n.restype = C.c_int32
@@ -226,6 +228,10 @@ class Session:
     def ll_prefill(self, tokens):
         arr = np.ascontiguousarray(tokens, dtype=np.int32)
         return _check(self.lib.ll_prefill(arr.ctypes.data_as(C.POINTER(C.c_int32)), arr.shape[0]))
+
+    def ll_prefill_static(self, tokens):
+        arr = np.ascontiguousarray(tokens, dtype=np.int32)
+        return _check(self.lib.ll_prefill_static(arr.ctypes.data_as(C.POINTER(C.c_int32)), arr.shape[0]))
 
     def ll_decode_step(self):
         return _check(self.lib.ll_decode_step())

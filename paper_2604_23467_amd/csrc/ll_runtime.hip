@@ -22,6 +22,14 @@
 #include "prefill_gemm.h"
 #include "batch_kernels.h"
 
+// Scratch of ll_prefill_static(): the buffers a short prefill needs besides its inputs and outputs
+// (activations, per-token partial sums, logits, selection candidates, the staged prompt ids), for
+// callers that cannot bring device memory of their own for them.  One copy per GPU the library runs
+// on, held until the process ends.  In host code this name is a stand-in, not a device address: the
+// address on the current device comes from hipGetSymbolAddress (static_scratch_ptr below).
+#define LL_STATIC_SCRATCH_BYTES (4u << 20)
+static __device__ __align__(256) unsigned char scratch[LL_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local std::string g_err;
@@ -207,6 +215,45 @@ struct PfBuffers {
   half_t* zeros;     // 256 bytes of zeros
 };
 
+// Device address of `scratch` on each GPU, looked up once per device with that device current
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch_ptr(int dev, void** out) {
+  if (dev < 0 || dev >= kMaxDevices) return fail(LL_E_HIP, "device ordinal %d out of range", dev);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    HIPCHK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || reinterpret_cast<uintptr_t>(p) % kAlign)
+      return fail(LL_E_HIP, "hipGetSymbolAddress(scratch) returned %p", p);
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return LL_OK;
+}
+
+// The buffers of a prefill of at most 32 rows, laid out from `base`; returns the bytes they take
+size_t carve_short_prefill(const ll_config& c, int lm_wgs, char* base, PfBuffers* out) {
+  const size_t d = c.d_model, F = c.ffn_hidden, M = 32;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return base + o; };
+  PfBuffers B{};
+  B.X = reinterpret_cast<float*>(take(M * d * 4));
+  B.Xn = reinterpret_cast<half_t*>(take(M * ((d + 31) / 32 * 32) * 2));
+  B.Q = reinterpret_cast<half_t*>(take(M * d * 2));
+  B.O = reinterpret_cast<half_t*>(take(M * ((d + 31) / 32 * 32) * 2));
+  B.H = reinterpret_cast<half_t*>(take(M * ((F + 31) / 32 * 32) * 2));
+  B.part = nullptr;                               // no GEMM slices: the short-prompt kernels sum inside a workgroup
+  B.ss = reinterpret_cast<float*>(take((size_t)2 * 32 * sk_ss_stride(c.d_model) * 4));
+  B.tokens = reinterpret_cast<int*>(take(M * 4));
+  B.logits = reinterpret_cast<float*>(take((size_t)c.vocab * 4));
+  B.amax_val = reinterpret_cast<float*>(take((size_t)lm_wgs * 4));
+  B.amax_idx = reinterpret_cast<int*>(take((size_t)lm_wgs * 4));
+  B.zeros = reinterpret_cast<half_t*>(take(256));
+  if (out) *out = B;
+  return off;
+}
+
 struct Batch;
 void destroy_batch(Batch* B);
 
@@ -218,6 +265,8 @@ struct Instance {
   ll_weights w;
   char* ws = nullptr;
   PfBuffers pf{};               // the workspace's set of these buffers
+  int device = 0;               // GPU the instance lives on
+  char* static_scratch = nullptr;   // that GPU's copy of the library's static scratch array
   const float* last_logits = nullptr;   // where the most recent step left its logits / residual rows
   const float* last_rows = nullptr;
   hipStream_t stream = nullptr;
@@ -923,6 +972,12 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
                     I->at<float>(L.logits), I->at<float>(L.amax_val), I->at<int>(L.amax_idx), I->at<half_t>(L.zeros)};
   I->last_logits = I->pf.logits;
   int rc = LL_OK;
+  {
+    void* sp = nullptr;
+    if (hipGetDevice(&I->device) != hipSuccess) { delete I; return fail(LL_E_HIP, "ll_init: hipGetDevice failed"); }
+    if ((rc = static_scratch_ptr(I->device, &sp)) != LL_OK) { delete I; return rc; }
+    I->static_scratch = static_cast<char*>(sp);
+  }
   auto bail = [&](int code) { destroy(I); return code; };
 
   if (hip_stream) {
@@ -1172,6 +1227,43 @@ int32_t ll_prefill(const int32_t* tokens, int32_t n) {
   I->last_was_prefill = true;
   I->last_logits = I->pf.logits;
   I->last_rows = I->pf.X;
+  return I->host_ring[0];
+}
+
+int32_t ll_prefill_static(const int32_t* tokens, int32_t n) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_prefill_static: not initialised");
+  Instance* I = g;
+  const int chk = prefill_check(I, "ll_prefill_static", tokens, n);
+  if (chk != LL_OK) return chk;
+  if (n > 32)
+    return fail(LL_E_CAPACITY, "ll_prefill_static: n = %d tokens, at most 32 fit the static scratch; use ll_prefill", n);
+  if (!I->skinny)
+    return fail(LL_E_BAD_CONFIG, "ll_prefill_static: needs d_model %% 16 == 0, head_dim %% 16 == 0 and ffn_hidden %% 8 == 0");
+  PfBuffers B{};
+  const size_t need = carve_short_prefill(I->cfg, I->L.lm_wgs, I->static_scratch, &B);
+  if (need > LL_STATIC_SCRATCH_BYTES)
+    return fail(LL_E_CAPACITY, "ll_prefill_static: this model needs %zu bytes of scratch, the static array holds %u; "
+                               "use ll_prefill", need, (unsigned)LL_STATIC_SCRATCH_BYTES);
+
+  // The array keeps what the last call left: the block of zeros that out-of-range operand loads are
+  // aimed at is cleared here; everything else is written by this call before it is read.
+  HIPCHK(hipMemsetAsync(B.zeros, 0, 256, I->stream));
+  DevState* hs = reinterpret_cast<DevState*>(I->host_stage);
+  int* htok = reinterpret_cast<int*>(reinterpret_cast<char*>(I->host_stage) + sizeof(DevState));
+  memset(hs, 0, sizeof(DevState));
+  hs->n_prompt = n;
+  memcpy(htok, tokens, (size_t)n * 4);
+  HIPCHK(hipMemcpyAsync(I->state(), hs, sizeof(DevState), hipMemcpyHostToDevice, I->stream));
+  HIPCHK(hipMemcpyAsync(B.tokens, htok, (size_t)n * 4, hipMemcpyHostToDevice, I->stream));
+  enqueue_prefill_skinny(I, I->stream, B, n <= 16 ? 16 : 32, true);     // launched kernel by kernel: no graph holds these addresses
+  HIPCHK(hipGetLastError());
+  HIPCHK(hipStreamSynchronize(I->stream));
+  I->last_chunk_rows = n;
+  I->pos = n;
+  I->steps = 1;
+  I->last_was_prefill = true;
+  I->last_logits = B.logits;
+  I->last_rows = B.X;
   return I->host_ring[0];
 }
 
