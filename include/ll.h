@@ -66,7 +66,7 @@ enum {
                               CU; ll_init fails with LL_E_BAD_CONFIG otherwise).  With neither
                               of the two flags the library picks the faster one it has measured
                               for the 7B shape, currently the multi-kernel graph. */
-  LL_FLAG_PER_LENGTH_GRAPHS = 8
+  LL_FLAG_PER_LENGTH_GRAPHS = 8,
                            /* the paper's own mechanism, kept as an ablation (Alg. 1, Sec. IV-A):
                               one decode graph PER KV LENGTH in a rolling buffer of 8 with
                               least-recently-used eviction; a miss captures before it replays,
@@ -74,6 +74,14 @@ enum {
                               a second stream while the current one replays.  Same kernels as
                               the multi-kernel graph (they read the length from device memory);
                               excludes LL_FLAG_EAGER and LL_FLAG_PERSISTENT. */
+  LL_FLAG_FUSED_ATTN_OPROJ = 16
+                           /* a measured experiment, off by default: decode attention and O projection of
+                              a layer in ONE launch, the projection's workgroups holding all of W_o in
+                              registers while they wait (bounded) for the attention workgroups' partials.
+                              It removes a kernel boundary per layer and comes out level with the two
+                              kernels (the hand-off through memory costs what the boundary cost).
+                              LL_E_BAD_CONFIG unless d_model <= 4096, max_seq <= 2048 and
+                              2 n_heads + d_model / 32 workgroups fit one per CU. */
 };
 
 /* what ll_decode_step() replays, see ll_decode_mode() */
@@ -269,8 +277,8 @@ int ll_dbg_get_kv(int32_t layer, int32_t which, int32_t n_pos, float *host_out);
 enum {
   LL_KC_EMBED = 0,
   LL_KC_QKV = 1,     /* RMSNorm + QKV GEMV + RoPE + KV write */
-  LL_KC_ATTN = 2,    /* split-K decode attention + combine */
-  LL_KC_OPROJ = 3,   /* O GEMV + residual */
+  LL_KC_ATTN = 2,    /* split-K decode attention + combine (+ the O projection where the two share a launch) */
+  LL_KC_OPROJ = 3,   /* O GEMV + residual (no launches of its own where it runs inside the attention launch) */
   LL_KC_GATEUP = 4,  /* RMSNorm + gate/up GEMV + SwiGLU */
   LL_KC_DOWN = 5,    /* down GEMV + residual */
   LL_KC_LMHEAD = 6,  /* final RMSNorm + LM-head GEMV + block argmax */
@@ -301,6 +309,13 @@ int ll_dbg_trace_decode(uint64_t *ticks_out, int32_t max_phases);
  * calibration kernel of known traffic for hardware counters; works with or
  * without an initialised instance. */
 int ll_dbg_stream_copy(void *dst, const void *src, size_t bytes);
+
+/* Read rate in GB/s of a read-only pass over `bytes` (a multiple of 16) at DEVICE pointer `src`
+ * (16-byte aligned) with the decode GEMVs' streaming loads, `reps` passes between one hipEvent pair;
+ * `sink` is a DEVICE buffer of at least 4 KiB that the kernel may write a word to.  The measured
+ * streaming ceiling of the chip at hand, reported next to the nominal peak; works with or without an
+ * initialised instance. */
+int ll_dbg_stream_read(const void *src, size_t bytes, int32_t reps, void *sink, float *gbps_out);
 
 /* Device time of `k` decode-step replays measured with one hipEvent pair on
  * the library's stream (milliseconds for all k steps), tokens discarded. */

@@ -20,6 +20,7 @@ LL_FLAG_EAGER = 1
 LL_FLAG_MULTIKERNEL = 2
 LL_FLAG_PERSISTENT = 4
 LL_FLAG_PER_LENGTH_GRAPHS = 8
+LL_FLAG_FUSED_ATTN_OPROJ = 16
 LL_MODE_PERSISTENT_GRAPH, LL_MODE_MULTIKERNEL_GRAPH, LL_MODE_EAGER, LL_MODE_PER_LENGTH_GRAPHS = 0, 1, 2, 3
 KERNEL_CLASSES = ("embed", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "sample")
 LAYER_KEYS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
@@ -29,7 +30,7 @@ EXPORTS = ("ll_workspace_bytes", "ll_init", "ll_prefill", "ll_prefill_static", "
            "ll_batch_pool_bytes", "ll_batch_open", "ll_batch_add", "ll_batch_step", "ll_batch_remove", "ll_batch_close",
            "ll_batch_dbg_get_logits", "ll_batch_dbg_force_next_token", "ll_batch_dbg_time_steps",
            "ll_dbg_get_hidden", "ll_dbg_graph_stats", "ll_dbg_gemm_plan", "ll_dbg_gemm_slice_count", "ll_dbg_force_next_token", "ll_dbg_get_kv", "ll_dbg_profile_decode",
-           "ll_dbg_time_decode", "ll_dbg_time_kernel_class", "ll_dbg_stream_copy", "ll_dbg_trace_decode")
+           "ll_dbg_time_decode", "ll_dbg_time_kernel_class", "ll_dbg_stream_copy", "ll_dbg_stream_read", "ll_dbg_trace_decode")
 
 
 class LLConfig(C.Structure):
@@ -127,6 +128,8 @@ def load():
     L.ll_dbg_trace_decode.argtypes = [C.POINTER(C.c_uint64), C.c_int32]
     L.ll_dbg_stream_copy.restype = C.c_int
     L.ll_dbg_stream_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
+    L.ll_dbg_stream_read.restype = C.c_int
+    L.ll_dbg_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.POINTER(C.c_float)]
     L.ll_dbg_time_decode.restype = C.c_int
     L.ll_dbg_time_decode.argtypes = [C.c_int32, C.POINTER(C.c_float)]
     _lib = L
@@ -156,6 +159,16 @@ def ll_dbg_stream_copy(dst, src):
     assert dst.numel() * dst.element_size() == nbytes
     return _check(load().ll_dbg_stream_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()),
                                             C.c_size_t(nbytes)))
+
+
+def ll_dbg_stream_read(src, reps=4):
+    """GB/s of a read-only streaming pass over one contiguous CUDA tensor."""
+    import torch
+    sink = torch.zeros(4096, dtype=torch.int32, device=src.device)
+    out = C.c_float(0.0)
+    _check(load().ll_dbg_stream_read(C.c_void_p(src.data_ptr()), C.c_size_t(src.numel() * src.element_size()),
+                                     reps, C.c_void_p(sink.data_ptr()), C.byref(out)))
+    return float(out.value)
 
 
 def ll_set_sampling_raw(temperature, top_k, top_p, seed):

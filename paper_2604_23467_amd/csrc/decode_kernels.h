@@ -501,6 +501,223 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict
   o[(size_t)h * HD + t] = A / L;
 }
 
+// Attention and O projection of one layer in ONE launch: x += W_o * attention(q, K, V).
+//
+// The two are the pair furthest below the HBM roofline as separate kernels (a launch each of ramp-up
+// and drain around 8-16 MB and 33.5 MB of traffic).  Here the first heads * S workgroups run the
+// split-K attention exactly as attn_decode_kernel does, while the remaining workgroups, one row pair
+// of W_o per wave, put ALL of W_o in flight at once (K <= 4096: 16 x 16-byte loads per lane and
+// row pair), so the weight stream of the projection runs underneath the attention.  The hand-off
+// is the one cross-workgroup dependency inside a launch on the default path: an attention workgroup
+// stores its partial (m, l, acc[HD]) with device-scope stores, drains its vector-memory counter and
+// then adds one to an arrival counter; one thread per projection workgroup polls that counter (bounded:
+// on a time-out it raises DevState::fault and the step reports token -1 instead of hanging), after
+// which the workgroup merges the partials into its LDS copy of o with device-scope loads and
+// finishes its 16 row pairs from registers.  The grid never exceeds one workgroup per CU (host
+// check), so every workgroup is resident and the attention workgroups, which wait for nobody, always
+// finish.  The last projection workgroup to pass the wait clears both counters for the next launch.
+#define ATTN_FUSED_MAX_SPLITS 2
+struct AttnOArgs {
+  const float* q;          // rotated query [d]
+  const half_t* kc;        // this layer's keys   [head][max_seq][HD]
+  const half_t* vc;        // this layer's values
+  const DevState* st;
+  float* part;             // [head][S][ATTN_PART_STRIDE(HD)] split-K partials
+  const half_t* wo;        // [d][d]
+  float* x;                // residual stream [d], updated in place
+  unsigned* sync;          // [0]: attention workgroups arrived; [32]: projection workgroups past the wait
+  int* fault;              // &DevState::fault
+  int d, n_heads, splits, max_seq;
+  int spin_limit;
+};
+
+template <int HD>
+__global__ __launch_bounds__(ATTN_THREADS) void attn_oproj_kernel(AttnOArgs a) {
+  constexpr int LPR = HD / 8, GPW = 64 / LPR, NW = ATTN_THREADS / 64, UK = 8;
+  constexpr int PS = ATTN_PART_STRIDE(HD);
+  extern __shared__ float lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n_attn = a.n_heads * a.splits;
+
+  if ((int)blockIdx.x < n_attn) {
+    // ---------------- attention workgroup (head h, split s): see attn_decode_kernel
+    float* s_m = lds;                  // [NW]
+    float* s_l = lds + NW;             // [NW]
+    float* s_acc = lds + 2 * NW;       // [NW][HD]
+    const int h = blockIdx.x / a.splits, s = blockIdx.x - h * a.splits, S = a.splits;
+    const int gi = lane / LPR, li = lane % LPR;
+    const int n_keys = a.st->pos + 1;
+    const float scale = 1.0f / sqrtf((float)HD);
+    float qv[8];
+    {
+      const f4 q0 = *reinterpret_cast<const f4*>(a.q + h * HD + li * 8);
+      const f4 q1 = *reinterpret_cast<const f4*>(a.q + h * HD + li * 8 + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { qv[e] = q0[e] * scale; qv[4 + e] = q1[e] * scale; }
+    }
+    const half_t* kh = a.kc + (size_t)h * a.max_seq * HD + li * 8;
+    const half_t* vh = a.vc + (size_t)h * a.max_seq * HD + li * 8;
+    float m = -INFINITY, l = 0.f, acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    const int stride = S * NW * GPW;
+    for (int base = (s * NW + wave) * GPW; base < n_keys; base += stride * UK) {
+      h8 kk[UK], vv[UK];
+#pragma unroll
+      for (int j = 0; j < UK; ++j) {
+        const int u = min(base + j * stride + gi, n_keys - 1);
+        kk[j] = load_h8(kh + (size_t)u * HD);
+        vv[j] = load_h8(vh + (size_t)u * HD);
+      }
+#pragma unroll
+      for (int j = 0; j < UK; ++j) {
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dot += qv[e] * (float)kk[j][e];
+        dot = group_sum<LPR>(dot);
+        if (base + j * stride + gi < n_keys) {
+          const float mn = fmaxf(m, dot);
+          const float corr = __expf(m - mn);
+          const float p = __expf(dot - mn);
+          l = l * corr + p;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[e] = acc[e] * corr + p * (float)vv[j][e];
+          m = mn;
+        }
+      }
+    }
+    {
+      float M = m;
+#pragma unroll
+      for (int off = LPR; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
+      const float w = (M > -INFINITY) ? __expf(m - M) : 0.f;
+      l *= w;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] *= w;
+#pragma unroll
+      for (int off = LPR; off < 64; off <<= 1) {
+        l += __shfl_xor(l, off);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += __shfl_xor(acc[e], off);
+      }
+      if (gi == 0) {
+        if (li == 0) { s_m[wave] = M; s_l[wave] = l; }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s_acc[wave * HD + li * 8 + e] = acc[e];
+      }
+    }
+    __syncthreads();
+    if (tid < HD) {
+      float M = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < NW; ++i) M = fmaxf(M, s_m[i]);
+      float L = 0.f, A = 0.f;
+      if (M > -INFINITY) {
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+          const float w = (s_m[i] > -INFINITY) ? __expf(s_m[i] - M) : 0.f;
+          L += s_l[i] * w;
+          A += s_acc[i * HD + tid] * w;
+        }
+      }
+      float* mypart = a.part + (size_t)blockIdx.x * PS;
+      if (tid == 0) { st_dev(mypart, M); st_dev(mypart + 1, L); }
+      st_dev(mypart + 4 + tid, A);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the partial is out before anyone is told
+    }
+    __syncthreads();
+    if (tid == 0) __hip_atomic_fetch_add(as_global(a.sync), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return;
+  }
+
+  // ---------------- projection workgroup: 16 row pairs of W_o, one per wave
+  const int K = a.d, P = a.d >> 1;
+  const int nch = (K + 511) >> 9;                      // <= 8 (host check)
+  const int p = ((int)blockIdx.x - n_attn) * NW + wave;
+  const bool valid = p < P;
+  const int rowA = 2 * min(p, P - 1), rowB = rowA + 1;
+  const half_t* pa = a.wo + (size_t)rowA * K;
+  const half_t* pb = a.wo + (size_t)rowB * K;
+  h8 wa[8], wb[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const int k = min(u * 512 + lane * 8, K - 8);
+    wa[u] = load_stream(pa + k);
+    wb[u] = load_stream(pb + k);
+  }
+  float pre0 = 0.f, pre1 = 0.f;
+  if (valid && lane == 0) { pre0 = *as_global(a.x + rowA); pre1 = *as_global(a.x + rowB); }
+
+  if (tid == 0) {
+    int spins = 0;
+    while (ld_dev_u(a.sync) < (unsigned)n_attn) {
+      __builtin_amdgcn_s_sleep(2);
+      if (++spins > a.spin_limit) { st_dev_i(a.fault, 1); break; }
+    }
+  }
+  __syncthreads();
+
+  // o = merge of the S partials of every head, staged lane-major for the dot products (chunk 8 stays zero)
+  for (int i = tid; i < 9 * 128; i += ATTN_THREADS) {
+    const int k = i * 4;
+    f4 t = {0.f, 0.f, 0.f, 0.f};
+    if (k < K) {
+      const int head = k / HD, dcol = k - head * HD;
+      const float* hb = a.part + (size_t)head * a.splits * PS;
+      float2 hd[ATTN_FUSED_MAX_SPLITS], v0[ATTN_FUSED_MAX_SPLITS], v1[ATTN_FUSED_MAX_SPLITS];
+#pragma unroll
+      for (int sp = 0; sp < ATTN_FUSED_MAX_SPLITS; ++sp) {          // all loads first: one round trip
+        hd[sp] = make_float2(-INFINITY, 0.f);
+        v0[sp] = v1[sp] = make_float2(0.f, 0.f);
+        if (sp < a.splits) {
+          hd[sp] = ld_dev2(hb + sp * PS);
+          v0[sp] = ld_dev2(hb + sp * PS + 4 + dcol);
+          v1[sp] = ld_dev2(hb + sp * PS + 6 + dcol);
+        }
+      }
+      float M = -INFINITY;
+#pragma unroll
+      for (int sp = 0; sp < ATTN_FUSED_MAX_SPLITS; ++sp) M = fmaxf(M, hd[sp].x);
+      float L = 0.f;
+#pragma unroll
+      for (int sp = 0; sp < ATTN_FUSED_MAX_SPLITS; ++sp) {
+        const float w = (hd[sp].x > -INFINITY) ? __expf(hd[sp].x - M) : 0.f;
+        L += hd[sp].y * w;
+        t[0] += v0[sp].x * w; t[1] += v0[sp].y * w; t[2] += v1[sp].x * w; t[3] += v1[sp].y * w;
+      }
+      const float rl = 1.0f / L;
+      t[0] *= rl; t[1] *= rl; t[2] *= rl; t[3] *= rl;
+    }
+    const int c = k >> 9, r = k & 511;
+    *reinterpret_cast<f4*>(lds + c * 512 + ((r >> 2) & 1) * 256 + (r >> 3) * 4) = t;
+  }
+  __syncthreads();
+
+  float accA = 0.f, accB = 0.f;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const int xc = u < nch ? u : 8;
+    const float* xp = lds + xc * 512 + lane * 4;
+    const f4 x0 = *reinterpret_cast<const f4*>(xp);
+    const f4 x1 = *reinterpret_cast<const f4*>(xp + 256);
+    accA = dot8(wa[u], x0, x1, accA);
+    accB = dot8(wb[u], x0, x1, accB);
+  }
+  accA = wave_sum(accA);
+  accB = wave_sum(accB);
+  if (valid && lane == 0) {
+    a.x[rowA] = pre0 + accA;
+    a.x[rowB] = pre1 + accB;
+  }
+  // every projection workgroup is past its wait when the last one gets here: clear the counters
+  if (tid == 0) {
+    const unsigned n_proj = gridDim.x - n_attn;
+    const unsigned t = __hip_atomic_fetch_add(as_global(a.sync + 32), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (t + 1u == n_proj) { st_dev_u(a.sync, 0u); st_dev_u(a.sync + 32, 0u); }
+  }
+}
+
 // Plain device-to-device copy with the same 16-byte streaming loads the GEMVs
 // use.  It exists to calibrate hardware traffic counters against a known byte
 // count; nothing on the decode path calls it.
@@ -509,4 +726,27 @@ __global__ __launch_bounds__(LL_WG) void stream_copy_kernel(const h8* __restrict
   const size_t stride = (size_t)gridDim.x * LL_WG;
   for (size_t i = (size_t)blockIdx.x * LL_WG + threadIdx.x; i < n16; i += stride)
     dst[i] = __builtin_nontemporal_load(src + i);
+}
+
+// Read-only pass over a buffer in the decode GEMVs' access shape: a wave takes 16 KB at a time (two
+// "rows" of 8 KB, 16 x 16-byte streaming loads in flight per lane, a wave's load covering 1 KB), waves
+// stride over the buffer.  Each workgroup may leave one word so that the loads cannot be dropped.  It
+// measures the HBM read rate a kernel of this shape reaches on the chip at hand (the ceiling the
+// decode step is compared with besides the nominal peak); nothing on the decode path calls it.
+__global__ __launch_bounds__(LL_WG) void stream_read_kernel(const h8* __restrict__ src, size_t n16,
+                                                            unsigned* __restrict__ sink) {
+  const int lane = threadIdx.x & 63;
+  const size_t gw = (size_t)blockIdx.x * (LL_WG / 64) + (threadIdx.x >> 6), GW = (size_t)gridDim.x * (LL_WG / 64);
+  const size_t nblk = n16 / 1024;                 // whole 16 KB blocks; a tail shorter than that is not read
+  unsigned acc = 0;
+  for (size_t b = gw; b < nblk; b += GW) {
+    const h8* p = src + b * 1024 + lane;
+    h8 v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = __builtin_nontemporal_load(as_global(p + u * 64));
+#pragma unroll
+    for (int u = 0; u < 16; ++u) acc ^= __builtin_bit_cast(unsigned, __builtin_shufflevector(v[u], v[u], 0, 1));
+  }
+  acc ^= __shfl_xor(acc, 32);
+  if (lane == 0 && acc == 0x9e3779b9u) sink[blockIdx.x] = acc;   // (practically never true: no store traffic)
 }

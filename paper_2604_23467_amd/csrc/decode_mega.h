@@ -74,38 +74,6 @@ struct MkPhase {
   int mode, npairs, K, nch, nseg, cps;   // nch chunks of 512 in K, split in nseg segments of cps chunks
 };
 
-__device__ __forceinline__ float ld_dev(const float* p) {
-  return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_dev(float* p, float v) {
-  __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_dev_i(int* p, int v) {
-  __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ int ld_dev_i(const int* p) {
-  return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_dev_h(half_t* p, float v) {
-  const half_t h = (half_t)v;
-  __hip_atomic_store(as_global(reinterpret_cast<unsigned short*>(p)), __builtin_bit_cast(unsigned short, h),
-                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float2 ld_dev2(const float* p) {
-  const unsigned long long u = __hip_atomic_load(as_global(reinterpret_cast<const unsigned long long*>(p)),
-                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return make_float2(__builtin_bit_cast(float, (unsigned)(u & 0xffffffffu)),
-                     __builtin_bit_cast(float, (unsigned)(u >> 32)));
-}
-struct U64x2 { unsigned long long v[2]; };
-__device__ __forceinline__ h8 ld_dev_h8(const half_t* p) {   // 16 bytes as two 8-byte device-scope loads
-  const LL_GLOBAL unsigned long long* q = as_global(reinterpret_cast<const unsigned long long*>(p));
-  U64x2 t;
-  t.v[0] = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  t.v[1] = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return __builtin_bit_cast(h8, t);
-}
-
 struct MkCtx {
   int tid, lane, wave, b, nb;
   unsigned epoch;      // barriers completed before this launch (all launches ever)

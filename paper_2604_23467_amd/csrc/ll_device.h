@@ -18,7 +18,8 @@ struct DevState {
   int32_t next_token;  // token the next decode step feeds
   int32_t n_prompt;    // prompt length of the prefill in flight
   int32_t steps;       // tokens produced since reset (index into the host ring)
-  int32_t pad[12];
+  int32_t fault;       // set by a kernel whose bounded wait for another workgroup ran out: the step reports token -1
+  int32_t pad[11];
 };
 
 #define LL_WAVE 64
@@ -65,6 +66,50 @@ __device__ __forceinline__ const LL_GLOBAL T* as_global(const T* p) {
 template <class T>
 __device__ __forceinline__ LL_GLOBAL T* as_global(T* p) {
   return (LL_GLOBAL T*)p;
+}
+
+// Device-scope accesses for data that one workgroup writes and another reads INSIDE one launch.
+// The 8 XCDs have private L2s: relaxed device-scope atomic stores go through to memory and
+// device-scope atomic loads do not stop at a stale line, so they are coherent across the L2s on
+// their own.  Ordering comes from completion: a producer drains its vector-memory counter before
+// it signals.  No release / acquire fences: a device-scope release writes back the whole L2.
+__device__ __forceinline__ float ld_dev(const float* p) {
+  return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(float* p, float v) {
+  __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev_i(int* p, int v) {
+  __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int ld_dev_i(const int* p) {
+  return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev_h(half_t* p, float v) {
+  const half_t h = (half_t)v;
+  __hip_atomic_store(as_global(reinterpret_cast<unsigned short*>(p)), __builtin_bit_cast(unsigned short, h),
+                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_dev2(const float* p) {
+  const unsigned long long u = __hip_atomic_load(as_global(reinterpret_cast<const unsigned long long*>(p)),
+                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__builtin_bit_cast(float, (unsigned)(u & 0xffffffffu)),
+                     __builtin_bit_cast(float, (unsigned)(u >> 32)));
+}
+struct U64x2 { unsigned long long v[2]; };
+__device__ __forceinline__ h8 ld_dev_h8(const half_t* p) {   // 16 bytes as two 8-byte device-scope loads
+  const LL_GLOBAL unsigned long long* q = as_global(reinterpret_cast<const unsigned long long*>(p));
+  U64x2 t;
+  t.v[0] = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  t.v[1] = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return __builtin_bit_cast(h8, t);
+}
+
+__device__ __forceinline__ unsigned ld_dev_u(const unsigned* p) {
+  return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev_u(unsigned* p, unsigned v) {
+  __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // 16-byte streaming load of weights that are read exactly once per step.

@@ -59,6 +59,7 @@ constexpr int kMaxPromptBucket = 1024;   // rows of the largest prefill graph; l
 constexpr int kGemmWantWgs = 256;
 constexpr int kGemmMinSlabs = 8;
 constexpr size_t kAlign = 256;
+constexpr size_t kAttnOLdsBytes = 9 * 512 * sizeof(float);   // staged o of the fused attention + O kernel (8 chunks + a zero chunk)
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
@@ -132,9 +133,9 @@ GemmPlan gemm_plan(int N, int K, int nmat, int Mb, int ldc) {
 }
 
 struct Layout {
-  size_t kv, rope, x, q, o, m, attn_part, attn_cnt, logits, amax_val, amax_idx, state, tokens;
+  size_t kv, rope, x, x_keep, q, o, m, attn_part, attn_cnt, logits, amax_val, amax_idx, state, tokens;
   size_t pf_x, pf_xn, pf_part, pf_q, pf_o, pf_h, pf_ss;
-  size_t mk_layers, mk_bar, mk_amax_val, mk_amax_idx, mk_trace, zeros, sample_cfg;
+  size_t mk_layers, mk_bar, mk_amax_val, mk_amax_idx, mk_trace, zeros, sample_cfg, ao_sync;
   size_t total;
   int attn_splits, lm_wgs, max_prompt, mb_max;
   size_t kv_layer_halves;   // halves per layer per K or V
@@ -162,6 +163,7 @@ Layout make_layout(const ll_config& c) {
   L.kv = take((size_t)c.n_layers * 2 * L.kv_layer_halves * 2);
   L.rope = take((size_t)c.max_seq * (c.head_dim / 2) * sizeof(float2));
   L.x = take(d * 4);
+  L.x_keep = take(d * 4);
   L.q = take(d * 4);
   L.o = take(d * 4);
   L.m = take(F * 4);
@@ -188,6 +190,7 @@ Layout make_layout(const ll_config& c) {
   L.pf_ss = take((size_t)2 * 32 * sk_ss_stride(c.d_model) * 4);
   L.zeros = take(256);
   L.sample_cfg = take(sizeof(SampleCfg));
+  L.ao_sync = take(64 * 4);                 // arrival counters of the fused attention + O kernel, a line apart
   L.mk_layers = take((size_t)c.n_layers * sizeof(MkLayer));
   L.mk_bar = take((size_t)MK_BAR_WORDS * 4);
   L.mk_amax_val = take(1024 * 4);   // one candidate per workgroup of the persistent kernel
@@ -291,6 +294,7 @@ struct Instance {
   std::vector<hipEvent_t>* prof_events = nullptr;
   std::vector<int>* prof_class = nullptr;
   bool use_mega = false;         // decode step = one persistent kernel
+  bool fused_attn = false;       // attention and O projection of a layer in one launch
   int mega_grid = 0;
   size_t mega_lds = 0;
   int mega_splits = 1;
@@ -372,7 +376,9 @@ void enqueue_head(Instance* I, hipStream_t s, const PfBuffers& B, const float* x
     ProfScope ps(I, s, LL_KC_SAMPLE);
     hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(SMP_THREADS), SMP_Z_WORDS * 4, s, B.amax_val,
                        B.amax_idx, I->L.lm_wgs, B.logits, c.vocab,
-                       I->at<SampleCfg>(I->L.sample_cfg), I->state(), I->dev_ring, I->ring_size, prefill);
+                       I->at<SampleCfg>(I->L.sample_cfg), I->state(), I->dev_ring, I->ring_size, prefill,
+                       (const half_t*)I->w.tok_emb, I->use_mega ? nullptr : I->at<float>(I->L.x),
+                       I->at<float>(I->L.x_keep), c.d_model);
   }
 }
 
@@ -383,7 +389,9 @@ void enqueue_decode_multi(Instance* I, hipStream_t s) {
   float* q = I->at<float>(I->L.q);
   float* o = I->at<float>(I->L.o);
   float* m = I->at<float>(I->L.m);
-  if (I->runs(LL_KC_EMBED)) {
+  // x already holds the embedding row of the token to feed: the selection kernel of the previous
+  // step (or of the prefill) gathered it, and ll_dbg_force_next_token refreshes it
+  if (I->use_mega && I->runs(LL_KC_EMBED)) {      // (the timing hooks of a persistent-kernel instance: its selection gathers nothing)
     ProfScope ps(I, s, LL_KC_EMBED);
     hipLaunchKernelGGL(embed_kernel, dim3((d + LL_WG * 8 - 1) / (LL_WG * 8)), dim3(LL_WG), 0, s,
                        (const half_t*)I->w.tok_emb, I->state(), x, d);
@@ -401,6 +409,23 @@ void enqueue_decode_multi(Instance* I, hipStream_t s) {
       a.head_dim = c.head_dim; a.max_seq = c.max_seq;
       launch_gemv<GM_QKV>(a, 3 * d / 2, 0, s);
     }
+    if (I->fused_attn) {
+      // attention + O projection in one launch (counted under the attention class by the timing hooks)
+      if (I->runs(LL_KC_ATTN)) {
+        ProfScope ps(I, s, LL_KC_ATTN);
+        AttnOArgs a{};
+        a.q = q; a.kc = I->kcache(l); a.vc = I->vcache(l); a.st = I->state();
+        a.part = I->at<float>(I->L.attn_part); a.wo = (const half_t*)W.wo; a.x = x;
+        a.sync = I->at<unsigned>(I->L.ao_sync); a.fault = &I->state()->fault;
+        a.d = d; a.n_heads = c.n_heads; a.splits = I->L.attn_splits; a.max_seq = c.max_seq;
+        a.spin_limit = 1 << 20;      // about a second, then the step reports an error instead of hanging
+        const int grid = c.n_heads * I->L.attn_splits + (d / 2 + ATTN_THREADS / 64 - 1) / (ATTN_THREADS / 64);
+        if (c.head_dim == 128)
+          hipLaunchKernelGGL(attn_oproj_kernel<128>, dim3(grid), dim3(ATTN_THREADS), kAttnOLdsBytes, s, a);
+        else
+          hipLaunchKernelGGL(attn_oproj_kernel<64>, dim3(grid), dim3(ATTN_THREADS), kAttnOLdsBytes, s, a);
+      }
+    } else {
     if (I->runs(LL_KC_ATTN)) {
       ProfScope ps(I, s, LL_KC_ATTN);
       dim3 grid(c.n_heads, I->L.attn_splits);
@@ -421,6 +446,7 @@ void enqueue_decode_multi(Instance* I, hipStream_t s) {
       if (I->L.attn_splits <= 2) a.attn_part = I->at<float>(I->L.attn_part);   // else o holds the merged heads
       a.attn_splits = I->L.attn_splits; a.head_dim = c.head_dim;
       launch_gemv<GM_ORES>(a, d / 2, 0, s);
+    }
     }
     if (I->runs(LL_KC_GATEUP)) {
       ProfScope ps(I, s, LL_KC_GATEUP);
@@ -956,9 +982,10 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
     return fail(LL_E_WORKSPACE, "ll_init: workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign)
     return fail(LL_E_WORKSPACE, "ll_init: workspace must be %zu-byte aligned", kAlign);
-  if (gemv_lds_bytes(cfg->ffn_hidden) > 64 * 1024 || gemv_lds_bytes(cfg->d_model) > 64 * 1024 ||
-      cfg->n_heads * 2 > 512)
-    return fail(LL_E_BAD_CONFIG, "ll_init: d_model / ffn_hidden too large for the LDS-staged GEMV");
+  if (gemv_lds_bytes(cfg->ffn_hidden) > 64 * 1024 || gemv_lds_bytes(cfg->d_model) > 64 * 1024)
+    return fail(LL_E_BAD_CONFIG, "ll_init: d_model / ffn_hidden too large for the LDS-staged GEMV (at most 12288)");
+  if (cfg->n_heads > 256)
+    return fail(LL_E_BAD_CONFIG, "ll_init: n_heads = %d, at most 256 (two attention workgroups per head)", cfg->n_heads);
 
   Instance* I = new Instance();
   I->cfg = *cfg;
@@ -1022,6 +1049,7 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipMemset(I->at<int>(L.tokens), 0, (size_t)L.mb_max * 4), "hipMemset(tokens)"))
     return bail(rc);
   if (!hip_or_bail(hipMemset(I->at<char>(L.zeros), 0, 256), "hipMemset(zeros)")) return bail(rc);
+  if (!hip_or_bail(hipMemset(I->at<char>(L.ao_sync), 0, 64 * 4), "hipMemset(sync)")) return bail(rc);
   if (!hip_or_bail(hipMemset(I->at<char>(L.sample_cfg), 0, sizeof(SampleCfg)), "hipMemset(sampling)"))
     return bail(rc);                                           // inv_temp = 0: greedy
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&sample_kernel),
@@ -1079,6 +1107,16 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
       g_num_cus = cus;
   }
   for (int b = I->skinny ? 16 : 64; b <= L.mb_max; b <<= 1) I->pf_buckets.push_back(b);
+  // Opt-in: attention and O projection in one launch.  It needs the whole of W_o in the registers of one
+  // round of workgroups (rows of at most 4096), at most two attention workgroups per head, and a CU
+  // for every workgroup of the launch (the projection's wait needs them all resident).
+  if (cfg->flags & LL_FLAG_FUSED_ATTN_OPROJ) {
+    const int wgs = cfg->n_heads * L.attn_splits + (cfg->d_model / 2 + ATTN_THREADS / 64 - 1) / (ATTN_THREADS / 64);
+    if (cfg->d_model > 4096 || L.attn_splits > ATTN_FUSED_MAX_SPLITS || wgs > g_num_cus)
+      return bail(fail(LL_E_BAD_CONFIG, "ll_init: LL_FLAG_FUSED_ATTN_OPROJ needs d_model <= 4096, max_seq <= 2048 and "
+                                        "2 * n_heads + d_model / 32 = %d workgroups <= %d CUs", wgs, g_num_cus));
+    I->fused_attn = true;
+  }
 
   // Warm-up: one eager pass of every kernel chain (loads the code objects, so
   // nothing is compiled or loaded inside a capture), on state that is reset
@@ -1126,6 +1164,7 @@ int ll_reset(void) {
   // also clears a barrier time-out left behind by a failed step
   HIPCHK(hipMemsetAsync(g->at<unsigned>(g->L.mk_bar), 0, (size_t)MK_BAR_WORDS * 4, g->stream));
   HIPCHK(hipMemsetAsync(g->at<unsigned>(g->L.attn_cnt), 0, (size_t)g->cfg.n_heads * 4, g->stream));
+  HIPCHK(hipMemsetAsync(g->at<char>(g->L.ao_sync), 0, 64 * 4, g->stream));
   HIPCHK(hipStreamSynchronize(g->stream));
   g->pos = 0;
   g->steps = 0;
@@ -1281,7 +1320,7 @@ int32_t ll_decode_n(int32_t k, int32_t* out_tokens) {
   HIPCHK(hipStreamSynchronize(I->stream));
   for (int i = 0; i < k; ++i)
     if (I->host_ring[I->steps + i] < 0)
-      return fail(LL_E_HIP, "ll_decode: the persistent kernel's grid barrier timed out (are other "
+      return fail(LL_E_HIP, "ll_decode: a bounded wait between workgroups of one launch ran out (are other "
                             "kernels occupying the GPU?); call ll_reset");
   if (out_tokens) memcpy(out_tokens, I->host_ring + I->steps, (size_t)k * 4);
   I->pos += k;
@@ -1557,17 +1596,18 @@ int ll_batch_dbg_time_steps(int32_t k, float* ms_out) {
   }
   hipEvent_t e0, e1;
   HIPCHK(hipEventCreate(&e0));
-  HIPCHK(hipEventCreate(&e1));
-  HIPCHK(hipEventRecord(e0, I->stream));
-  for (int i = 0; i < k; ++i) {
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(LL_E_HIP, "ll_batch_dbg_time_steps: hipEventCreate"); }
+  hipError_t te = hipEventRecord(e0, I->stream);
+  for (int i = 0; i < k && te == hipSuccess; ++i) {
     if (eager(I)) enqueue_batch_step(I, I->stream);
-    else HIPCHK(hipGraphLaunch(B->exec, I->stream));
+    else te = hipGraphLaunch(B->exec, I->stream);
   }
-  HIPCHK(hipEventRecord(e1, I->stream));
-  HIPCHK(hipStreamSynchronize(I->stream));
-  HIPCHK(hipEventElapsedTime(ms_out, e0, e1));
+  if (te == hipSuccess) te = hipEventRecord(e1, I->stream);
+  if (te == hipSuccess) te = hipStreamSynchronize(I->stream);
+  if (te == hipSuccess) te = hipEventElapsedTime(ms_out, e0, e1);
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
+  if (te != hipSuccess) return fail(LL_E_HIP, "ll_batch_dbg_time_steps: %s", hipGetErrorString(te));
   for (int b = 0; b < B->max_batch; ++b)
     if (B->h_state->active[b]) { B->h_state->pos[b] += k; B->h_state->steps[b] += k; B->h_state->next_token[b] = B->h_out[b]; }
   return LL_OK;
@@ -1619,7 +1659,7 @@ int ll_dbg_get_hidden(float* host_out) {
   HIPCHK(hipStreamSynchronize(g->stream));
   const float* src = g->last_was_prefill
                          ? g->last_rows + (size_t)(g->last_chunk_rows - 1) * g->cfg.d_model
-                         : g->at<float>(g->L.x);
+                         : g->at<float>(g->use_mega ? g->L.x : g->L.x_keep);
   HIPCHK(hipMemcpy(host_out, src, (size_t)g->cfg.d_model * 4, hipMemcpyDeviceToHost));
   return LL_OK;
 }
@@ -1631,6 +1671,12 @@ int ll_dbg_force_next_token(int32_t tok) {
   int* h = g->host_stage;
   *h = tok;
   HIPCHK(hipMemcpyAsync(&g->state()->next_token, h, 4, hipMemcpyHostToDevice, g->stream));
+  if (!g->use_mega) {            // the step reads the token's embedding row from x, not the id
+    const int d = g->cfg.d_model;
+    hipLaunchKernelGGL(embed_kernel, dim3((d + LL_WG * 8 - 1) / (LL_WG * 8)), dim3(LL_WG), 0, g->stream,
+                       (const half_t*)g->w.tok_emb, g->state(), g->at<float>(g->L.x), d);
+    HIPCHK(hipGetLastError());
+  }
   HIPCHK(hipStreamSynchronize(g->stream));
   return LL_OK;
 }
@@ -1728,6 +1774,29 @@ int ll_dbg_stream_copy(void* dst, const void* src, size_t bytes) {
   return LL_OK;
 }
 
+int ll_dbg_stream_read(const void* src, size_t bytes, int32_t reps, void* sink, float* gbps_out) {
+  if (!src || !sink || !gbps_out || bytes == 0 || bytes % 16 || reps < 1 || reinterpret_cast<uintptr_t>(src) % 16)
+    return fail(LL_E_BAD_ARG, "ll_dbg_stream_read: bad argument");
+  hipStream_t s = g ? g->stream : nullptr;
+  const int grid = 256 * kGemvWgsPerCu;
+  hipEvent_t e0, e1;
+  HIPCHK(hipEventCreate(&e0));
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(LL_E_HIP, "ll_dbg_stream_read: hipEventCreate"); }
+  hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(LL_WG), 0, s, (const h8*)src, bytes / 16, (unsigned*)sink);   // untimed
+  (void)hipEventRecord(e0, s);
+  for (int r = 0; r < reps; ++r)
+    hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(LL_WG), 0, s, (const h8*)src, bytes / 16, (unsigned*)sink);
+  (void)hipEventRecord(e1, s);
+  hipError_t e = hipStreamSynchronize(s);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (e != hipSuccess) return fail(LL_E_HIP, "ll_dbg_stream_read: %s", hipGetErrorString(e));
+  *gbps_out = (float)((double)bytes * reps / (ms * 1e-3) / 1e9);
+  return LL_OK;
+}
+
 int ll_dbg_time_kernel_class(int32_t klass, int32_t reps, float* us_out) {
   if (!g) return fail(LL_E_NOT_INIT, "ll_dbg_time_kernel_class: not initialised");
   Instance* I = g;
@@ -1735,6 +1804,8 @@ int ll_dbg_time_kernel_class(int32_t klass, int32_t reps, float* us_out) {
     return fail(LL_E_BAD_ARG, "ll_dbg_time_kernel_class: bad argument");
   if (I->pos == 0) return fail(LL_E_STATE, "ll_dbg_time_kernel_class: empty context");
   if (I->pos >= I->cfg.max_seq) return fail(LL_E_CAPACITY, "ll_dbg_time_kernel_class: cache full");
+  if (klass == LL_KC_OPROJ && I->fused_attn)
+    return fail(LL_E_STATE, "ll_dbg_time_kernel_class: the O projection runs inside the attention launch in this instance");
   hipEvent_t e0, e1;
   HIPCHK(hipEventCreate(&e0));
   HIPCHK(hipEventCreate(&e1));

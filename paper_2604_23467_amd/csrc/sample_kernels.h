@@ -349,12 +349,18 @@ __device__ __forceinline__ int smp_draw_token(const float* __restrict__ logits, 
 
 //   prefill = 1: pos += n_prompt (rows of the last prompt chunk), steps := 1, ring[0] := token (draw index 0)
 //   prefill = 0: pos += 1, ring[steps] := token, steps += 1   (draw index = steps before the step)
+// It also gathers the selected token's embedding row into x_next (when given), the input of the next
+// decode step, which therefore needs no gather kernel of its own (what x_next held, the step's final
+// residual stream, is kept in x_keep for the read-back hook); and it reports token -1 to the host
+// when a kernel of the step raised DevState::fault (the device state still advances with a valid id).
 __global__ __launch_bounds__(SMP_THREADS) void sample_kernel(const float* __restrict__ pval,
                                                              const int* __restrict__ pidx, int nparts,
                                                              const float* __restrict__ logits, int vocab,
                                                              const SampleCfg* __restrict__ cfg,
                                                              DevState* st, int* host_ring, int ring_size,
-                                                             int prefill) {
+                                                             int prefill, const half_t* __restrict__ emb,
+                                                             float* __restrict__ x_next, float* __restrict__ x_keep,
+                                                             int d) {
   extern __shared__ float smp_z[];     // SMP_Z_WORDS words, used by the stochastic path only
   __shared__ float sv[SMP_THREADS];
   __shared__ int si[SMP_THREADS];
@@ -391,6 +397,21 @@ __global__ __launch_bounds__(SMP_THREADS) void sample_kernel(const float* __rest
     tok = smp_draw_token(logits, vocab, cfg, (uint32_t)(prefill ? 0 : st->steps), smp_z, si, sk, red, &found);
   }
 
+  if (tid == 0) found = tok;        // one value for every thread, whichever path chose it
+  __syncthreads();
+  tok = found;
+  if (x_next) {
+    for (int i = tid * 8; i < d; i += SMP_THREADS * 8) {
+      const h8 e = load_h8(emb + (size_t)tok * d + i);
+      if (!prefill) {
+        *reinterpret_cast<f4*>(x_keep + i) = *reinterpret_cast<const f4*>(x_next + i);
+        *reinterpret_cast<f4*>(x_keep + i + 4) = *reinterpret_cast<const f4*>(x_next + i + 4);
+      }
+      *reinterpret_cast<f4*>(x_next + i) = f4{(float)e[0], (float)e[1], (float)e[2], (float)e[3]};
+      *reinterpret_cast<f4*>(x_next + i + 4) = f4{(float)e[4], (float)e[5], (float)e[6], (float)e[7]};
+    }
+  }
+
   if (tid == 0) {
     int idx;
     if (prefill) {
@@ -403,6 +424,6 @@ __global__ __launch_bounds__(SMP_THREADS) void sample_kernel(const float* __rest
       st->steps = idx + 1;
     }
     st->next_token = tok;
-    if (idx < ring_size) host_ring[idx] = tok;
+    if (idx < ring_size) host_ring[idx] = st->fault ? -1 : tok;
   }
 }

@@ -26,7 +26,8 @@ def _session(cfg, w_np, flags=0):
 
 
 # ------------------------------------------------------------ config 1: tiny model
-@pytest.mark.parametrize("flags", [4, 2, 1, 0, 8], ids=["persistent", "multikernel", "eager", "default", "per-length-graphs"])
+@pytest.mark.parametrize("flags", [4, 2, 1, 0, 8, 16, 17],
+                         ids=["persistent", "multikernel", "eager", "default", "per-length-graphs", "fused-attn-oproj", "fused-eager"])
 def test_tiny_config_prefill_and_16_steps(torch_cuda, oracle32, flags):
     """2 layers, d=256, 4x64 heads, FFN 688, vocab 1024, fp32 weights seed 0,
     10-token prompt seed 0, prefill + 16 greedy steps.  The oracle keeps the
@@ -36,7 +37,7 @@ def test_tiny_config_prefill_and_16_steps(torch_cuda, oracle32, flags):
     prompt = wl.make_tokens(10, cfg["vocab"], seed=0)
     om = oracle32.model(cfg, w)
     with _session(cfg, w, flags) as s:
-        assert s.ll_decode_mode() == {4: 0, 2: 1, 1: 2, 0: DEFAULT_MODE, 8: 3}[flags]
+        assert s.ll_decode_mode() == {4: 0, 2: 1, 1: 2, 0: DEFAULT_MODE, 8: 3, 16: DEFAULT_MODE, 17: 2}[flags]
         stats = run_teacher_forced(s, om, prompt, 16, "tiny")
         assert s.ll_position() == 26 and om.pos == 26
         # the token comparison with the oracle must have been binding somewhere
@@ -77,7 +78,7 @@ SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("flags", [4, 2], ids=["persistent", "multikernel"])
+@pytest.mark.parametrize("flags", [4, 2, 18], ids=["persistent", "multikernel", "fused-attn-oproj"])
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "L%d_H%dx%d_F%d_V%d_S%d_p%d" % s[:7])
 def test_shapes_tails_and_buckets(torch_cuda, oracle32, shape, flags):
     n_layers, H, dh, F, V, max_seq, n_prompt, steps = shape
@@ -321,7 +322,7 @@ def test_one_7b_layer_decode_step(torch_cuda, oracle32, kv_len):
     om.close()
 
 
-@pytest.mark.parametrize("flags", [2, 4], ids=["multikernel", "persistent"])
+@pytest.mark.parametrize("flags", [2, 4, 18], ids=["multikernel", "persistent", "fused-attn-oproj"])
 def test_one_7b_layer_long_decode_to_kv_1000(torch_cuda, oracle32, flags):
     """Decode-path attention at the long end of the regime: prompt 500, then
     500 teacher-forced decode steps (KV grows to 1000) on one 7B-shaped layer;
@@ -486,12 +487,19 @@ def test_timing_hooks_leave_a_usable_context(torch_cuda, oracle32):
             assert s.ll_dbg_time_kernel_class(name, 2) > 0.0
         assert s.ll_position() == 10
         prof = s.ll_dbg_profile_decode(2)
-        assert prof["gateup"][1] == cfg["n_layers"] and s.ll_position() == 12
+        assert prof["gateup"][1] == cfg["n_layers"] and prof["oproj"][1] == cfg["n_layers"] and s.ll_position() == 12
         assert s.ll_dbg_time_decode(3) > 0.0 and s.ll_position() == 15
         s.ll_reset()                                   # required after the class timing hook
         run_teacher_forced(s, om, prompt, 3, "after-hooks")
     om.close()
     from paper_2604_23467_amd import binding
+    with _session(cfg, w, binding.LL_FLAG_FUSED_ATTN_OPROJ) as s:
+        s.ll_prefill(prompt)
+        assert s.ll_dbg_time_kernel_class("attn", 2) > 0.0
+        with pytest.raises(binding.LLError) as e:           # no launch of its own: it runs inside the attention launch
+            s.ll_dbg_time_kernel_class("oproj", 2)
+        assert e.value.code == binding.LL_E_STATE
+        assert s.ll_dbg_profile_decode(1)["oproj"][1] == 0
     with _session(cfg, w, binding.LL_FLAG_PERSISTENT) as s:
         s.ll_prefill(prompt)
         t = s.ll_dbg_trace_decode()
