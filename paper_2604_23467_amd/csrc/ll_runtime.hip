@@ -1793,7 +1793,7 @@ int ll_dbg_stream_read(const void* src, size_t bytes, int32_t reps, void* sink, 
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
   if (e != hipSuccess) return fail(LL_E_HIP, "ll_dbg_stream_read: %s", hipGetErrorString(e));
-  *gbps_out = (float)((double)bytes * reps / (ms * 1e-3) / 1e9);
+  *gbps_out = (float)((double)(bytes / 16384 * 16384) * reps / (ms * 1e-3) / 1e9);   // the kernel reads whole 16 KiB blocks
   return LL_OK;
 }
 
