@@ -116,15 +116,22 @@ typedef struct {
   const void *lm_head;                /* [vocab, d_model] */
 } ll_weights;
 
-/* Bytes of device workspace ll_init() needs for this shape (KV cache, RoPE
- * table, activations, split-K partials, logits, state block).  Pure function;
- * returns 0 for a configuration ll_init() would reject. */
+/* Bytes of device workspace ll_init() needs for this shape: the KV cache, the RoPE table, the
+ * state block and the ONE activation arena that every captured graph shares (the paper lets all
+ * of its graphs reuse one activation workspace, Sec. IV-B): activations, split-K partials, logits.
+ * Host arithmetic only (it asks the current device for its CU count, 256 without a device, because
+ * the prefill GEMM's slice buffer is sized for one round of workgroups); returns 0 for a
+ * configuration ll_init() would reject. */
 size_t ll_workspace_bytes(const ll_config *cfg);
 
-/* Binds weights, carves the workspace (256-byte aligned device pointer),
- * uploads the RoPE cos/sin table, warms every kernel up and captures the
- * decode graph and one prefill graph per prompt-length bucket on `hip_stream`
- * (a hipStream_t; NULL selects the default stream).  Context starts empty. */
+/* The initialisation step of Alg. 1 (streams created, graphs pre-captured; Sec. IV-A): binds the
+ * weights W, carves the workspace (256-byte aligned device pointer), uploads the RoPE cos/sin
+ * table, warms every kernel up and captures the decode graph (ONE for all lengths, where the paper
+ * pre-captures lengths 1-50) and one prefill graph per prompt-length bucket on `hip_stream`, a
+ * hipStream_t of default priority that every later call also runs on.  NULL makes the library
+ * create a private non-blocking stream of its own: work the caller queued on other streams (e.g.
+ * weight uploads) must then have completed before ll_init is called.  Launch shapes follow the
+ * device's CU count; the chip it is tuned for has 256 CUs in 8 XCDs.  Context starts empty. */
 int ll_init(const ll_config *cfg, const ll_weights *w, void *workspace, size_t workspace_bytes,
             void *hip_stream);
 
@@ -158,13 +165,15 @@ int32_t ll_prefill_static(const int32_t *tokens, int32_t n);
  * LL_E_CAPACITY once max_seq positions are cached. */
 int32_t ll_decode_step(void);
 
-/* k decoding steps enqueued back to back with ONE synchronisation at the end;
- * out_tokens (host, k entries, may be NULL) receives the generated ids.
- * Returns the last token. */
+/* k iterations of the decoding loop of Alg. 1 enqueued back to back with ONE synchronisation at
+ * the end (the loop needs no host round trip: position, KV length and token stay on the device);
+ * out_tokens (host, k entries, may be NULL) receives the generated ids.  Returns the last token.
+ * Same errors as ll_decode_step, checked for all k steps before anything runs. */
 int32_t ll_decode_n(int32_t k, int32_t *out_tokens);
 
-/* Empties the context (position 0, no cached keys); weights, graphs and the
- * workspace binding are kept. */
+/* Starts a new request (a new prompt P for the loop of Alg. 1, whose initialisation is not repeated):
+ * empties the context (position 0, no cached keys; the KV rows need no clearing because the length
+ * is what bounds attention); weights, graphs and the workspace binding are kept. */
 int ll_reset(void);
 
 /* Token selection of every following ll_prefill / ll_decode_step.  The paper keeps "token
@@ -183,7 +192,8 @@ int ll_reset(void);
  * persistent-kernel mode.  The setting survives ll_reset. */
 int ll_set_sampling(float temperature, int32_t top_k, float top_p, uint64_t seed);
 
-/* Destroys graphs and host buffers; caller memory is untouched. */
+/* The clean-up step of Alg. 1: waits for the stream, then destroys the graphs and the host
+ * buffers; caller memory is untouched. */
 int ll_shutdown(void);
 
 /* Longest prompt ll_prefill() accepts for the current instance: max_seq - 1.  Prompts of more
@@ -226,12 +236,14 @@ size_t ll_batch_pool_bytes(int32_t page_tokens, int32_t n_pages);
 int ll_batch_open(int32_t max_batch, int32_t page_tokens, int32_t n_pages, void *pool, size_t pool_bytes);
 /* Adds a sequence: prefills tokens[0..n) (host pointer), moves its cache rows into freshly taken
  * pages, stores the first generated token in *first_token and returns the slot (>= 0) the sequence
- * occupies.  LL_E_CAPACITY when no slot or not enough pages are free, or n + 1 > max_seq. */
+ * occupies.  LL_E_CAPACITY when no slot or not enough pages are free, or n + 1 > max_seq; those and
+ * the argument checks come first and leave everything as it was.  Past them the single-sequence
+ * context is replaced, whether or not the prefill then succeeds. */
 int32_t ll_batch_add(const int32_t *tokens, int32_t n, int32_t *first_token);
 /* One decode step of every sequence in the batch.  out_tokens (host, max_batch entries) receives
  * the new token of every occupied slot and -1 for free slots.  A sequence that crosses a page border
  * takes a page first: LL_E_CAPACITY (nothing ran) when the pool is exhausted or a sequence is at
- * max_seq - remove one and call again. */
+ * max_seq - remove one and call again.  The host's page lists change only after the step has run. */
 int ll_batch_step(int32_t *out_tokens);
 /* Ends the sequence in `slot` and returns its pages to the pool. */
 int ll_batch_remove(int32_t slot);

@@ -56,12 +56,27 @@ constexpr int kGemvU = 8;          // 512-element chunks of a weight row in flig
 constexpr int kGemvWgsPerCu = 4;   // measured best of 2/3/4 on the 7B shapes
 constexpr int kAttnMaxSplits = 16;
 constexpr int kMaxPromptBucket = 1024;   // rows of the largest prefill graph; longer prompts go through in chunks of it
-constexpr int kGemmWantWgs = 256;
 constexpr int kGemmMinSlabs = 8;
 constexpr size_t kAlign = 256;
 constexpr size_t kAttnOLdsBytes = 9 * 512 * sizeof(float);   // staged o of the fused attention + O kernel (8 chunks + a zero chunk)
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+// Compute units of the current device, the unit every launch shape is sized in (workgroups per CU for
+// the GEMVs, one round of workgroups for the prefill GEMM's plan, one workgroup per CU for the
+// persistent projections).  Queried once; 256, the MI355X's count, where no device can be asked (the
+// host-only plan hooks on a machine without a GPU).
+int g_num_cus = 0;
+int num_cus() {
+  if (g_num_cus > 0) return g_num_cus;
+  int dev = 0, cus = 0, ndev = 0;
+  if (hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0 && hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+    g_num_cus = cus;
+  else
+    g_num_cus = 256;
+  return g_num_cus;
+}
 
 bool config_ok(const ll_config* c, const char** why) {
   const char* w = nullptr;
@@ -102,6 +117,7 @@ struct GemmPlan {
 
 GemmPlan gemm_plan(int N, int K, int nmat, int Mb, int ldc) {
   GemmPlan p{};
+  const int kGemmWantWgs = num_cus();               // one round of workgroups
   p.mtiles = Mb / gemm_bm(Mb);
   p.map.nslabs = (K + 63) / 64;
   p.map.ntiles = (N + 255) / 256;
@@ -143,7 +159,7 @@ struct Layout {
 
 int gemv_grid(int pairs) {
   // a few workgroups per CU keep enough 16-byte loads in flight; never more waves than row pairs
-  const int want = 256 * kGemvWgsPerCu;
+  const int want = num_cus() * kGemvWgsPerCu;
   const int need = (pairs + (LL_WG / 64) - 1) / (LL_WG / 64);
   return need < want ? (need < 1 ? 1 : need) : want;
 }
@@ -562,7 +578,6 @@ SliceMap launch_gemm(Instance* I, hipStream_t s, const PfBuffers& B, const half_
   return p.map;
 }
 
-int g_num_cus = 256;
 
 template <int MODE>
 void launch_skinny(hipStream_t s, const PfBuffers& B, SkinnyArgs a, int Mb) {
@@ -1100,12 +1115,7 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipDeviceSynchronize(), "hipDeviceSynchronize")) return bail(rc);
 
   I->skinny = skinny_ok(*cfg);
-  {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
-      g_num_cus = cus;
-  }
+  (void)num_cus();
   for (int b = I->skinny ? 16 : 64; b <= L.mb_max; b <<= 1) I->pf_buckets.push_back(b);
   // Opt-in: attention and O projection in one launch.  It needs the whole of W_o in the registers of one
   // round of workgroups (rows of at most 4096), at most two attention workgroups per head, and a CU
@@ -1439,6 +1449,9 @@ int32_t ll_batch_add(const int32_t* tokens, int32_t n, int32_t* first_token) {
   if ((int)B->free_pages.size() < need)
     return fail(LL_E_CAPACITY, "ll_batch_add: %d pages needed, %zu free", need, B->free_pages.size());
 
+  for (int i = 0; i < n; ++i)                     // before anything is touched: ll_prefill's own check comes after the reset
+    if (tokens[i] < 0 || tokens[i] >= I->cfg.vocab)
+      return fail(LL_E_BAD_ARG, "ll_batch_add: tokens[%d] = %d outside [0, %d)", i, tokens[i], I->cfg.vocab);
   // the prompt runs through the single-sequence prefill (whose context it replaces) ...
   int rc = ll_reset();
   if (rc != LL_OK) return rc;
@@ -1504,16 +1517,19 @@ int ll_batch_step(int32_t* out_tokens) {
   if (!live) return fail(LL_E_STATE, "ll_batch_step: no sequence in the batch");
   if (fresh > (int)B->free_pages.size())
     return fail(LL_E_CAPACITY, "ll_batch_step: %d new pages needed, %zu free", fresh, B->free_pages.size());
+  // Pages are handed out on the device first (the new table entries travel by value in front of the
+  // step); the host's lists and pool follow only once the step has run, so a launch or
+  // synchronisation that fails leaves the bookkeeping as it was.
+  PageUpdates up{};                                // at most one new page per slot and step
+  int up_slot[BT_MAX_BATCH];
   if (fresh) {
-    PageUpdates up{};                              // at most one new page per slot and step
+    size_t next_free = B->free_pages.size();
     for (int b = 0; b < B->max_batch; ++b) {
       if (!B->h_state->active[b]) continue;
       const int i = B->h_state->pos[b] / B->page_tokens;
       if (i < (int)B->pages[b].size()) continue;
-      const int pg = B->free_pages.back();
-      B->free_pages.pop_back();
-      B->pages[b].push_back(pg);
-      B->h_table[b * B->L.pt_stride + i] = pg * B->page_tokens;
+      const int pg = B->free_pages[--next_free];
+      up_slot[up.n] = b;
       up.index[up.n] = b * B->L.pt_stride + i;
       up.row[up.n++] = pg * B->page_tokens;
     }
@@ -1527,6 +1543,11 @@ int ll_batch_step(int32_t* out_tokens) {
     HIPCHK(hipGraphLaunch(B->exec, I->stream));
   }
   HIPCHK(hipStreamSynchronize(I->stream));
+  for (int j = 0; j < up.n; ++j) {                 // the step ran: the pages are the slots' now
+    B->free_pages.pop_back();
+    B->pages[up_slot[j]].push_back(up.row[j] / B->page_tokens);
+    B->h_table[up.index[j]] = up.row[j];
+  }
   for (int b = 0; b < BT_MAX_BATCH; ++b) {
     const int t = b < B->max_batch ? B->h_out[b] : -1;
     if (b < B->max_batch) out_tokens[b] = t;
@@ -1767,7 +1788,7 @@ int ll_dbg_stream_copy(void* dst, const void* src, size_t bytes) {
       reinterpret_cast<uintptr_t>(src) % 16)
     return fail(LL_E_BAD_ARG, "ll_dbg_stream_copy: pointers and size must be 16-byte multiples");
   hipStream_t s = g ? g->stream : nullptr;
-  hipLaunchKernelGGL(stream_copy_kernel, dim3(256 * 8), dim3(LL_WG), 0, s, (const h8*)src, (h8*)dst,
+  hipLaunchKernelGGL(stream_copy_kernel, dim3(num_cus() * 8), dim3(LL_WG), 0, s, (const h8*)src, (h8*)dst,
                      bytes / 16);
   HIPCHK(hipGetLastError());
   HIPCHK(hipStreamSynchronize(s));
@@ -1778,7 +1799,7 @@ int ll_dbg_stream_read(const void* src, size_t bytes, int32_t reps, void* sink, 
   if (!src || !sink || !gbps_out || bytes == 0 || bytes % 16 || reps < 1 || reinterpret_cast<uintptr_t>(src) % 16)
     return fail(LL_E_BAD_ARG, "ll_dbg_stream_read: bad argument");
   hipStream_t s = g ? g->stream : nullptr;
-  const int grid = 256 * kGemvWgsPerCu;
+  const int grid = num_cus() * kGemvWgsPerCu;
   hipEvent_t e0, e1;
   HIPCHK(hipEventCreate(&e0));
   if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(LL_E_HIP, "ll_dbg_stream_read: hipEventCreate"); }
