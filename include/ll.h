@@ -322,6 +322,12 @@ int ll_dbg_trace_decode(uint64_t *ticks_out, int32_t max_phases);
  * without an initialised instance. */
 int ll_dbg_stream_copy(void *dst, const void *src, size_t bytes);
 
+/* Debug aid against stale reads: fills every workspace buffer that a step or a prefill is meant to
+ * write before it reads (activations, attention partials, logits, selection candidates, the prefill
+ * buffers and GEMM slices) with NaN bit patterns; the KV rows, the state and what else carries over
+ * between calls stay.  A following step must give the same result as without the call. */
+int ll_dbg_poison_scratch(void);
+
 /* Read rate in GB/s of a read-only pass over `bytes` (a multiple of 16) at DEVICE pointer `src`
  * (16-byte aligned) with the decode GEMVs' streaming loads, `reps` passes between one hipEvent pair;
  * `sink` is a DEVICE buffer of at least 4 KiB that the kernel may write a word to.  The measured

@@ -30,7 +30,7 @@ EXPORTS = ("ll_workspace_bytes", "ll_init", "ll_prefill", "ll_prefill_static", "
            "ll_batch_pool_bytes", "ll_batch_open", "ll_batch_add", "ll_batch_step", "ll_batch_remove", "ll_batch_close",
            "ll_batch_dbg_get_logits", "ll_batch_dbg_force_next_token", "ll_batch_dbg_time_steps",
            "ll_dbg_get_hidden", "ll_dbg_graph_stats", "ll_dbg_gemm_plan", "ll_dbg_gemm_slice_count", "ll_dbg_force_next_token", "ll_dbg_get_kv", "ll_dbg_profile_decode",
-           "ll_dbg_time_decode", "ll_dbg_time_kernel_class", "ll_dbg_stream_copy", "ll_dbg_stream_read", "ll_dbg_trace_decode")
+           "ll_dbg_time_decode", "ll_dbg_time_kernel_class", "ll_dbg_stream_copy", "ll_dbg_stream_read", "ll_dbg_poison_scratch", "ll_dbg_trace_decode")
 
 
 class LLConfig(C.Structure):
@@ -78,7 +78,7 @@ def load():
     L.ll_decode_step.argtypes = []
     L.ll_decode_n.restype = C.c_int32
     L.ll_decode_n.argtypes = [C.c_int32, C.POINTER(C.c_int32)]
-    for name in ("ll_reset", "ll_shutdown"):
+    for name in ("ll_reset", "ll_shutdown", "ll_dbg_poison_scratch"):
         getattr(L, name).restype = C.c_int
         getattr(L, name).argtypes = []
     for name in ("ll_max_prompt", "ll_position", "ll_decode_mode"):
@@ -347,6 +347,9 @@ class Session:
         out = np.empty(self.cfg["d_model"], dtype=np.float32)
         _check(self.lib.ll_dbg_get_hidden(out.ctypes.data_as(C.POINTER(C.c_float))))
         return out
+
+    def ll_dbg_poison_scratch(self):
+        return _check(self.lib.ll_dbg_poison_scratch())
 
     def ll_dbg_force_next_token(self, tok):
         return _check(self.lib.ll_dbg_force_next_token(int(tok)))

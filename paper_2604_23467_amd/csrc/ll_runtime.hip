@@ -1795,6 +1795,26 @@ int ll_dbg_stream_copy(void* dst, const void* src, size_t bytes) {
   return LL_OK;
 }
 
+int ll_dbg_poison_scratch(void) {
+  if (!g) return fail(LL_E_NOT_INIT, "ll_dbg_poison_scratch: not initialised");
+  Instance* I = g;
+  const Layout& L = I->L;
+  // every buffer a step or a prefill is meant to (re)write before it reads it; what carries state from
+  // call to call (KV rows, RoPE table, state block, the next step's input row x, sampling settings,
+  // barrier and arrival counters, the block of zeros) stays
+  const size_t regions[][2] = {
+      {L.x_keep, L.q}, {L.q, L.o}, {L.o, L.m}, {L.m, L.attn_part}, {L.attn_part, L.attn_cnt}, {L.logits, L.amax_val},
+      {L.amax_val, L.amax_idx}, {L.amax_idx, L.state}, {L.tokens, L.pf_x}, {L.pf_x, L.pf_xn}, {L.pf_xn, L.pf_q},
+      {L.pf_q, L.pf_o}, {L.pf_o, L.pf_part}, {L.pf_part, L.pf_h}, {L.pf_h, L.pf_ss}, {L.pf_ss, L.zeros}};
+  HIPCHK(hipStreamSynchronize(I->stream));
+  for (const auto& r : regions) {
+    if (r[1] <= r[0]) return fail(LL_E_STATE, "ll_dbg_poison_scratch: layout order changed");
+    HIPCHK(hipMemsetAsync(I->ws + r[0], 0xFF, r[1] - r[0], I->stream));      // all-ones bytes: NaN as fp16 and as fp32
+  }
+  HIPCHK(hipStreamSynchronize(I->stream));
+  return LL_OK;
+}
+
 int ll_dbg_stream_read(const void* src, size_t bytes, int32_t reps, void* sink, float* gbps_out) {
   if (!src || !sink || !gbps_out || bytes == 0 || bytes % 16 || reps < 1 || reinterpret_cast<uintptr_t>(src) % 16)
     return fail(LL_E_BAD_ARG, "ll_dbg_stream_read: bad argument");

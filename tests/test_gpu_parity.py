@@ -236,6 +236,28 @@ def test_per_length_graph_buffer_replays_the_same_tokens(torch_cuda):
         assert e.value.code == b.LL_E_BAD_CONFIG
 
 
+@pytest.mark.parametrize("flags", [0, 1, 4, 16], ids=["graph", "eager", "persistent", "fused-attn-oproj"])
+@pytest.mark.parametrize("n_prompt", [9, 70])
+def test_poisoned_scratch_changes_nothing(torch_cuda, flags, n_prompt):
+    """Every scratch buffer is written before it is read: with NaN patterns planted in all of them
+    before the prefill and between the decode steps, tokens and logits come out bit-identical."""
+    cfg = wl.custom_cfg(2, 4, 64, 688, 512, 128)
+    w = wl.weights_astype(wl.make_weights_numpy(cfg, seed=4, gain_jitter=0.1), np.float16)
+    prompt = wl.make_tokens(n_prompt, cfg["vocab"], seed=2)
+    with _session(cfg, w, flags) as s:
+        ref = [(s.ll_prefill(prompt), s.ll_dbg_get_logits())]
+        for _ in range(6):
+            ref.append((s.ll_decode_step(), s.ll_dbg_get_logits()))
+        s.ll_reset()
+        s.ll_dbg_poison_scratch()
+        got = [(s.ll_prefill(prompt), s.ll_dbg_get_logits())]
+        for _ in range(6):
+            s.ll_dbg_poison_scratch()
+            got.append((s.ll_decode_step(), s.ll_dbg_get_logits()))
+    for (t0, l0), (t1, l1) in zip(ref, got):
+        assert t0 == t1 and np.isfinite(l1).all() and np.array_equal(l0, l1)
+
+
 def test_prefill_matches_token_by_token_decode(torch_cuda, oracle32):
     """The MFMA prefill and the GEMV decode path are two implementations of the
     same layer: feeding the prompt through decode steps must give the same
