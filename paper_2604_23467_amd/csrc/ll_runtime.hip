@@ -572,9 +572,9 @@ SliceMap launch_gemm(Instance* I, hipStream_t s, const PfBuffers& B, const half_
   ga.mtiles = p.mtiles; ga.runs = p.runs; ga.map = p.map;
   dim3 grid((p.runs + 7) / 8 * 8 * p.mtiles);      // runs are dealt to the 8 XCDs
   if (gemm_bm(Mb) == 128)
-    hipLaunchKernelGGL((pf_gemm_kernel<128, 3, 2>), grid, dim3(PF_GEMM_THREADS * 2), PF_GEMM_LDS_BYTES(128, 3), s, ga);
+    hipLaunchKernelGGL((pf_gemm_kernel<128, 3, 2, 4, 64>), grid, dim3(PF_GEMM_THREADS_OF(2, 4)), PF_GEMM_LDS_BYTES(128, 3, 64), s, ga);
   else
-    hipLaunchKernelGGL((pf_gemm_kernel<64, 3, 1>), grid, dim3(PF_GEMM_THREADS), PF_GEMM_LDS_BYTES(64, 3), s, ga);
+    hipLaunchKernelGGL((pf_gemm_kernel<64, 3, 1, 4, 64>), grid, dim3(PF_GEMM_THREADS_OF(1, 4)), PF_GEMM_LDS_BYTES(64, 3, 64), s, ga);
   return p.map;
 }
 
@@ -1073,11 +1073,11 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&bt_select_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, SMP_Z_WORDS * 4),
                    "hipFuncSetAttribute(batch select)")) return bail(rc);
-  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128, 3, 2>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128, 3)),
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128, 3, 2, 4, 64>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128, 3, 64)),
                    "hipFuncSetAttribute(gemm 128)")) return bail(rc);
-  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<64, 3, 1>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(64, 3)),
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<64, 3, 1, 4, 64>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(64, 3, 64)),
                    "hipFuncSetAttribute(gemm 64)")) return bail(rc);
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_attn_kernel<128, 4>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, PF_ATTN_LDS_BYTES(128, 4)),

@@ -50,10 +50,9 @@ struct GemmArgs {
 };
 
 #define PF_BN 256
-#define PF_BK 64
-#define PF_GEMM_WAVES 4
-#define PF_GEMM_THREADS (PF_GEMM_WAVES * 64)
-#define PF_GEMM_LDS_BYTES(BM, NS) ((NS) * ((BM) + PF_BN) * PF_BK * 2)
+#define PF_SLAB 64            // K slabs as the host's plan counts them; a kernel may walk one in BK-wide halves
+#define PF_GEMM_LDS_BYTES(BM, NS, BK) ((NS) * ((BM) + PF_BN) * (BK) * 2)
+#define PF_GEMM_THREADS_OF(WM, WN) ((WM) * (WN) * 64)
 
 // s_waitcnt vmcnt(N) (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the export and LDS counters
 // left at "no wait")
@@ -62,20 +61,37 @@ __device__ __forceinline__ void wait_vm_at_most() {
   __builtin_amdgcn_s_waitcnt((N & 15) | 0x70 | 0xF00 | ((N >> 4) << 14));
 }
 
-template <int BM, int NS, int WM>
-__global__ __launch_bounds__(PF_GEMM_THREADS * WM, 1) void pf_gemm_kernel(GemmArgs g) {
-  constexpr int NWAVES = PF_GEMM_WAVES * WM;           // WM waves along M, 4 along N
+// BM x 256 tile, WM x WN waves of (BM / WM) x (256 / WN) each, NS ring stages of BK-wide slabs.
+//   <128, 3, 2, 4, 64>  8 waves of 64 x 64: prompts of 65..255 rows
+//   <64, 3, 1, 4, 64>   4 waves of 64 x 64: prompts of at most 64 rows
+// Measured and not instantiated: <256, 4 or 5, 2, 2, 32>, four waves of 128 x 128 (one per SIMD, 256
+// accumulator registers) on 32-wide slabs so that four or five stages fit the LDS.  A wave's k-step
+// then reads 4 + 4 fragments from LDS for 16 matrix instructions instead of 2 + 2 for 4, and the tile
+// takes a third less from L2 per flop; at 500 tokens Q/K/V, O, gate/up, down ran in 68.9 / 30.8 /
+// 107.1 / 58.7 us (five stages; 73.6 / 31.6 / 111.3 / 61.5 with four) against 71 / 29 / 116 / 60 for
+// the 128 x 256 tile, the consumers of the then more numerous slices took 11 us per layer longer, and
+// at 250 tokens the prefill was 0.4 ms slower: neither LDS reads (SQ_WAIT_INST_LDS under 1 % of the
+// wave cycles) nor bytes in flight (+33 % with the fifth stage bought 4-6 %) are what holds these
+// GEMMs at 35-40 % of the matrix cores' time.  Two workgroups per CU (<128, 3, 2, 2, 32, 2>: four waves
+// of 64 x 128 each, the plan dealing two rounds' worth of runs) lost outright: 82 / 32 / 123 / 67 us.
+template <int BM, int NS, int WM, int WN, int BK, int OCC = 1>
+__global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kernel(GemmArgs g) {
+  constexpr int NWAVES = WM * WN;
   constexpr int MT = BM / WM / 32;                     // 32-row accumulators per wave
-  constexpr int NT = 2;                                // 32-column accumulators per wave
-  constexpr int A_LD = BM / 8 / NWAVES;                // 1 KB direct loads per wave and slab (8 rows each)
-  constexpr int W_LD = PF_BN / 8 / NWAVES;
+  constexpr int NT = PF_BN / WN / 32;                  // 32-column accumulators per wave
+  constexpr int SUB = PF_SLAB / BK;                    // ring slabs per plan slab
+  constexpr int CPR = BK / 8;                          // 16-byte chunks per LDS row
+  constexpr int RPL = 64 / CPR;                        // rows one 1 KB direct load covers
+  constexpr int A_LD = BM / RPL / NWAVES;              // direct loads per wave and ring slab
+  constexpr int W_LD = PF_BN / RPL / NWAVES;
   constexpr int PER_SLAB = A_LD + W_LD;
-  constexpr int STAGE_HALVES = (BM + PF_BN) * PF_BK;
-  static_assert(PER_SLAB * (NS - 1) < 64, "vmcnt is a 6-bit counter");
+  constexpr int STAGE_HALVES = (BM + PF_BN) * BK;
+  static_assert(BK == 64 || BK == 32, "swizzles below are for 128- and 64-byte rows");
+  static_assert(A_LD >= 1 && W_LD >= 1 && PER_SLAB * (NS - 1) < 64, "vmcnt is a 6-bit counter");
   extern __shared__ __attribute__((aligned(16))) half_t pf_lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave / PF_GEMM_WAVES, wn = wave % PF_GEMM_WAVES;
+  const int wm = wave / WN, wn = wave % WN;
 
   // slot t of XCD x: run (t / mtiles) * 8 + x of the slab sequence, M tile t % mtiles
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -83,9 +99,13 @@ __global__ __launch_bounds__(PF_GEMM_THREADS * WM, 1) void pf_gemm_kernel(GemmAr
   const int m0 = (slot % g.mtiles) * BM;
   if (run >= g.runs || m0 >= g.st->n_prompt) return;
   const int K = g.K, S = g.map.nslabs;                  // S may be padded beyond the K loop's real slabs ...
-  const int s_real = (K + PF_BK - 1) / PF_BK;           // ... so that runs end where tiles end
+  const int s_real = (K + PF_SLAB - 1) / PF_SLAB;       // ... so that runs end where tiles end
   const int total_units = g.map.ntiles * g.nmat * S;
   const int r = lane & 31, half = lane >> 5;
+  // LDS rows are unpadded; 16-byte chunk c of row r sits at chunk position c ^ swz(r), which spreads
+  // the 8 lanes the LDS serves per clock over all of its banks (128-byte rows: 8 rows x 8 chunk
+  // positions; 64-byte rows: rows of equal parity share a bank range, 4 of them x 4 positions)
+  auto swz = [](int row) { return BK == 64 ? (row & 7) : ((row >> 1) & 3); };
   int u = run * g.map.quota;
   const int u_end = min(u + g.map.quota, total_units);
   while (u < u_end) {
@@ -97,40 +117,43 @@ __global__ __launch_bounds__(PF_GEMM_THREADS * WM, 1) void pf_gemm_kernel(GemmAr
   const int slice = run - (nt_all * S) / g.map.quota;
   const int z = nt_all / g.map.ntiles, n0 = (nt_all - z * g.map.ntiles) * PF_BN;
 
-  // this lane's piece of every 8-row group: row (lane / 8), physical chunk (lane % 8),
-  // which holds logical chunk (lane % 8) ^ (row & 7) = (lane % 8) ^ (lane / 8)
-  const int lrow = lane >> 3, lchunk = (lane & 7) ^ lrow;
+  // this lane's piece of every group of RPL rows: row (lane / CPR), physical chunk (lane % CPR),
+  // which holds logical chunk (lane % CPR) ^ swz(row)
+  const int lrow = lane / CPR, lchunk = (lane % CPR) ^ swz(lrow);
   const half_t* arow[A_LD];
   const half_t* wrow[W_LD];
 #pragma unroll
   for (int i = 0; i < A_LD; ++i)
-    arow[i] = g.A + (size_t)(m0 + (wave * A_LD + i) * 8 + lrow) * K + lchunk * 8;
+    arow[i] = g.A + (size_t)(m0 + (wave * A_LD + i) * RPL + lrow) * K + lchunk * 8;
 #pragma unroll
   for (int i = 0; i < W_LD; ++i) {
-    const int n = n0 + (wave * W_LD + i) * 8 + lrow;
+    const int n = n0 + (wave * W_LD + i) * RPL + lrow;
     wrow[i] = (n < g.N) ? g.W[z] + (size_t)n * K + lchunk * 8 : nullptr;
   }
   // Every workgroup walks its K range from a different starting slab (and wraps around): all
   // tiles reading the same 128-byte column of their weight rows at the same time would keep
   // hitting the same few memory channels, since the rows lie a multiple of 2 K bytes apart.
   const int rot = (nt_all * 7) % cnt;
+  const int iters = cnt * SUB;
   auto issue = [&](int it, int stage) {
     half_t* sa = pf_lds + stage * STAGE_HALVES;
-    half_t* sw = sa + BM * PF_BK;
-    const int sl = sl0 + (it + rot < cnt ? it + rot : it + rot - cnt);
-    const bool kin = it < cnt && sl * PF_BK + lchunk * 8 < K;   // K % 8 == 0: a chunk is all in or all out
+    half_t* sw = sa + BM * BK;
+    const int ps = it / SUB, sub = it - ps * SUB;         // plan slab (rotated below) and the BK-wide part of it
+    const int sl = sl0 + (ps + rot < cnt ? ps + rot : ps + rot - cnt);
+    const int k0 = sl * PF_SLAB + sub * BK;
+    const bool kin = it < iters && k0 + lchunk * 8 < K;   // K % 8 == 0: a chunk is all in or all out
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
-      const half_t* src = kin ? arow[i] + sl * PF_BK : g.zeros;
+      const half_t* src = kin ? arow[i] + k0 : g.zeros;
       __builtin_amdgcn_global_load_lds((const LL_GLOBAL void*)src,
-                                       (__attribute__((address_space(3))) void*)(sa + (wave * A_LD + i) * 8 * PF_BK),
+                                       (__attribute__((address_space(3))) void*)(sa + (wave * A_LD + i) * RPL * BK),
                                        16, 0, 0);
     }
 #pragma unroll
     for (int i = 0; i < W_LD; ++i) {
-      const half_t* src = (kin && wrow[i]) ? wrow[i] + sl * PF_BK : g.zeros;
+      const half_t* src = (kin && wrow[i]) ? wrow[i] + k0 : g.zeros;
       __builtin_amdgcn_global_load_lds((const LL_GLOBAL void*)src,
-                                       (__attribute__((address_space(3))) void*)(sw + (wave * W_LD + i) * 8 * PF_BK),
+                                       (__attribute__((address_space(3))) void*)(sw + (wave * W_LD + i) * RPL * BK),
                                        16, 0, 0);
     }
   };
@@ -147,31 +170,31 @@ __global__ __launch_bounds__(PF_GEMM_THREADS * WM, 1) void pf_gemm_kernel(GemmAr
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s) issue(s, s);
 
-  for (int it = 0; it < cnt; ++it) {
+  for (int it = 0; it < iters; ++it) {
     const int stage = it % NS;
-    // this wave's pieces of slab sl have landed (younger slabs may still be in flight) ...
+    // this wave's pieces of the slab have landed (younger slabs may still be in flight) ...
     wait_vm_at_most<PER_SLAB * (NS - 2)>();
-    // ... and so have everybody else's; everybody is also done reading the stage of slab sl - 1.
+    // ... and so have everybody else's; everybody is also done reading the stage of the slab before.
     // A bare s_barrier: __syncthreads() carries a fence that would drain ALL loads in flight.
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     issue(it + NS - 1, (stage + NS - 1) % NS);
-    const half_t* sa = pf_lds + stage * STAGE_HALVES + (wm * (BM / WM) + r) * PF_BK;
-    const half_t* sw = pf_lds + stage * STAGE_HALVES + (BM + wn * 64 + r) * PF_BK;
+    const half_t* sa = pf_lds + stage * STAGE_HALVES + (wm * (BM / WM) + r) * BK;
+    const half_t* sw = pf_lds + stage * STAGE_HALVES + (BM + wn * (PF_BN / WN) + r) * BK;
     // fragments of k-step ks + 1 are read from LDS while the matrix cores work on k-step ks
     auto load_frags = [&](int ks, h8 (&fa)[MT], h8 (&fb)[NT]) {
-      const int pc = ((ks * 2 + half) ^ (r & 7)) * 8;   // all fragment rows start at multiples of 8
+      const int pc = ((ks * 2 + half) ^ swz(r)) * 8;    // all fragment rows start at multiples of 32
 #pragma unroll
-      for (int i = 0; i < MT; ++i) fa[i] = *reinterpret_cast<const h8*>(sa + i * 32 * PF_BK + pc);
+      for (int i = 0; i < MT; ++i) fa[i] = *reinterpret_cast<const h8*>(sa + i * 32 * BK + pc);
 #pragma unroll
-      for (int j = 0; j < NT; ++j) fb[j] = *reinterpret_cast<const h8*>(sw + j * 32 * PF_BK + pc);
+      for (int j = 0; j < NT; ++j) fb[j] = *reinterpret_cast<const h8*>(sw + j * 32 * BK + pc);
     };
     h8 fa[2][MT], fb[2][NT];
     load_frags(0, fa[0], fb[0]);
 #pragma unroll
-    for (int ks = 0; ks < PF_BK / 16; ++ks) {
-      if (ks + 1 < PF_BK / 16) load_frags(ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      if (ks + 1 < BK / 16) load_frags(ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
 #pragma unroll
       for (int j = 0; j < NT; ++j)
 #pragma unroll
@@ -185,7 +208,7 @@ __global__ __launch_bounds__(PF_GEMM_THREADS * WM, 1) void pf_gemm_kernel(GemmAr
   // rows 8*(e/4) + 4*(lane/32) + e%4 for e = 0..15
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
-    const int col = n0 + wn * 64 + j * 32 + r;
+    const int col = n0 + wn * (PF_BN / WN) + j * 32 + r;
     if (col >= g.N) continue;
     float* cbase = g.C + slice * g.map.slice_floats + (size_t)z * g.N + col +
                    (size_t)(m0 + wm * (BM / WM) + 4 * half) * g.ldc;

@@ -80,7 +80,7 @@ int main() {
         for (int K : {8, 64, 136, 256, 384, 1000, 4096, 8712, 11008, 28672}) {
           CHECK(ll_dbg_gemm_plan(N, K, nmat, rows, p) == LL_OK);
           const int row_tile = p[0], row_tiles = p[1], runs = p[2], quota = p[3], tile_slabs = p[4], max_slices = p[5];
-          CHECK((row_tile == 64 || row_tile == 128) && row_tile * row_tiles == rows && runs >= 1 && quota >= 1);
+          CHECK((row_tile == 64 || row_tile == 128 || row_tile == 256) && row_tile * row_tiles == rows && runs >= 1 && quota >= 1);
           const int slabs = (K + 63) / 64, tiles = (N + 255) / 256 * nmat;
           CHECK(tile_slabs >= slabs && max_slices >= 1);
           CHECK((long)runs * quota >= (long)tiles * tile_slabs);        // the runs reach the end of the last tile
