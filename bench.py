@@ -186,6 +186,10 @@ def main():
     ap.add_argument("--launch-gaps", choices=("7b-graph", "7b-eager", "tiny-graph", "tiny-eager"), default=None,
                     help="workload for `rocprofv3 --kernel-trace`: a prefill, then --steps decode steps issued as "
                          "graph replays or as eager launches, on the 7B shape or on the tiny model; nothing else runs")
+    ap.add_argument("--decode-variants", action="store_true",
+                    help="workload for `rocprofv3 --kernel-trace --stats`: prefill(--prompt) + --steps decode steps in each "
+                         "of the measured arrangements of a step (two kernels for attention and O projection, the "
+                         "fused launch, the single persistent kernel); prints device ms per step of each")
     ap.add_argument("--gap-stats", metavar="KERNEL_TRACE_CSV", default=None,
                     help="no GPU work: launch-gap statistics of the decode steps in a kernel-trace CSV of a "
                          "--launch-gaps run (JSON on stdout)")
@@ -264,6 +268,20 @@ def main():
     w_t = wl.make_weights_torch(cfg, seed=0, device="cuda:0")
     torch.cuda.synchronize()
     prompt = wl.make_tokens(n_prompt, cfg["vocab"], seed=0)
+
+    if args.decode_variants:
+        out = {}
+        for name, fl in (("default: attention and O projection as two kernels", 0),
+                         ("LL_FLAG_FUSED_ATTN_OPROJ: one launch for both", binding.LL_FLAG_FUSED_ATTN_OPROJ),
+                         ("LL_FLAG_PERSISTENT: the whole step as one kernel", binding.LL_FLAG_PERSISTENT)):
+            vs = binding.Session(cfg, w_t, flags=fl)
+            vs.ll_prefill(prompt)
+            vs.ll_decode_n(10)
+            out[name] = vs.ll_dbg_time_decode(K) / K
+            vs.close()
+            log("[bench] %-55s %.4f ms per step (device, KV %d..%d)" % (name, out[name], n_prompt + 10, n_prompt + 10 + K))
+        print(json.dumps(dict(metric="decode step, measured arrangements", unit="ms", steps=K, prompt=n_prompt, device_ms_per_step=out)))
+        return 0
 
     if args.batched:
         print(json.dumps(dict(metric="batched decode step over a paged KV cache", unit="ms", n_gpus=1, dtype="f16",

@@ -20,7 +20,9 @@
  * host buffers and host bookkeeping.
  *
  * Weights are IEEE binary16, row-major [out, in] (y = W x); RMSNorm gains are
- * binary16 [d_model]; tok_emb and lm_head are [vocab, d_model] and not tied.
+ * binary16 [d_model]; tok_emb and lm_head are [vocab, d_model] and not tied.  They must not
+ * change between ll_init() and ll_shutdown(): the library keeps a re-ordered copy of the
+ * projection matrices in the workspace (see LL_FLAG_LEAN_WORKSPACE).
  *
  * Errors: every call returns >= 0 on success and a negative LL_E_* code on
  * failure; ll_last_error() then describes it.  A call that fails its argument,
@@ -74,6 +76,12 @@ enum {
                               a second stream while the current one replays.  Same kernels as
                               the multi-kernel graph (they read the length from device memory);
                               excludes LL_FLAG_EAGER and LL_FLAG_PERSISTENT. */
+  LL_FLAG_LEAN_WORKSPACE = 32,
+                           /* do without the second copy of the projection weights that ll_init otherwise
+                              writes into the workspace in the short-prompt kernels' operand order (about
+                              the size of the layers' weights again: 13 GB at the 7B shape; prompts of at
+                              most 32 tokens and batched steps then read the caller's row-major weights,
+                              some 15 % slower) */
   LL_FLAG_FUSED_ATTN_OPROJ = 16
                            /* a measured experiment, off by default: decode attention and O projection of
                               a layer in ONE launch, the projection's workgroups holding all of W_o in

@@ -21,6 +21,7 @@ LL_FLAG_MULTIKERNEL = 2
 LL_FLAG_PERSISTENT = 4
 LL_FLAG_PER_LENGTH_GRAPHS = 8
 LL_FLAG_FUSED_ATTN_OPROJ = 16
+LL_FLAG_LEAN_WORKSPACE = 32
 LL_MODE_PERSISTENT_GRAPH, LL_MODE_MULTIKERNEL_GRAPH, LL_MODE_EAGER, LL_MODE_PER_LENGTH_GRAPHS = 0, 1, 2, 3
 KERNEL_CLASSES = ("embed", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "sample")
 LAYER_KEYS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
@@ -263,7 +264,10 @@ class Session:
     def ll_shutdown(self):
         if self.open:
             self.open = False
-            return _check(self.lib.ll_shutdown())
+            rc = _check(self.lib.ll_shutdown())
+            self.workspace = None          # the library is done with it
+            self.pool = None
+            return rc
         return 0
 
     close = ll_shutdown

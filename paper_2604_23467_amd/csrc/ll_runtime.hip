@@ -152,6 +152,8 @@ struct Layout {
   size_t kv, rope, x, x_keep, q, o, m, attn_part, attn_cnt, logits, amax_val, amax_idx, state, tokens;
   size_t pf_x, pf_xn, pf_part, pf_q, pf_o, pf_h, pf_ss;
   size_t mk_layers, mk_bar, mk_amax_val, mk_amax_idx, mk_trace, zeros, sample_cfg, ao_sync;
+  size_t wf;                // fragment-major copy of the projection weights for the short-prompt kernels (0 bytes without it)
+  size_t wf_qkv, wf_o, wf_gu, wf_down, wf_layer, wf_lm;   // offsets inside a layer's part, bytes per layer, offset of the LM head's copy
   size_t total;
   int attn_splits, lm_wgs, max_prompt, mb_max;
   size_t kv_layer_halves;   // halves per layer per K or V
@@ -212,6 +214,21 @@ Layout make_layout(const ll_config& c) {
   L.mk_amax_val = take(1024 * 4);   // one candidate per workgroup of the persistent kernel
   L.mk_amax_idx = take(1024 * 4);
   L.mk_trace = take((size_t)(5 * c.n_layers + 2) * 8 * 8);
+  // Second copy of the weights in the short-prompt kernels' operand order (see sk_shuffle_kernel):
+  // [layer][q,k,v | o | gate,up | down] then the LM head, 1 KB per 16-row block and 32-wide K step.
+  if (skinny_ok(c) && !(c.flags & LL_FLAG_LEAN_WORKSPACE)) {
+    const size_t kd = (d + 31) / 32, kf = (F + 31) / 32;
+    L.wf_qkv = 0;
+    L.wf_o = L.wf_qkv + align_up((size_t)skinny_units(SK_QKV, c.d_model) * kd * 1024);
+    L.wf_gu = L.wf_o + align_up((size_t)skinny_units(SK_RES, c.d_model) * kd * 1024);
+    L.wf_down = L.wf_gu + align_up((size_t)skinny_units(SK_GATEUP, c.ffn_hidden) * kd * 1024);
+    L.wf_layer = L.wf_down + align_up((size_t)skinny_units(SK_RES, c.d_model) * kf * 1024);
+    L.wf_lm = L.wf_layer * c.n_layers;
+    L.wf = take(L.wf_lm + (c.vocab % 16 == 0 ? (size_t)skinny_units(SK_LOGITS, c.vocab) * kd * 1024 : 0));
+  } else {
+    L.wf_layer = 0;
+    L.wf = off;
+  }
   L.total = off;
   return L;
 }
@@ -331,6 +348,11 @@ struct Instance {
   half_t* kcache(int layer) const { return at<half_t>(L.kv) + (size_t)layer * 2 * L.kv_layer_halves; }
   half_t* vcache(int layer) const { return kcache(layer) + L.kv_layer_halves; }
   DevState* state() const { return at<DevState>(L.state); }
+  // fragment-major copy of one matrix group of a layer (null without the copy)
+  const half_t* wfrag(int layer, size_t group_off) const {
+    return L.wf_layer ? at<half_t>(L.wf + (size_t)layer * L.wf_layer + group_off) : nullptr;
+  }
+  const half_t* wfrag_lm() const { return L.wf_layer && cfg.vocab % 16 == 0 ? at<half_t>(L.wf + L.wf_lm) : nullptr; }
 };
 
 Instance* g = nullptr;
@@ -630,6 +652,7 @@ void enqueue_prefill_skinny(Instance* I, hipStream_t s, const PfBuffers& B, int 
     a.X = Xn; a.W[0] = (const half_t*)W.wq; a.W[1] = (const half_t*)W.wk; a.W[2] = (const half_t*)W.wv;
     a.N = d; a.K = d; a.Q = Qh; a.kc = I->kcache(l); a.vc = I->vcache(l); a.rope = I->at<float2>(I->L.rope);
     a.ss_in = ss_attn; a.ss_parts = l == 0 ? 1 : parts;     // the embedding gather leaves whole sums in slot 0
+    a.Wf = I->wfrag(l, I->L.wf_qkv);
     launch_skinny<SK_QKV>(s, B, a, Mb);
     dim3 agrid(c.n_heads, 1);
     if (c.head_dim == 128)
@@ -640,13 +663,16 @@ void enqueue_prefill_skinny(Instance* I, hipStream_t s, const PfBuffers& B, int 
                          I->vcache(l), I->state(), Oh, d, c.max_seq, tb);
     a.X = Oh; a.W[0] = (const half_t*)W.wo; a.W[1] = a.W[2] = nullptr; a.N = d; a.K = d; a.Xres = X;
     a.gain_next = (const half_t*)W.ffn_norm; a.Xh_next = Xn; a.ss_out = ss_ffn;
+    a.Wf = I->wfrag(l, I->L.wf_o);
     launch_skinny<SK_RES>(s, B, a, Mb);
     a.X = Xn; a.W[0] = (const half_t*)W.w_gate; a.W[1] = (const half_t*)W.w_up; a.N = F; a.K = d; a.Hout = Hm;
     a.ss_in = ss_ffn; a.ss_parts = parts;
+    a.Wf = I->wfrag(l, I->L.wf_gu);
     launch_skinny<SK_GATEUP>(s, B, a, Mb);
     a.X = Hm; a.W[0] = (const half_t*)W.w_down; a.W[1] = nullptr; a.N = d; a.K = F; a.Xres = X;
     a.gain_next = l + 1 < c.n_layers ? (const half_t*)I->layers[l + 1].attn_norm : nullptr;
     a.Xh_next = Xn; a.ss_out = ss_attn;
+    a.Wf = I->wfrag(l, I->L.wf_down);
     launch_skinny<SK_RES>(s, B, a, Mb);
   }
   if (with_head) enqueue_head(I, s, B, X, 1, 1);
@@ -923,6 +949,7 @@ void enqueue_batch_step(Instance* I, hipStream_t s) {
     a.N = d; a.K = d; a.Q = Qh; a.kc = B->kpool(l); a.vc = B->vpool(l); a.rope = I->at<float2>(I->L.rope);
     a.ss_in = ss_attn; a.ss_parts = l == 0 ? 1 : parts;
     a.row_pos = bs->pos; a.page_table = table; a.pt_stride = B->L.pt_stride; a.page_tokens = B->page_tokens;
+    a.Wf = I->wfrag(l, I->L.wf_qkv);
     launch_skinny<SK_QKV>(s, P, a, Mb);
     dim3 agrid(c.n_heads, Mb);
     if (c.head_dim == 128)
@@ -934,13 +961,16 @@ void enqueue_batch_step(Instance* I, hipStream_t s) {
     a.row_pos = nullptr; a.page_table = nullptr;
     a.X = Oh; a.W[0] = (const half_t*)W.wo; a.W[1] = a.W[2] = nullptr; a.N = d; a.K = d; a.Xres = X;
     a.gain_next = (const half_t*)W.ffn_norm; a.Xh_next = Xn; a.ss_out = ss_ffn;
+    a.Wf = I->wfrag(l, I->L.wf_o);
     launch_skinny<SK_RES>(s, P, a, Mb);
     a.X = Xn; a.W[0] = (const half_t*)W.w_gate; a.W[1] = (const half_t*)W.w_up; a.N = F; a.K = d; a.Hout = Hm;
     a.ss_in = ss_ffn; a.ss_parts = parts;
+    a.Wf = I->wfrag(l, I->L.wf_gu);
     launch_skinny<SK_GATEUP>(s, P, a, Mb);
     a.X = Hm; a.W[0] = (const half_t*)W.w_down; a.W[1] = nullptr; a.N = d; a.K = F; a.Xres = X;
     a.gain_next = l + 1 < c.n_layers ? (const half_t*)I->layers[l + 1].attn_norm : (const half_t*)I->w.final_norm;
     a.Xh_next = Xn; a.ss_out = ss_attn;
+    a.Wf = I->wfrag(l, I->L.wf_down);
     launch_skinny<SK_RES>(s, P, a, Mb);
   }
   {
@@ -949,6 +979,7 @@ void enqueue_batch_step(Instance* I, hipStream_t s) {
     a.st = st; a.eps = c.rms_eps; a.head_dim = c.head_dim; a.max_seq = c.max_seq;
     a.X = Xn; a.W[0] = (const half_t*)I->w.lm_head; a.N = c.vocab; a.K = d;
     a.ss_in = ss_attn; a.ss_stride = sst; a.ss_parts = parts; a.logits = B->at<float>(B->L.logits);
+    a.Wf = I->wfrag_lm();
     a.zeros_off = P.zeros - a.X;
     const int units = skinny_units(SK_LOGITS, c.vocab);
     dim3 grid(units < g_num_cus ? units : g_num_cus);
@@ -1098,6 +1129,27 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
     }
     if (!hip_or_bail(hipMemcpy(I->at<MkLayer>(L.mk_layers), tab.data(), tab.size() * sizeof(MkLayer),
                                hipMemcpyHostToDevice), "hipMemcpy(layer table)")) return bail(rc);
+  }
+  if (L.wf_layer) {
+    // the short-prompt kernels' copy of the projection weights, written once (the weights must not
+    // change while the instance lives)
+    const int d = cfg->d_model, F = cfg->ffn_hidden, kd = (d + 31) / 32, kf = (F + 31) / 32;
+    auto shuffle = [&](auto kernel, int units, int ksteps, const void* w0, const void* w1, const void* w2, int N, int K,
+                       const half_t* out) {
+      hipLaunchKernelGGL(kernel, dim3(units, (ksteps + LL_WG / 64 - 1) / (LL_WG / 64)), dim3(LL_WG), 0, I->stream,
+                         (const half_t*)w0, (const half_t*)w1, (const half_t*)w2, N, K, cfg->head_dim, const_cast<half_t*>(out));
+    };
+    for (int l = 0; l < cfg->n_layers; ++l) {
+      const ll_layer_weights& lw = I->layers[l];
+      shuffle(sk_shuffle_kernel<SK_QKV>, skinny_units(SK_QKV, d), kd, lw.wq, lw.wk, lw.wv, d, d, I->wfrag(l, L.wf_qkv));
+      shuffle(sk_shuffle_kernel<SK_RES>, skinny_units(SK_RES, d), kd, lw.wo, nullptr, nullptr, d, d, I->wfrag(l, L.wf_o));
+      shuffle(sk_shuffle_kernel<SK_GATEUP>, skinny_units(SK_GATEUP, F), kd, lw.w_gate, lw.w_up, nullptr, F, d, I->wfrag(l, L.wf_gu));
+      shuffle(sk_shuffle_kernel<SK_RES>, skinny_units(SK_RES, d), kf, lw.w_down, nullptr, nullptr, d, F, I->wfrag(l, L.wf_down));
+    }
+    if (I->wfrag_lm())
+      shuffle(sk_shuffle_kernel<SK_LOGITS>, skinny_units(SK_LOGITS, cfg->vocab), kd, I->w.lm_head, nullptr, nullptr,
+              cfg->vocab, d, I->wfrag_lm());
+    if (!hip_or_bail(hipGetLastError(), "weight re-layout launch")) return bail(rc);
   }
   if ((cfg->flags & LL_FLAG_PERSISTENT) && !(cfg->flags & (LL_FLAG_EAGER | LL_FLAG_MULTIKERNEL))) {
     std::string why;

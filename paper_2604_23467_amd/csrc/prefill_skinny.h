@@ -44,6 +44,9 @@ enum SkinnyMode { SK_QKV = 0, SK_RES = 1, SK_GATEUP = 2, SK_LOGITS = 3 };
 struct SkinnyArgs {
   const half_t* X;        // 16 TB token rows x K fp16 activations, fragment-major; rows >= n hold anything
   const half_t* W[3];     // [N][K] fp16 each (QKV: q, k, v; GATEUP: gate, up; RES: one matrix)
+  const half_t* Wf;       // optional copy of the same matrices in the kernels' own operand order (see
+                          // sk_shuffle_kernel): the 16 x 32 piece of row block u and K step s is the 1 KB at
+                          // ((u * ceil(K / 32) + s) * 64 + lane) * 8, zero beyond K.  Null: read W row-major
   const DevState* st;
   int N, K;
   float* Xres;            // RES: residual stream [rows][N] fp32, updated in place for rows < n
@@ -158,6 +161,10 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_kernel(SkinnyArgs a) 
     }
   }
 
+  // with a fragment-major copy a wave's load is 1 KB of consecutive bytes instead of 16 rows x 64 bytes
+  const bool frag = a.Wf != nullptr;
+  const half_t* wfrag = frag ? a.Wf + ((size_t)blockIdx.x * ((K + 31) >> 5) * 64 + lane) * 8 : nullptr;
+
   f4 acc[TB];
 #pragma unroll
   for (int t = 0; t < TB; ++t) acc[t] = f4{0.f, 0.f, 0.f, 0.f};
@@ -196,7 +203,7 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_kernel(SkinnyArgs a) 
     for (int i = 0; i < U; ++i) {
       const int st = s0 + i, k = st * 32 + g * 8;
       const bool in = st < s_end && k < K;           // K % 8 == 0: 8 halves are all in or all out
-      A[i] = load_h8(wrow + (in ? k : 0));
+      A[i] = load_h8(frag ? wfrag + (in ? (long)st * 512 : 0) : wrow + (in ? k : 0));
 #pragma unroll
       for (int t = 0; t < TB; ++t)
         B[i][t] = load_h8(a.X + (in ? (long)(st * TB + t) * 512 + lane * 8 : a.zeros_off));
@@ -376,9 +383,14 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
   };
   // element offset of K step i in a weight row; steps outside the wave's range re-read the row
   // start instead (always valid memory) and meet a zero B fragment
+  // (with a fragment-major copy: its 1 KB pieces, 512 halves per K step, instead of 16 rows x 64 bytes)
+  const bool frag = a.Wf != nullptr;
   int koff[SKP_KSTEPS];
 #pragma unroll
-  for (int i = 0; i < SKP_KSTEPS; ++i) koff[i] = in[i] ? (s_begin + i) * 32 + g * 8 : 0;
+  for (int i = 0; i < SKP_KSTEPS; ++i) koff[i] = !in[i] ? 0 : frag ? (s_begin + i) * 512 : (s_begin + i) * 32 + g * 8;
+  auto blk_ptr = [&](int u) -> const half_t* {
+    return frag ? a.Wf + ((size_t)u * ksteps * 64 + lane) * 8 : row_ptr(u);
+  };
 
   // a few small loads for the tokens' norm factors, then the weight stream, then the (cached) activations
   SkSsLoads sl;
@@ -387,7 +399,7 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
   int u = blockIdx.x;
   h8 fa0[HALF], fa1[HALF];
   {
-    const half_t* wp = row_ptr(u < units ? u : 0);
+    const half_t* wp = blk_ptr(u < units ? u : 0);
 #pragma unroll
     for (int i = 0; i < HALF; ++i) fa0[i] = load_h8(wp + koff[i]);
   }
@@ -404,7 +416,7 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
   int round = 0;
   for (; u < units; u += gridDim.x, ++round) {
     {
-      const half_t* wp = row_ptr(u);
+      const half_t* wp = blk_ptr(u);
 #pragma unroll
       for (int i = 0; i < HALF; ++i) fa1[i] = load_h8(wp + koff[HALF + i]);
     }
@@ -420,7 +432,7 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
     // row block 0, which every workgroup re-reads from cache
     {
       const int un = u + gridDim.x;
-      const half_t* wp = row_ptr(un < units ? un : 0);
+      const half_t* wp = blk_ptr(un < units ? un : 0);
 #pragma unroll
       for (int i = 0; i < HALF; ++i) fa0[i] = load_h8(wp + koff[i]);
     }
@@ -494,6 +506,43 @@ __global__ __launch_bounds__(SK_THREADS, 1) void pf_skinny_persist_kernel(Skinny
       }
     }
   }
+}
+
+// One-off re-layout of a projection's weights into the short-prompt kernels' operand order (run once
+// per matrix group at initialisation).  Read row-major, the A operand of a 16 x 16 x 32 product is 16
+// rows x 64 bytes per wave and load, a shape this chip streams at 5.7 TB/s where 1 KB of consecutive
+// bytes per load reaches 6.8 (measured with plain read kernels); the copy puts the 16 x 32 piece of
+// row block u and K step s, in lane order, at ((u * ksteps + s) * 64 + lane) * 8 halves, so the
+// projections stream it like the decode GEMVs stream rows.  Row blocks are the kernels' own (RoPE
+// partners, gate / up pairs).  grid = (row blocks, ceil(ksteps / 4)), 256 threads: one wave per piece.
+template <int MODE>
+__global__ __launch_bounds__(LL_WG) void sk_shuffle_kernel(const half_t* __restrict__ w0, const half_t* __restrict__ w1,
+                                                           const half_t* __restrict__ w2, int N, int K, int head_dim,
+                                                           half_t* __restrict__ out) {
+  const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+  const int ksteps = (K + 31) >> 5, u = blockIdx.x, s = blockIdx.y * (LL_WG / 64) + (threadIdx.x >> 6);
+  if (s >= ksteps) return;
+  const half_t* W[3] = {w0, w1, w2};
+  const half_t* src;
+  if (MODE == SK_RES || MODE == SK_LOGITS) {
+    src = W[0] + (size_t)(u * 16 + r) * K;
+  } else if (MODE == SK_GATEUP) {
+    src = W[r >> 3] + (size_t)(u * 8 + (r & 7)) * K;
+  } else {
+    const int hh = head_dim >> 1, per = N / 16, z = u / per, v = u - z * per;
+    int row;
+    if (z == 2) {
+      row = v * 16 + r;
+    } else {
+      const int bph = hh / 8, head = v / bph, j0 = (v - head * bph) * 8;
+      row = head * head_dim + j0 + (r & 7) + (r >> 3) * hh;
+    }
+    src = W[z] + (size_t)row * K;
+  }
+  const int k = s * 32 + g * 8;
+  h8 v8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (k < K) v8 = load_h8(src + k);                      // K % 8 == 0: a piece is all in or all out
+  *reinterpret_cast<h8*>(out + (((size_t)u * ksteps + s) * 64 + lane) * 8) = v8;
 }
 
 // Layer-0 front end of the short-prompt path: X[r] = float(E[tokens[r]]) (zero for r >= n),

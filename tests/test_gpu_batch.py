@@ -58,7 +58,7 @@ def _step_all(sess, seqs):
     return [q.check(sess, toks) for q in seqs]
 
 
-@pytest.mark.parametrize("flags", [0, 1], ids=["graph", "eager"])
+@pytest.mark.parametrize("flags", [0, 1, 32], ids=["graph", "eager", "lean-workspace"])
 def test_tiny_batch_with_sequences_joining_and_leaving(torch_cuda, oracle32, flags):
     """Pages of 8 positions, so every sequence crosses several page borders; a sequence joins while
     others are running, one leaves and its pages serve a newcomer."""

@@ -108,7 +108,7 @@ def test_short_prompt_wide_model(torch_cuda, oracle32, n_prompt):
     om.close()
 
 
-@pytest.mark.parametrize("flags", [0, 1], ids=["graph", "eager"])
+@pytest.mark.parametrize("flags", [0, 1, 32], ids=["graph", "eager", "lean-workspace"])
 @pytest.mark.parametrize("n_prompt", [2, 15, 16, 17, 31, 32, 33, 50])
 def test_short_prompt_row_blocks(torch_cuda, oracle32, n_prompt, flags):
     """Prompts around the 16 / 32 / 64-row boundaries of the short-prompt kernels, head_dim 128
