@@ -582,7 +582,7 @@ void enqueue_decode(Instance* I, hipStream_t s) {
 // Projection GEMM A W_z^T into the slice buffer; the returned map tells the consuming kernel
 // which slices to add up for which column.
 SliceMap launch_gemm(Instance* I, hipStream_t s, const PfBuffers& B, const half_t* A, const void* w0, const void* w1,
-                     const void* w2, int nmat, int ldc, int N, int K, int Mb) {
+                     const void* w2, int nmat, int ldc, int N, int K, int Mb, const half_t* wf = nullptr) {
   const GemmPlan p = gemm_plan(N, K, nmat, Mb, ldc);
   GemmArgs ga{};
   ga.A = A;
@@ -593,7 +593,10 @@ SliceMap launch_gemm(Instance* I, hipStream_t s, const PfBuffers& B, const half_
   ga.N = N; ga.K = K; ga.ldc = ldc; ga.nmat = nmat;
   ga.mtiles = p.mtiles; ga.runs = p.runs; ga.map = p.map;
   dim3 grid((p.runs + 7) / 8 * 8 * p.mtiles);      // runs are dealt to the 8 XCDs
-  if (gemm_bm(Mb) == 128)
+  ga.Wf = wf;
+  if (gemm_bm(Mb) == 128 && wf && nmat == 1)
+    hipLaunchKernelGGL((pf_gemm_kernel<128, 3, 2, 4, 64, 1, true>), grid, dim3(PF_GEMM_THREADS_OF(2, 4)), PF_GEMM_LDS_BYTES(128, 3, 64), s, ga);
+  else if (gemm_bm(Mb) == 128)
     hipLaunchKernelGGL((pf_gemm_kernel<128, 3, 2, 4, 64>), grid, dim3(PF_GEMM_THREADS_OF(2, 4)), PF_GEMM_LDS_BYTES(128, 3, 64), s, ga);
   else
     hipLaunchKernelGGL((pf_gemm_kernel<64, 3, 1, 4, 64>), grid, dim3(PF_GEMM_THREADS_OF(1, 4)), PF_GEMM_LDS_BYTES(64, 3, 64), s, ga);
@@ -724,14 +727,14 @@ void enqueue_prefill(Instance* I, hipStream_t s, int Mb, bool with_head = true) 
                        I->at<float2>(I->L.rope), I->state(), Qh, I->kcache(l), I->vcache(l), d,
                        c.head_dim, c.max_seq);
     launch_attn(I, s, B, l, Mb);
-    res = launch_gemm(I, s, B, Oh, W.wo, nullptr, nullptr, 1, d, d, d, Mb);
+    res = launch_gemm(I, s, B, Oh, W.wo, nullptr, nullptr, 1, d, d, d, Mb, I->wfrag(l, I->L.wf_o));
     res_part = P;
     hipLaunchKernelGGL(pf_rmsnorm_kernel, dim3(Mb), dim3(PF_NORM_THREADS), 0, s, X, (const half_t*)W.ffn_norm,
                        Xn, d, c.rms_eps, I->state(), res_part, res, 0);
     const SliceMap gu = launch_gemm(I, s, B, Xn, W.w_gate, W.w_up, nullptr, 2, 2 * F, F, d, Mb);
     hipLaunchKernelGGL(pf_swiglu_kernel, dim3(Mb, (F + LL_WG * 4 - 1) / (LL_WG * 4)), dim3(LL_WG), 0,
                        s, P, gu, I->state(), Hm, F);
-    res = launch_gemm(I, s, B, Hm, W.w_down, nullptr, nullptr, 1, d, d, F, Mb);
+    res = launch_gemm(I, s, B, Hm, W.w_down, nullptr, nullptr, 1, d, d, F, Mb, I->wfrag(l, I->L.wf_down));
   }
   if (with_head && res_part)    // (a chunk that is not the prompt's last needs nothing of X any more)
     hipLaunchKernelGGL(pf_fold_kernel, dim3(Mb, (d + LL_WG * 4 - 1) / (LL_WG * 4)), dim3(LL_WG), 0, s, X,
@@ -1104,6 +1107,9 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&bt_select_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, SMP_Z_WORDS * 4),
                    "hipFuncSetAttribute(batch select)")) return bail(rc);
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128, 3, 2, 4, 64, 1, true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128, 3, 64)),
+                   "hipFuncSetAttribute(gemm 128, fragment-major weights)")) return bail(rc);
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128, 3, 2, 4, 64>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128, 3, 64)),
                    "hipFuncSetAttribute(gemm 128)")) return bail(rc);

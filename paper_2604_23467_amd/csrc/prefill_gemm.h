@@ -40,6 +40,9 @@
 struct GemmArgs {
   const half_t* A;        // [>= mtiles * BM rows][K]
   const half_t* W[3];
+  const half_t* Wf;       // optional: matrix 0 in the short-prompt kernels' fragment-major order (16-row blocks x
+                          // 32-wide K steps, 1 KB each, zero beyond K; see sk_shuffle_kernel with plain row blocks);
+                          // kernels instantiated with WFRAG read the weights from it in whole 1 KB pieces
   float* C;               // slices: [slice][rows][ldc]
   const DevState* st;
   const half_t* zeros;    // >= 16 bytes of zeros in global memory
@@ -74,8 +77,9 @@ __device__ __forceinline__ void wait_vm_at_most() {
 // wave cycles) nor bytes in flight (+33 % with the fifth stage bought 4-6 %) are what holds these
 // GEMMs at 35-40 % of the matrix cores' time.  Two workgroups per CU (<128, 3, 2, 2, 32, 2>: four waves
 // of 64 x 128 each, the plan dealing two rounds' worth of runs) lost outright: 82 / 32 / 123 / 67 us.
-template <int BM, int NS, int WM, int WN, int BK, int OCC = 1>
+template <int BM, int NS, int WM, int WN, int BK, int OCC = 1, bool WFRAG = false>
 __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kernel(GemmArgs g) {
+  static_assert(!WFRAG || BK == 64, "the fragment-major weight path pairs two 32-wide K steps per slab");
   constexpr int NWAVES = WM * WN;
   constexpr int MT = BM / WM / 32;                     // 32-row accumulators per wave
   constexpr int NT = PF_BN / WN / 32;                  // 32-column accumulators per wave
@@ -125,10 +129,17 @@ __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kerne
 #pragma unroll
   for (int i = 0; i < A_LD; ++i)
     arow[i] = g.A + (size_t)(m0 + (wave * A_LD + i) * RPL + lrow) * K + lchunk * 8;
+  const int ksteps32 = (K + 31) >> 5;
 #pragma unroll
   for (int i = 0; i < W_LD; ++i) {
-    const int n = n0 + (wave * W_LD + i) * RPL + lrow;
-    wrow[i] = (n < g.N) ? g.W[z] + (size_t)n * K + lchunk * 8 : nullptr;
+    if (WFRAG) {
+      // piece f of the stage = 16-row block f / 2 of the tile, K step f % 2 of the slab: 1 KB of consecutive bytes
+      const int f = wave * W_LD + i, blk = n0 / 16 + (f >> 1);
+      wrow[i] = (blk * 16 < g.N) ? g.Wf + (((size_t)blk * ksteps32 + (f & 1)) * 64 + lane) * 8 : nullptr;
+    } else {
+      const int n = n0 + (wave * W_LD + i) * RPL + lrow;
+      wrow[i] = (n < g.N) ? g.W[z] + (size_t)n * K + lchunk * 8 : nullptr;
+    }
   }
   // Every workgroup walks its K range from a different starting slab (and wraps around): all
   // tiles reading the same 128-byte column of their weight rows at the same time would keep
@@ -151,7 +162,13 @@ __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kerne
     }
 #pragma unroll
     for (int i = 0; i < W_LD; ++i) {
-      const half_t* src = (kin && wrow[i]) ? wrow[i] + k0 : g.zeros;
+      const half_t* src;
+      if (WFRAG) {          // K step 2 sl + (piece % 2); the copy is zero beyond K, steps past its end come from the zeros
+        const int st = sl * 2 + ((wave * W_LD + i) & 1);
+        src = (it < iters && st < ksteps32 && wrow[i]) ? wrow[i] + (size_t)sl * 1024 : g.zeros;
+      } else {
+        src = (kin && wrow[i]) ? wrow[i] + k0 : g.zeros;
+      }
       __builtin_amdgcn_global_load_lds((const LL_GLOBAL void*)src,
                                        (__attribute__((address_space(3))) void*)(sw + (wave * W_LD + i) * RPL * BK),
                                        16, 0, 0);
@@ -188,7 +205,17 @@ __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kerne
 #pragma unroll
       for (int i = 0; i < MT; ++i) fa[i] = *reinterpret_cast<const h8*>(sa + i * 32 * BK + pc);
 #pragma unroll
-      for (int j = 0; j < NT; ++j) fb[j] = *reinterpret_cast<const h8*>(sw + j * 32 * BK + pc);
+      for (int j = 0; j < NT; ++j) {
+        if (WFRAG) {
+          // row R of the tile sits in piece (R / 16) * 2 + ks / 2 at lane position ((ks % 2) * 2 + half) * 16 + R % 16:
+          // 8 lanes read 128 consecutive bytes, no swizzle needed
+          const int R = wn * (PF_BN / WN) + j * 32 + r;
+          fb[j] = *reinterpret_cast<const h8*>(pf_lds + stage * STAGE_HALVES + BM * BK +
+                                               ((((R >> 4) * 2 + (ks >> 1)) * 64) + ((ks & 1) * 2 + half) * 16 + (R & 15)) * 8);
+        } else {
+          fb[j] = *reinterpret_cast<const h8*>(sw + j * 32 * BK + pc);
+        }
+      }
     };
     h8 fa[2][MT], fb[2][NT];
     load_frags(0, fa[0], fb[0]);
