@@ -76,7 +76,15 @@ __device__ __forceinline__ void wait_vm_at_most() {
 // at 250 tokens the prefill was 0.4 ms slower: neither LDS reads (SQ_WAIT_INST_LDS under 1 % of the
 // wave cycles) nor bytes in flight (+33 % with the fifth stage bought 4-6 %) are what holds these
 // GEMMs at 35-40 % of the matrix cores' time.  Two workgroups per CU (<128, 3, 2, 2, 32, 2>: four waves
-// of 64 x 128 each, the plan dealing two rounds' worth of runs) lost outright: 82 / 32 / 123 / 67 us.
+// of 64 x 128 each, the plan dealing two rounds' worth of runs) lost outright: 82 / 32 / 123 / 67 us; the
+// 256 x 256 tile as eight waves of 64 x 128 (<256, 5, 4, 2, 32>) gave 75 / 33 / 115 / 63 us.  Where the
+// time goes at 500 tokens, from two timing-only builds of the 128 x 256 kernel: without the global
+// loads (matrix instructions, LDS reads, barriers and the stores of the slices) the four projections take
+// 41 / 18 / 65 / 34 us, i.e. with 64 x 64 waves the LDS reads alone take as long as the matrix
+// instructions and the two overlap poorly; without the matrix instructions (loads, LDS reads, stores)
+// 58 / 21 / 96 / 47 us; together 72 / 27 / 118 / 57 us.  FETCH_SIZE counts 210 / 42 / 364 / 157 MB from
+// HBM per launch against 101 / 34 / 180 / 90 MB of weights: the four row tiles of a column tile, placed
+// on one XCD, share about half of their weight fetches through its L2.
 template <int BM, int NS, int WM, int WN, int BK, int OCC = 1, bool WFRAG = false>
 __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kernel(GemmArgs g) {
   static_assert(!WFRAG || BK == 64, "the fragment-major weight path pairs two 32-wide K steps per slab");
