@@ -70,8 +70,8 @@ __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
       const int u = min(base + j * STRIDE + gi, n_keys - 1);
       const int pg = u / page_tokens;
       const size_t row = (size_t)(s_pt[pg] + (u - pg * page_tokens));
-      kk[j] = load_h8(kh + row * HD);
-      vv[j] = load_h8(vh + row * HD);
+      kk[j] = load_stream(kh + row * HD);
+      vv[j] = load_stream(vh + row * HD);
     }
 #pragma unroll
     for (int j = 0; j < UK; ++j) {

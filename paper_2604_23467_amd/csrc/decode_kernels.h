@@ -418,8 +418,8 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_decode_kernel(
 #pragma unroll
     for (int j = 0; j < UK; ++j) {
       const int u = min(base + j * stride + gi, n_keys - 1);
-      kk[j] = load_h8(kh + (size_t)u * HD);
-      vv[j] = load_h8(vh + (size_t)u * HD);
+      kk[j] = load_stream(kh + (size_t)u * HD);
+      vv[j] = load_stream(vh + (size_t)u * HD);
     }
 #pragma unroll
     for (int j = 0; j < UK; ++j) {

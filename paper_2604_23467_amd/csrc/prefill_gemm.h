@@ -14,7 +14,7 @@
 // over 256 CUs it is the L2 -> CU traffic, not HBM, that bounds these GEMMs.
 //
 // Both operands go global -> LDS directly (global_load_lds_dwordx4: no staging registers)
-// into a ring of NS stages, NS - 1 slabs ahead of the one being multiplied.  A direct load
+// into a ring of NS stages, refilled as soon as every wave holds a slab's last fragments in registers.  A direct load
 // writes the 64 lanes' 16-byte pieces to consecutive LDS addresses, so rows are stored
 // unpadded (128 bytes) and 16-byte chunk c of row r lives at chunk position c ^ (r & 7);
 // fragment reads of 32 rows x 2 chunks then run at the LDS's full rate (measured).  Pieces
@@ -98,8 +98,12 @@ __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kerne
   constexpr int W_LD = PF_BN / RPL / NWAVES;
   constexpr int PER_SLAB = A_LD + W_LD;
   constexpr int STAGE_HALVES = (BM + PF_BN) * BK;
+  // Cache policy of the weight loads.  With one row tile per column tile (prompts of at most 64 rows) every
+  // weight byte is used once and is loaded non-temporal (4.29 -> 4.12 ms at 50 tokens); with sibling row
+  // tiles the copies that the siblings find in L2 matter more (non-temporal: 11.14 -> 11.40 ms at 500).
+  constexpr int W_AUX = BM == 64 ? 2 : 0;
   static_assert(BK == 64 || BK == 32, "swizzles below are for 128- and 64-byte rows");
-  static_assert(A_LD >= 1 && W_LD >= 1 && PER_SLAB * (NS - 1) < 64, "vmcnt is a 6-bit counter");
+  static_assert(A_LD >= 1 && W_LD >= 1 && PER_SLAB * NS < 64, "vmcnt is a 6-bit counter");
   extern __shared__ __attribute__((aligned(16))) half_t pf_lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -179,7 +183,7 @@ __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kerne
       }
       __builtin_amdgcn_global_load_lds((const LL_GLOBAL void*)src,
                                        (__attribute__((address_space(3))) void*)(sw + (wave * W_LD + i) * RPL * BK),
-                                       16, 0, 0);
+                                       16, 0, W_AUX);
     }
   };
 
@@ -193,48 +197,86 @@ __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kerne
 
   __syncthreads();        // a previous piece's last fragment reads are over before its ring is refilled
 #pragma unroll
-  for (int s = 0; s < NS - 1; ++s) issue(s, s);
+  for (int s = 0; s < NS; ++s) issue(s, s);
 
-  for (int it = 0; it < iters; ++it) {
-    const int stage = it % NS;
-    // this wave's pieces of the slab have landed (younger slabs may still be in flight) ...
+  // fragments of the next k-step are read from LDS while the matrix cores work on the current one
+  auto load_frags = [&](int stage, int ks, h8 (&fa)[MT], h8 (&fb)[NT]) {
+    const half_t* sa = pf_lds + stage * STAGE_HALVES + (wm * (BM / WM) + r) * BK;
+    const half_t* sw = pf_lds + stage * STAGE_HALVES + (BM + wn * (PF_BN / WN) + r) * BK;
+    const int pc = ((ks * 2 + half) ^ swz(r)) * 8;    // all fragment rows start at multiples of 32
+#pragma unroll
+    for (int i = 0; i < MT; ++i) fa[i] = *reinterpret_cast<const h8*>(sa + i * 32 * BK + pc);
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      if (WFRAG) {
+        // row R of the tile sits in piece (R / 16) * 2 + ks / 2 at lane position ((ks % 2) * 2 + half) * 16 + R % 16:
+        // 8 lanes read 128 consecutive bytes, no swizzle needed
+        const int R = wn * (PF_BN / WN) + j * 32 + r;
+        fb[j] = *reinterpret_cast<const h8*>(pf_lds + stage * STAGE_HALVES + BM * BK +
+                                             ((((R >> 4) * 2 + (ks >> 1)) * 64) + ((ks & 1) * 2 + half) * 16 + (R & 15)) * 8);
+      } else {
+        fb[j] = *reinterpret_cast<const h8*>(sw + j * 32 * BK + pc);
+      }
+    }
+  };
+  // The slab hand-over sits in front of a slab's LAST k-step, not behind it: by then a wave holds the
+  // slab's last fragments in registers, so once every wave is there the slab's stage is free and is
+  // refilled at once (NS slabs in flight, not NS - 1), and the first fragments of the next slab are
+  // read while the matrix cores still work on this one; the barrier and the burst of LDS reads that
+  // opens a slab are hidden behind a k-step of matrix instructions instead of leaving them idle.
+  auto hand_over = [&](int it) {
+    // this wave's pieces of slab it + 1 have landed (younger slabs may still be in flight) ...
     wait_vm_at_most<PER_SLAB * (NS - 2)>();
-    // ... and so have everybody else's; everybody is also done reading the stage of the slab before.
+    // ... its fragment reads of slab it are done, and after the barrier so are everybody else's.
     // A bare s_barrier: __syncthreads() carries a fence that would drain ALL loads in flight.
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    issue(it + NS - 1, (stage + NS - 1) % NS);
-    const half_t* sa = pf_lds + stage * STAGE_HALVES + (wm * (BM / WM) + r) * BK;
-    const half_t* sw = pf_lds + stage * STAGE_HALVES + (BM + wn * (PF_BN / WN) + r) * BK;
-    // fragments of k-step ks + 1 are read from LDS while the matrix cores work on k-step ks
-    auto load_frags = [&](int ks, h8 (&fa)[MT], h8 (&fb)[NT]) {
-      const int pc = ((ks * 2 + half) ^ swz(r)) * 8;    // all fragment rows start at multiples of 32
+    issue(it + NS, it % NS);
+  };
+  constexpr int KS = BK / 16;
+  static_assert(KS % 2 == 0, "the fragment double buffer keeps its parity across slabs");
+  h8 fa[2][MT], fb[2][NT];
+  wait_vm_at_most<PER_SLAB * (NS - 1)>();
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  load_frags(0, 0, fa[0], fb[0]);
+  // PIN: scheduling fences pin the pipeline.  A k-step's group is the LDS reads of the NEXT k-step followed
+  // by the matrix instructions of this one, and the hand-over follows the group of the last k-step but one;
+  // left alone the compiler sinks every read to just before its use and waits for it there.  Measured at
+  // 500 tokens: Q/K/V 72.2 -> 69.7 us, gate/up 117.1 -> 113.3 us; the kernel on fragment-major weights is
+  // faster left to the compiler (O 27.2 against 28.2 us pinned, down 56.0 against 58.4), with the hand-over
+  // inside its last k-step.
+  constexpr bool PIN = !WFRAG;
+  if (PIN) __builtin_amdgcn_sched_barrier(0);
+  for (int it = 0; it < iters; ++it) {
+    const int stage = it % NS;
 #pragma unroll
-      for (int i = 0; i < MT; ++i) fa[i] = *reinterpret_cast<const h8*>(sa + i * 32 * BK + pc);
-#pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        if (WFRAG) {
-          // row R of the tile sits in piece (R / 16) * 2 + ks / 2 at lane position ((ks % 2) * 2 + half) * 16 + R % 16:
-          // 8 lanes read 128 consecutive bytes, no swizzle needed
-          const int R = wn * (PF_BN / WN) + j * 32 + r;
-          fb[j] = *reinterpret_cast<const h8*>(pf_lds + stage * STAGE_HALVES + BM * BK +
-                                               ((((R >> 4) * 2 + (ks >> 1)) * 64) + ((ks & 1) * 2 + half) * 16 + (R & 15)) * 8);
-        } else {
-          fb[j] = *reinterpret_cast<const h8*>(sw + j * 32 * BK + pc);
-        }
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) {
+        load_frags(stage, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+      } else if (!PIN) {
+        hand_over(it);
+        load_frags((it + 1) % NS, 0, fa[0], fb[0]);
       }
-    };
-    h8 fa[2][MT], fb[2][NT];
-    load_frags(0, fa[0], fb[0]);
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      if (ks + 1 < BK / 16) load_frags(ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
 #pragma unroll
       for (int j = 0; j < NT; ++j)
 #pragma unroll
         for (int i = 0; i < MT; ++i)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+      if (PIN) {
+        if (ks + 1 < KS) {
+          __builtin_amdgcn_sched_group_barrier(0x100, MT + NT, 0);   // the reads first ...
+          __builtin_amdgcn_sched_group_barrier(0x008, MT * NT, 0);   // ... then the matrix instructions
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (ks == KS - 2) {
+          hand_over(it);
+          load_frags((it + 1) % NS, 0, fa[0], fb[0]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
     }
   }
   wait_vm_at_most<0>();   // the zero-filled look-ahead loads must not outlive the workgroup's LDS
