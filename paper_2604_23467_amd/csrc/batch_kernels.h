@@ -47,15 +47,13 @@ __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
     return;
   }
   const int n_keys = bs->pos[b] + 1;
+  const h8 q = load_h8(Q + (size_t)b * d + h * HD + li * 8);   // requested ahead of the page table: one round trip for both
   for (int i = tid; i * page_tokens < n_keys; i += BT_ATTN_THREADS) s_pt[i] = page_table[b * pt_stride + i];
   __syncthreads();
   const float scale = 1.0f / sqrtf((float)HD);
   float qv[8];
-  {
-    const h8 q = load_h8(Q + (size_t)b * d + h * HD + li * 8);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) qv[e] = (float)q[e] * scale;
-  }
+  for (int e = 0; e < 8; ++e) qv[e] = (float)q[e] * scale;
   const half_t* kh = kc + (size_t)h * pool_rows * HD + li * 8;
   const half_t* vh = vc + (size_t)h * pool_rows * HD + li * 8;
 
@@ -73,21 +71,22 @@ __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
       kk[j] = load_stream(kh + row * HD);
       vv[j] = load_stream(vh + row * HD);
     }
+    __builtin_amdgcn_sched_barrier(0);     // all requests out before the first use
 #pragma unroll
     for (int j = 0; j < UK; ++j) {
       float dot = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) dot += qv[e] * (float)kk[j][e];
       dot = group_sum<LPR>(dot);
-      if (base + j * STRIDE + gi < n_keys) {
-        const float mn = fmaxf(m, dot);
-        const float corr = __expf(m - mn);
-        const float p = __expf(dot - mn);
-        l = l * corr + p;
+      // branch-free, as in attn_decode_kernel: a branch here makes the compiler sink a value row's load into it
+      const bool ok = base + j * STRIDE + gi < n_keys;
+      const float mn = ok ? fmaxf(m, dot) : m;
+      const float corr = (m == mn) ? 1.0f : __expf(m - mn);
+      const float p = ok ? __expf(dot - mn) : 0.f;
+      l = l * corr + p;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = acc[e] * corr + p * (float)vv[j][e];
-        m = mn;
-      }
+      for (int e = 0; e < 8; ++e) acc[e] = acc[e] * corr + p * (float)vv[j][e];
+      m = mn;
     }
   }
   {

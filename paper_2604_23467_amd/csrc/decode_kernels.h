@@ -398,13 +398,10 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_decode_kernel(
   const int n_keys = st->pos + 1;
   const float scale = 1.0f / sqrtf((float)HD);
 
-  float qv[8];
-  {
-    const f4 q0 = *reinterpret_cast<const f4*>(q + h * HD + li * 8);
-    const f4 q1 = *reinterpret_cast<const f4*>(q + h * HD + li * 8 + 4);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) { qv[e] = q0[e] * scale; qv[4 + e] = q1[e] * scale; }
-  }
+  // The query is used unscaled (the score takes the factor): nothing is computed from it before the
+  // first keys are requested, so its L2 round trip runs underneath theirs instead of in front of it.
+  const f4 q0 = *reinterpret_cast<const f4*>(q + h * HD + li * 8);
+  const f4 q1 = *reinterpret_cast<const f4*>(q + h * HD + li * 8 + 4);
   const half_t* kh = kc + (size_t)h * max_seq * HD + li * 8;
   const half_t* vh = vc + (size_t)h * max_seq * HD + li * 8;
 
@@ -413,7 +410,7 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_decode_kernel(
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
 
   const int stride = S * NW * GPW;
-  for (int base = (s * NW + wave) * GPW; base < n_keys; base += stride * UK) {
+  auto batch = [&](int base) {
     h8 kk[UK], vv[UK];
 #pragma unroll
     for (int j = 0; j < UK; ++j) {
@@ -421,24 +418,30 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_decode_kernel(
       kk[j] = load_stream(kh + (size_t)u * HD);
       vv[j] = load_stream(vh + (size_t)u * HD);
     }
+    __builtin_amdgcn_sched_barrier(0);     // all 16 requests out before the first use: one round trip, not several
 #pragma unroll
     for (int j = 0; j < UK; ++j) {
       float dot = 0.f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) dot += qv[e] * (float)kk[j][e];
-      dot = group_sum<LPR>(dot);
-      if (base + j * stride + gi < n_keys) {
-        const float mn = fmaxf(m, dot);
-        const float corr = __expf(m - mn);
-        const float p = __expf(dot - mn);
-        l = l * corr + p;
+      for (int e = 0; e < 4; ++e) dot += q0[e] * (float)kk[j][e] + q1[e] * (float)kk[j][4 + e];
+      dot = group_sum<LPR>(dot) * scale;
+      // no branch around the update: inside one the compiler sinks the value row's load to where it is
+      // used and waits for it there, a second memory round trip behind the first
+      const bool ok = base + j * stride + gi < n_keys;
+      const float mn = ok ? fmaxf(m, dot) : m;
+      const float corr = (m == mn) ? 1.0f : __expf(m - mn);     // also m = mn = -inf
+      const float p = ok ? __expf(dot - mn) : 0.f;
+      l = l * corr + p;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = acc[e] * corr + p * (float)vv[j][e];
-        m = mn;
-      }
+      for (int e = 0; e < 8; ++e) acc[e] = acc[e] * corr + p * (float)vv[j][e];
+      m = mn;
     }
-  }
-
+  };
+  // the first batch stands outside the loop: straight-line code, in which the wait for the query leaves
+  // the keys and values requested after it in flight (a loop header waits for everything)
+  const int base0 = (s * NW + wave) * GPW;
+  if (base0 < n_keys) batch(base0);
+  for (int base = base0 + stride * UK; base < n_keys; base += stride * UK) batch(base);
   // merge the lane groups of this wave: lanes with equal li hold the same columns
   {
     float M = m;
