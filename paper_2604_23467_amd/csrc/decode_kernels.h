@@ -110,81 +110,128 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
     }
   };
 
-  // The weight stream does not depend on the input vector: put the first
-  // loads of this wave's first row pair in flight before staging x, so HBM is
-  // already busy while the prologue runs.
   const int gw = blockIdx.x * (LL_WG / 64) + wave, GW = gridDim.x * (LL_WG / 64);
-  if (gw < P) {
-    select_rows(gw);
-    load_group(0);
-  }
 
   const float* xin = a.xin;
   if (MODE == GM_LMHEAD && a.x_row_from_prompt) xin += (size_t)(a.st->n_prompt - 1) * K;
 
+  // Staging of the input vector, four float4 per thread and pass, all of a pass's loads issued before
+  // any is used (one L2 round trip, not four).  For the O projection in two separate steps (loads;
+  // arithmetic and LDS writes) and branch-free (addresses clamped, values selected afterwards), so that
+  // the weight loads can be requested in between and the wait in front of the LDS writes leaves exactly
+  // them in flight.
   // O projection: its input is the merge of the attention kernel's (at most two) partials per
   // head, o = sum_s w_s acc_s with w_s = exp(m_s - M) / sum_s l_s exp(m_s - M).  Every thread
   // fetches the (m, l) headers next to the accumulators it stages and forms the weights
   // itself, so the whole merge costs one L2 round trip and no extra barrier.
-  // ... then the staging proper, four float4 per thread and pass with all of a
-  // pass's loads issued before any is used (one L2 round trip, not four).
-  float ss = 0.f;
   constexpr int SU = 4;
-  for (int i0 = tid; i0 < nchp * 128; i0 += LL_WG * SU) {
+  struct StageRegs {
     f4 v[SU], v2[SU];
     h4 g[SU];
-    float w0[SU], w1[SU];
     float2 hd0[SU], hd1[SU];     // (m, l) of the two partials
+  };
+  auto stage_load = [&](int i0, StageRegs& R) {
 #pragma unroll
     for (int j = 0; j < SU; ++j) {
       const int k = (i0 + j * LL_WG) * 4;
-      v[j] = f4{0.f, 0.f, 0.f, 0.f};
-      v2[j] = v[j];
-      g[j] = h4{0, 0, 0, 0};
-      w0[j] = w1[j] = 0.f;
-      if (k < K) {
-        if (MODE == GM_ORES && a.attn_part) {
-          // o[k..k+3] of head k / head_dim: the (at most two) partial accumulators
-          const int HD = a.head_dim, PS = ATTN_PART_STRIDE(HD);
-          const int head = k / HD, dcol = k - head * HD;
-          const float* hb = a.attn_part + (size_t)head * a.attn_splits * PS;
-          const float* hp = hb + 4 + dcol;
-          v[j] = *reinterpret_cast<const f4*>(hp);
-          hd0[j] = *reinterpret_cast<const float2*>(hb);
-          hd1[j] = make_float2(-INFINITY, 0.f);
-          if (a.attn_splits > 1) {
-            v2[j] = *reinterpret_cast<const f4*>(hp + PS);
-            hd1[j] = *reinterpret_cast<const float2*>(hb + PS);
-          }
-        } else {
-          v[j] = *reinterpret_cast<const f4*>(xin + k);
-        }
-        if (NORM) g[j] = *reinterpret_cast<const h4*>(a.gain + k);
+      const int kc = min(k, K - 4);                     // K % 8 == 0
+      if (MODE == GM_ORES) {
+        // o[k..k+3] of head k / head_dim: the (at most two) partial accumulators; without partials
+        // (long-context instances merge in a kernel of their own) the merged vector itself
+        const int HD = a.head_dim, PS = ATTN_PART_STRIDE(HD);
+        const int head = kc / HD, dcol = kc - head * HD;
+        const bool parts = a.attn_part != nullptr;
+        const float* hb = parts ? a.attn_part + (size_t)head * a.attn_splits * PS : xin;
+        const float* hp = parts ? hb + 4 + dcol : xin + kc;
+        const int second = (parts && a.attn_splits > 1) ? PS : 0;
+        R.v[j] = *reinterpret_cast<const f4*>(hp);
+        R.v2[j] = *reinterpret_cast<const f4*>(hp + second);
+        R.hd0[j] = *reinterpret_cast<const float2*>(hb);
+        R.hd1[j] = *reinterpret_cast<const float2*>(hb + second);
+      } else {
+        R.v[j] = *reinterpret_cast<const f4*>(xin + kc);
       }
+      if (NORM) R.g[j] = *reinterpret_cast<const h4*>(a.gain + kc);
     }
+  };
+  float ss = 0.f;
+  auto stage_store = [&](int i0, const StageRegs& R) {
 #pragma unroll
     for (int j = 0; j < SU; ++j) {
       const int k = (i0 + j * LL_WG) * 4;
       if (k >= nchp * 512) continue;
-      f4 t = v[j];
-      if (MODE == GM_ORES && a.attn_part && k < K) {
-        const float M = fmaxf(hd0[j].x, hd1[j].x);
-        const float e0 = (hd0[j].x > -INFINITY) ? __expf(hd0[j].x - M) : 0.f;
-        const float e1 = (hd1[j].x > -INFINITY) ? __expf(hd1[j].x - M) : 0.f;
-        const float rl = 1.0f / (hd0[j].y * e0 + hd1[j].y * e1);
-        w0[j] = e0 * rl;
-        w1[j] = e1 * rl;
-        t[0] = v[j][0] * w0[j] + v2[j][0] * w1[j];
-        t[1] = v[j][1] * w0[j] + v2[j][1] * w1[j];
-        t[2] = v[j][2] * w0[j] + v2[j][2] * w1[j];
-        t[3] = v[j][3] * w0[j] + v2[j][3] * w1[j];
+      f4 t = R.v[j];
+      if (MODE == GM_ORES) {
+        const bool parts = a.attn_part != nullptr, two = parts && a.attn_splits > 1;
+        const float m0 = R.hd0[j].x, m1 = two ? R.hd1[j].x : -INFINITY;
+        const float M = fmaxf(m0, m1);
+        const float e0 = (m0 > -INFINITY) ? __expf(m0 - M) : 0.f;
+        const float e1 = (m1 > -INFINITY) ? __expf(m1 - M) : 0.f;
+        const float rl = 1.0f / (R.hd0[j].y * e0 + (two ? R.hd1[j].y : 0.f) * e1);
+        const float w0 = parts ? e0 * rl : 1.0f, w1 = parts ? e1 * rl : 0.f;
+        t[0] = R.v[j][0] * w0 + R.v2[j][0] * w1;
+        t[1] = R.v[j][1] * w0 + R.v2[j][1] * w1;
+        t[2] = R.v[j][2] * w0 + R.v2[j][2] * w1;
+        t[3] = R.v[j][3] * w0 + R.v2[j][3] * w1;
       }
+      if (k >= K) t = f4{0.f, 0.f, 0.f, 0.f};          // padding up to a whole group of chunks
       if (NORM) {
         ss += t[0] * t[0] + t[1] * t[1] + t[2] * t[2] + t[3] * t[3];
-        t[0] *= (float)g[j][0]; t[1] *= (float)g[j][1]; t[2] *= (float)g[j][2]; t[3] *= (float)g[j][3];
+        t[0] *= (float)R.g[j][0]; t[1] *= (float)R.g[j][1]; t[2] *= (float)R.g[j][2]; t[3] *= (float)R.g[j][3];
       }
       const int c = k >> 9, r = k & 511;
       *reinterpret_cast<f4*>(lds + c * 512 + ((r >> 2) & 1) * 256 + (r >> 3) * 4) = t;
+    }
+  };
+
+  // Order of the first requests.  The weight stream does not depend on the input vector, and the time
+  // of these kernels is the time of that stream: the first loads of this wave's first row pair go out
+  // before anything else (measured: the staging loads in front of them cost 1 % of a step).  The O
+  // projection is the exception: at one row pair per wave those first loads are ALL of its weights, and
+  // loads return in order, so staging requested behind them would start only when the stream has ended;
+  // there the (small, cached) partials are requested first and merged while the weights arrive.
+  if constexpr (MODE == GM_ORES) {
+    StageRegs R;
+    stage_load(tid, R);
+    __builtin_amdgcn_sched_barrier(0);
+    select_rows(min(gw, P - 1));                       // a wave without a pair fetches the last one's start: no branch
+    load_group(0);
+    __builtin_amdgcn_sched_barrier(0);
+    stage_store(tid, R);
+    for (int i0 = tid + LL_WG * SU; i0 < nchp * 128; i0 += LL_WG * SU) {   // K > 4096
+      stage_load(i0, R);
+      stage_store(i0, R);
+    }
+  } else {
+    if (gw < P) {
+      select_rows(gw);
+      load_group(0);
+    }
+    for (int i0 = tid; i0 < nchp * 128; i0 += LL_WG * SU) {
+      f4 v[SU];
+      h4 g[SU];
+#pragma unroll
+      for (int j = 0; j < SU; ++j) {
+        const int k = (i0 + j * LL_WG) * 4;
+        v[j] = f4{0.f, 0.f, 0.f, 0.f};
+        g[j] = h4{0, 0, 0, 0};
+        if (k < K) {
+          v[j] = *reinterpret_cast<const f4*>(xin + k);
+          if (NORM) g[j] = *reinterpret_cast<const h4*>(a.gain + k);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < SU; ++j) {
+        const int k = (i0 + j * LL_WG) * 4;
+        if (k >= nchp * 512) continue;
+        f4 t = v[j];
+        if (NORM) {
+          ss += t[0] * t[0] + t[1] * t[1] + t[2] * t[2] + t[3] * t[3];
+          t[0] *= (float)g[j][0]; t[1] *= (float)g[j][1]; t[2] *= (float)g[j][2]; t[3] *= (float)g[j][3];
+        }
+        const int c = k >> 9, r = k & 511;
+        *reinterpret_cast<f4*>(lds + c * 512 + ((r >> 2) & 1) * 256 + (r >> 3) * 4) = t;
+      }
     }
   }
   if (NORM) {
