@@ -340,7 +340,7 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
 // (NSEG waves per pair, adjacent), the NSEG partial sums meet in LDS.  grid =
 // ceil(pairs / 4), one pass, no loop.
 template <int NSEG>
-__global__ __launch_bounds__(NSEG * 256, 2) void gemv_ksplit_kernel(GemvArgs a) {
+__global__ __launch_bounds__(NSEG * 256, 6) void gemv_ksplit_kernel(GemvArgs a) {
   extern __shared__ float lds[];
   constexpr int NT = NSEG * 256;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -358,9 +358,27 @@ __global__ __launch_bounds__(NSEG * 256, 2) void gemv_ksplit_kernel(GemvArgs a) 
   const half_t* pb = a.w0 + (size_t)rowB * K;
   const int gc0 = seg * cps;
 
+  // The input vector goes global -> LDS directly, requested BEFORE the weights.  This kernel requests all
+  // of its weights at once and loads return in order, so staging requested behind them would start only
+  // when the weight stream has ended; in front of them it needs no registers (16-byte direct loads, lane
+  // l of half-chunk (c, f) fetching x[c * 512 + l * 8 + 4 f ..], which is exactly the lane-major layout
+  // the dot products read) and is over long before the first weights arrive.
+  constexpr int XL = (22 * 2 + NT / 64 - 1) / (NT / 64);      // direct loads per wave for K <= 11264
+  const bool direct = nch <= 22;
+  if (direct) {
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+      const int c2 = wave + i * (NT / 64);                     // wave-uniform
+      if (c2 >= 2 * nch) break;
+      const int c = c2 >> 1, f = c2 & 1;
+      const int k = min(c * 512 + lane * 8 + 4 * f, K - 4);    // ragged tail: clamped here, zeroed below
+      __builtin_amdgcn_global_load_lds((const LL_GLOBAL void*)(a.xin + k),
+                                       (__attribute__((address_space(3))) void*)(lds + c * 512 + f * 256), 16, 0, 0);
+    }
+  }
   h8 wa[8], wb[8];
 #pragma unroll
-  for (int u = 0; u < 8; ++u) {   // in flight before the input vector is staged
+  for (int u = 0; u < 8; ++u) {
     const int k = min((gc0 + u) * 512 + lane * 8, K - 8);
     wa[u] = load_stream(pa + k);
     wb[u] = load_stream(pb + k);
@@ -369,14 +387,31 @@ __global__ __launch_bounds__(NSEG * 256, 2) void gemv_ksplit_kernel(GemvArgs a) 
   float pre0 = 0.f, pre1 = 0.f;
   if (valid && seg == 0 && lane == 0) { pre0 = *as_global(a.out + rowA); pre1 = *as_global(a.out + rowB); }
 
-  for (int i = tid; i < (nch + 1) * 128; i += NT) {   // chunk nch stays zero
-    const int k = i * 4;
-    f4 v = {0.f, 0.f, 0.f, 0.f};
-    if (k < K) v = *reinterpret_cast<const f4*>(a.xin + k);
-    const int c = k >> 9, r = k & 511;
-    *reinterpret_cast<f4*>(lds + c * 512 + ((r >> 2) & 1) * 256 + (r >> 3) * 4) = v;
+  if (direct) {
+    wait_vm_at_most<16>();          // the direct loads have landed; the 16 weight loads behind them may be in flight
+    asm volatile("" ::: "memory");
+    // zeros: chunk nch, and what lies beyond K in the last chunk (written by the wave that loaded there)
+    for (int i = tid; i < 128; i += NT) *reinterpret_cast<f4*>(lds + nch * 512 + i * 4) = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+      const int c2 = wave + i * (NT / 64);
+      const int c = c2 >> 1, f = c2 & 1;
+      if (c2 < 2 * nch && c * 512 + lane * 8 + 4 * f >= K)
+        *reinterpret_cast<f4*>(lds + c * 512 + f * 256 + lane * 4) = f4{0.f, 0.f, 0.f, 0.f};
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();    // bare: __syncthreads() would wait for the weights
+    asm volatile("" ::: "memory");
+  } else {
+    for (int i = tid; i < (nch + 1) * 128; i += NT) {   // chunk nch stays zero
+      const int k = i * 4;
+      f4 v = {0.f, 0.f, 0.f, 0.f};
+      if (k < K) v = *reinterpret_cast<const f4*>(a.xin + k);
+      const int c = k >> 9, r = k & 511;
+      *reinterpret_cast<f4*>(lds + c * 512 + ((r >> 2) & 1) * 256 + (r >> 3) * 4) = v;
+    }
+    __syncthreads();
   }
-  __syncthreads();
 
   float accA = 0.f, accB = 0.f;
 #pragma unroll

@@ -116,6 +116,13 @@ __device__ __forceinline__ void st_dev_u(unsigned* p, unsigned v) {
 __device__ __forceinline__ h8 load_stream(const half_t* p) {
   return __builtin_nontemporal_load(as_global(reinterpret_cast<const h8*>(p)));
 }
+// s_waitcnt vmcnt(N) (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the export and LDS counters
+// left at "no wait")
+template <int N>
+__device__ __forceinline__ void wait_vm_at_most() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | 0x70 | 0xF00 | ((N >> 4) << 14));
+}
+
 // plain 16-byte load from global memory
 __device__ __forceinline__ h8 load_h8(const half_t* p) {
   return *as_global(reinterpret_cast<const h8*>(p));

@@ -57,12 +57,6 @@ struct GemmArgs {
 #define PF_GEMM_LDS_BYTES(BM, NS, BK) ((NS) * ((BM) + PF_BN) * (BK) * 2)
 #define PF_GEMM_THREADS_OF(WM, WN) ((WM) * (WN) * 64)
 
-// s_waitcnt vmcnt(N) (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the export and LDS counters
-// left at "no wait")
-template <int N>
-__device__ __forceinline__ void wait_vm_at_most() {
-  __builtin_amdgcn_s_waitcnt((N & 15) | 0x70 | 0xF00 | ((N >> 4) << 14));
-}
 
 // BM x 256 tile, WM x WN waves of (BM / WM) x (256 / WN) each, NS ring stages of BK-wide slabs.
 //   <128, 3, 2, 4, 64>  8 waves of 64 x 64: prompts of 65..255 rows
