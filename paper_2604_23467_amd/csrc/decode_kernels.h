@@ -202,6 +202,43 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
       stage_load(i0, R);
       stage_store(i0, R);
     }
+  } else if constexpr (MODE == GM_QKV || MODE == GM_GATEUP) {
+    // Normalising projections of a layer (the LM head, with many row pairs per wave, measured no gain):
+    // the raw vector and the gains go global -> LDS directly (no registers), requested in front of the
+    // weights, each wave its own chunks; when they have landed (the weight
+    // loads behind them stay in flight) the same lanes multiply the gains in, in place, and add up the
+    // squares.  The prologue thus never waits for the weight stream's first loads.
+    half_t* gl = reinterpret_cast<half_t*>(red + 16);
+    for (int c = wave; c < nch; c += LL_WG / 64) {
+      const int k = min(c * 512 + lane * 8, K - 8);            // K % 8 == 0: a lane's 8 elements are all in or all out
+      __builtin_amdgcn_global_load_lds((const LL_GLOBAL void*)(xin + k),
+                                       (__attribute__((address_space(3))) void*)(lds + c * 512), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const LL_GLOBAL void*)(xin + k + 4),
+                                       (__attribute__((address_space(3))) void*)(lds + c * 512 + 256), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const LL_GLOBAL void*)(a.gain + k),
+                                       (__attribute__((address_space(3))) void*)(gl + c * 512), 16, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    select_rows(min(gw, P - 1));          // unconditional: the wait below counts on 16 younger loads in every wave
+    load_group(0);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vm_at_most<16>();
+    asm volatile("" ::: "memory");
+    for (int c = wave; c < nchp; c += LL_WG / 64) {
+      float* xp = lds + c * 512 + lane * 4;
+      f4 x0 = {0.f, 0.f, 0.f, 0.f}, x1 = x0;
+      if (c < nch && c * 512 + lane * 8 < K) {
+        x0 = *reinterpret_cast<const f4*>(xp);
+        x1 = *reinterpret_cast<const f4*>(xp + 256);
+        const h8 gv = *reinterpret_cast<const h8*>(gl + c * 512 + lane * 8);
+        ss += x0[0] * x0[0] + x0[1] * x0[1] + x0[2] * x0[2] + x0[3] * x0[3] +
+              x1[0] * x1[0] + x1[1] * x1[1] + x1[2] * x1[2] + x1[3] * x1[3];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { x0[e] *= (float)gv[e]; x1[e] *= (float)gv[4 + e]; }
+      }
+      *reinterpret_cast<f4*>(xp) = x0;                          // also the zero padding beyond K and up to nchp chunks
+      *reinterpret_cast<f4*>(xp + 256) = x1;
+    }
   } else {
     if (gw < P) {
       select_rows(gw);

@@ -357,10 +357,11 @@ struct Instance {
 
 Instance* g = nullptr;
 
-size_t gemv_lds_bytes(int K) {
+size_t gemv_lds_bytes(int K, bool norm) {
   const int nch = (K + 511) / 512;
   const int nchp = (nch + kGemvU - 1) / kGemvU * kGemvU;
-  return ((size_t)nchp * 512 + 8) * sizeof(float);   // input vector, reduction scratch
+  // input vector, reduction scratch, and for the normalising projections the staged gains
+  return ((size_t)nchp * 512 + 16) * sizeof(float) + (norm ? (size_t)nch * 512 * sizeof(half_t) : 0);
 }
 
 struct ProfScope {
@@ -388,7 +389,8 @@ struct ProfScope {
 template <int MODE>
 void launch_gemv(const GemvArgs& a, int pairs, int grid_override, hipStream_t s) {
   const int grid = grid_override > 0 ? grid_override : gemv_grid(pairs);
-  hipLaunchKernelGGL((gemv_kernel<MODE, kGemvU>), dim3(grid), dim3(LL_WG), gemv_lds_bytes(a.K), s, a);
+  hipLaunchKernelGGL((gemv_kernel<MODE, kGemvU>), dim3(grid), dim3(LL_WG),
+                     gemv_lds_bytes(a.K, MODE == GM_QKV || MODE == GM_GATEUP || MODE == GM_LMHEAD), s, a);
 }
 
 // final RMSNorm + LM head + argmax + state advance, shared by decode and prefill
@@ -1031,7 +1033,7 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
     return fail(LL_E_WORKSPACE, "ll_init: workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign)
     return fail(LL_E_WORKSPACE, "ll_init: workspace must be %zu-byte aligned", kAlign);
-  if (gemv_lds_bytes(cfg->ffn_hidden) > 64 * 1024 || gemv_lds_bytes(cfg->d_model) > 64 * 1024)
+  if (gemv_lds_bytes(cfg->ffn_hidden, false) > 64 * 1024 || gemv_lds_bytes(cfg->d_model, true) > 64 * 1024)
     return fail(LL_E_BAD_CONFIG, "ll_init: d_model / ffn_hidden too large for the LDS-staged GEMV (at most 12288)");
   if (cfg->n_heads > 256)
     return fail(LL_E_BAD_CONFIG, "ll_init: n_heads = %d, at most 256 (two attention workgroups per head)", cfg->n_heads);
