@@ -12,6 +12,7 @@
 #include "ll_device.h"
 
 #define ATTN_THREADS 1024
+#define ATTN_MERGE_MAX 4     // attention partials per head that the O projection's prologue merges
 #define ATTN_PART_STRIDE(HD) ((HD) + 4)   // floats per attention partial: m, l, 2 pad, acc[HD] (16-byte aligned)
 
 enum GemvMode { GM_QKV = 0, GM_ORES = 1, GM_GATEUP = 2, GM_DOWN = 3, GM_LMHEAD = 4 };
@@ -54,9 +55,13 @@ struct GemvArgs {
 //   others  rows (2p, 2p+1)
 // RMSNorm is folded in as y = (W (x*g)) * rsqrt(mean(x^2)+eps): the scalar
 // factor multiplies the accumulator, so the weight stream never waits for it.
+// Threads per workgroup: the O projection, whose every workgroup merges all of the attention partials
+// while it stages them, runs workgroups of 8 waves (half as many stagings for the same row pairs)
+#define GEMV_WG(MODE) ((MODE) == GM_ORES ? 2 * LL_WG : LL_WG)
 template <int MODE, int U>
-__global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
+__global__ __launch_bounds__(GEMV_WG(MODE)) void gemv_kernel(GemvArgs a) {
   extern __shared__ float lds[];
+  constexpr int WG = GEMV_WG(MODE);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int K = a.K;
   const int nch = (K + 511) >> 9;
@@ -110,7 +115,7 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
     }
   };
 
-  const int gw = blockIdx.x * (LL_WG / 64) + wave, GW = gridDim.x * (LL_WG / 64);
+  const int gw = blockIdx.x * (WG / 64) + wave, GW = gridDim.x * (WG / 64);
 
   const float* xin = a.xin;
   if (MODE == GM_LMHEAD && a.x_row_from_prompt) xin += (size_t)(a.st->n_prompt - 1) * K;
@@ -120,65 +125,62 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
   // arithmetic and LDS writes) and branch-free (addresses clamped, values selected afterwards), so that
   // the weight loads can be requested in between and the wait in front of the LDS writes leaves exactly
   // them in flight.
-  // O projection: its input is the merge of the attention kernel's (at most two) partials per
+  // O projection: its input is the merge of the attention kernel's (at most ATTN_MERGE_MAX) partials per
   // head, o = sum_s w_s acc_s with w_s = exp(m_s - M) / sum_s l_s exp(m_s - M).  Every thread
   // fetches the (m, l) headers next to the accumulators it stages and forms the weights
   // itself, so the whole merge costs one L2 round trip and no extra barrier.
   constexpr int SU = 4;
+  constexpr int MP = MODE == GM_ORES ? ATTN_MERGE_MAX : 1;    // partials merged in the prologue
   struct StageRegs {
-    f4 v[SU], v2[SU];
-    h4 g[SU];
-    float2 hd0[SU], hd1[SU];     // (m, l) of the two partials
+    f4 v[MP][SU];
+    float2 hd[MP][SU];           // (m, l) of the partials
   };
   auto stage_load = [&](int i0, StageRegs& R) {
 #pragma unroll
     for (int j = 0; j < SU; ++j) {
-      const int k = (i0 + j * LL_WG) * 4;
+      const int k = (i0 + j * WG) * 4;
       const int kc = min(k, K - 4);                     // K % 8 == 0
-      if (MODE == GM_ORES) {
-        // o[k..k+3] of head k / head_dim: the (at most two) partial accumulators; without partials
-        // (long-context instances merge in a kernel of their own) the merged vector itself
-        const int HD = a.head_dim, PS = ATTN_PART_STRIDE(HD);
-        const int head = kc / HD, dcol = kc - head * HD;
-        const bool parts = a.attn_part != nullptr;
-        const float* hb = parts ? a.attn_part + (size_t)head * a.attn_splits * PS : xin;
-        const float* hp = parts ? hb + 4 + dcol : xin + kc;
-        const int second = (parts && a.attn_splits > 1) ? PS : 0;
-        R.v[j] = *reinterpret_cast<const f4*>(hp);
-        R.v2[j] = *reinterpret_cast<const f4*>(hp + second);
-        R.hd0[j] = *reinterpret_cast<const float2*>(hb);
-        R.hd1[j] = *reinterpret_cast<const float2*>(hb + second);
-      } else {
-        R.v[j] = *reinterpret_cast<const f4*>(xin + kc);
+      // o[k..k+3] of head k / head_dim: the partial accumulators; without partials (long-context
+      // instances merge in a kernel of their own) the merged vector itself
+      const int HD = a.head_dim, PS = ATTN_PART_STRIDE(HD);
+      const int head = kc / HD, dcol = kc - head * HD;
+      const bool parts = a.attn_part != nullptr;
+      const float* hb = parts ? a.attn_part + (size_t)head * a.attn_splits * PS : xin;
+      const float* hp = parts ? hb + 4 + dcol : xin + kc;
+#pragma unroll
+      for (int sp = 0; sp < MP; ++sp) {
+        const int off = parts ? min(sp, a.attn_splits - 1) * PS : 0;    // a missing partial re-reads the last one
+        R.v[sp][j] = *reinterpret_cast<const f4*>(hp + off);
+        R.hd[sp][j] = *reinterpret_cast<const float2*>(hb + off);
       }
-      if (NORM) R.g[j] = *reinterpret_cast<const h4*>(a.gain + kc);
     }
   };
   float ss = 0.f;
   auto stage_store = [&](int i0, const StageRegs& R) {
 #pragma unroll
     for (int j = 0; j < SU; ++j) {
-      const int k = (i0 + j * LL_WG) * 4;
+      const int k = (i0 + j * WG) * 4;
       if (k >= nchp * 512) continue;
-      f4 t = R.v[j];
-      if (MODE == GM_ORES) {
-        const bool parts = a.attn_part != nullptr, two = parts && a.attn_splits > 1;
-        const float m0 = R.hd0[j].x, m1 = two ? R.hd1[j].x : -INFINITY;
-        const float M = fmaxf(m0, m1);
-        const float e0 = (m0 > -INFINITY) ? __expf(m0 - M) : 0.f;
-        const float e1 = (m1 > -INFINITY) ? __expf(m1 - M) : 0.f;
-        const float rl = 1.0f / (R.hd0[j].y * e0 + (two ? R.hd1[j].y : 0.f) * e1);
-        const float w0 = parts ? e0 * rl : 1.0f, w1 = parts ? e1 * rl : 0.f;
-        t[0] = R.v[j][0] * w0 + R.v2[j][0] * w1;
-        t[1] = R.v[j][1] * w0 + R.v2[j][1] * w1;
-        t[2] = R.v[j][2] * w0 + R.v2[j][2] * w1;
-        t[3] = R.v[j][3] * w0 + R.v2[j][3] * w1;
+      const bool parts = a.attn_part != nullptr;
+      const int np = parts ? a.attn_splits : 0;
+      float M = -INFINITY;
+#pragma unroll
+      for (int sp = 0; sp < MP; ++sp) M = fmaxf(M, sp < np ? R.hd[sp][j].x : -INFINITY);
+      float e[MP], den = 0.f;
+#pragma unroll
+      for (int sp = 0; sp < MP; ++sp) {
+        const float m = R.hd[sp][j].x;
+        e[sp] = (sp < np && m > -INFINITY) ? __expf(m - M) : 0.f;
+        den += R.hd[sp][j].y * e[sp];
+      }
+      const float rl = 1.0f / den;
+      f4 t = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int sp = 0; sp < MP; ++sp) {
+        const float w = parts ? e[sp] * rl : (sp == 0 ? 1.0f : 0.f);
+        t[0] += R.v[sp][j][0] * w; t[1] += R.v[sp][j][1] * w; t[2] += R.v[sp][j][2] * w; t[3] += R.v[sp][j][3] * w;
       }
       if (k >= K) t = f4{0.f, 0.f, 0.f, 0.f};          // padding up to a whole group of chunks
-      if (NORM) {
-        ss += t[0] * t[0] + t[1] * t[1] + t[2] * t[2] + t[3] * t[3];
-        t[0] *= (float)R.g[j][0]; t[1] *= (float)R.g[j][1]; t[2] *= (float)R.g[j][2]; t[3] *= (float)R.g[j][3];
-      }
       const int c = k >> 9, r = k & 511;
       *reinterpret_cast<f4*>(lds + c * 512 + ((r >> 2) & 1) * 256 + (r >> 3) * 4) = t;
     }
@@ -198,7 +200,7 @@ __global__ __launch_bounds__(LL_WG) void gemv_kernel(GemvArgs a) {
     load_group(0);
     __builtin_amdgcn_sched_barrier(0);
     stage_store(tid, R);
-    for (int i0 = tid + LL_WG * SU; i0 < nchp * 128; i0 += LL_WG * SU) {   // K > 4096
+    for (int i0 = tid + WG * SU; i0 < nchp * 128; i0 += WG * SU) {   // K > 4096 (8192 with 8 waves)
       stage_load(i0, R);
       stage_store(i0, R);
     }
@@ -487,26 +489,29 @@ __global__ __launch_bounds__(LL_WG) void embed_kernel(const half_t* __restrict__
 
 // Split-K attention of the one new query against keys 0..pos of one head.
 //
-// grid = (heads, S), 1024 threads.  A key row (HD halves) is read by HD/8
+// grid = (heads, S), NTHR threads.  A key row (HD halves) is read by HD/8
 // adjacent lanes with one 16-byte load each, so a wave covers 64/(HD/8)
 // consecutive keys per load.  Every such lane group keeps its own
 // online-softmax state (running max m, denominator l, 8 output columns per
 // lane) over the keys it is dealt, round robin over all groups of all S
 // workgroups of the head -- the grid is fixed and the key range comes from
-// DevState, so the same captured launch serves every KV length.  With S = 2
-// and 8 keys in flight per group one pass covers 1024 keys.  Groups merge
-// inside the wave by shuffles, waves through LDS; the S partials (m, l,
-// acc[HD]) of a head are merged by the consumer, the O-projection's prologue,
-// which costs it 2 x 130 floats per head and saves this kernel a cross-
-// workgroup hand-off (stores -> counter -> reload: about 5 us of pure latency).
+// DevState, so the same captured launch serves every KV length.  With S = 4
+// workgroups of 512 threads and 8 keys in flight per group one pass covers
+// 1024 keys, and a CU has at most 128 KB of key and value rows to pull (a CU
+// takes about 140 GB/s: with two workgroups of 1024 threads per head the kernel
+// grew by 0.8 us per 440 keys).  Groups merge inside the wave by shuffles,
+// waves through LDS; the S <= ATTN_MERGE_MAX partials (m, l, acc[HD]) of a head
+// are merged by the consumer, the O-projection's prologue, underneath its weight
+// stream, which saves this kernel a cross-workgroup hand-off (stores -> counter
+// -> reload: about 5 us of pure latency).
 
-template <int HD>
-__global__ __launch_bounds__(ATTN_THREADS) void attn_decode_kernel(
+template <int HD, int NTHR = ATTN_THREADS>
+__global__ __launch_bounds__(NTHR) void attn_decode_kernel(
     const float* __restrict__ q, const half_t* __restrict__ kc, const half_t* __restrict__ vc,
     const DevState* __restrict__ st, float* __restrict__ part, int max_seq) {
   constexpr int LPR = HD / 8;      // lanes per key row
   constexpr int GPW = 64 / LPR;    // lane groups per wave
-  constexpr int NW = ATTN_THREADS / 64;
+  constexpr int NW = NTHR / 64;
   constexpr int UK = 8;            // keys in flight per group
   constexpr int PS = ATTN_PART_STRIDE(HD);
   __shared__ float s_m[NW], s_l[NW], s_acc[NW][HD];
@@ -601,26 +606,6 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_decode_kernel(
     if (tid == 0) { mypart[0] = M; mypart[1] = L; }
     mypart[4 + tid] = A;
   }
-}
-
-// Merge of S > 2 attention partials of a head into o[head] (long-context instances only; with
-// two partials the O projection merges them while it stages its input).  grid = heads, HD threads.
-__global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict__ part, float* __restrict__ o,
-                                                         int S, int HD) {
-  const int h = blockIdx.x, t = threadIdx.x;
-  if (t >= HD) return;
-  const int PS = ATTN_PART_STRIDE(HD);
-  const float* hb = part + (size_t)h * S * PS;
-  float M = -INFINITY;
-  for (int sp = 0; sp < S; ++sp) M = fmaxf(M, hb[sp * PS]);
-  float L = 0.f, A = 0.f;
-  for (int sp = 0; sp < S; ++sp) {
-    const float mi = hb[sp * PS];
-    const float w = (mi > -INFINITY) ? __expf(mi - M) : 0.f;
-    L += hb[sp * PS + 1] * w;
-    A += hb[sp * PS + 4 + t] * w;
-  }
-  o[(size_t)h * HD + t] = A / L;
 }
 
 // Attention and O projection of one layer in ONE launch: x += W_o * attention(q, K, V).

@@ -155,23 +155,29 @@ struct Layout {
   size_t wf;                // fragment-major copy of the projection weights for the short-prompt kernels (0 bytes without it)
   size_t wf_qkv, wf_o, wf_gu, wf_down, wf_layer, wf_lm;   // offsets inside a layer's part, bytes per layer, offset of the LM head's copy
   size_t total;
-  int attn_splits, lm_wgs, max_prompt, mb_max;
+  int attn_splits, attn_threads, lm_wgs, max_prompt, mb_max;
   size_t kv_layer_halves;   // halves per layer per K or V
 };
 
-int gemv_grid(int pairs) {
+int gemv_grid(int pairs, int wg_threads = LL_WG) {
   // a few workgroups per CU keep enough 16-byte loads in flight; never more waves than row pairs
-  const int want = num_cus() * kGemvWgsPerCu;
-  const int need = (pairs + (LL_WG / 64) - 1) / (LL_WG / 64);
+  const int want = num_cus() * kGemvWgsPerCu * LL_WG / wg_threads;
+  const int need = (pairs + (wg_threads / 64) - 1) / (wg_threads / 64);
   return need < want ? (need < 1 ? 1 : need) : want;
 }
 
 Layout make_layout(const ll_config& c) {
   Layout L{};
   const size_t d = c.d_model, F = c.ffn_hidden, V = c.vocab;
-  // 1024-thread workgroups per head: two (merged for free by the O projection) up to 2 K
-  // positions, four plus a small merge kernel in long-context instances (measured best of 2..16)
-  L.attn_splits = c.n_heads * 2 > 512 ? 1 : c.max_seq <= 2048 ? 2 : 4;
+  // Workgroups per head of the decode attention: four, of 512 threads up to 2 K positions and of 1024
+  // threads in long-context instances (two of 1024 when attention and O projection run as one launch,
+  // which takes at most two).  Their partials are merged by the O projection's prologue underneath its
+  // weight stream.  Measured at the 7B shape: 4 x 512 against 2 x 1024 threads 6.2 against 7.5 us per layer
+  // at 500..800 keys; against a merge kernel of its own in a max_seq 4096 instance 2.57 / 2.62 / 2.81 ms
+  // against 2.64 / 2.70 / 2.90 ms per step at 1000 / 2000 / 4000 keys.
+  const bool fused = (c.flags & LL_FLAG_FUSED_ATTN_OPROJ) != 0;
+  L.attn_splits = c.n_heads * 2 > 512 ? 1 : (c.max_seq <= 2048 && fused) ? 2 : 4;
+  L.attn_threads = (c.max_seq <= 2048 && L.attn_splits == 4) ? 512 : ATTN_THREADS;
   L.lm_wgs = gemv_grid((c.vocab + 1) / 2);
   L.max_prompt = c.max_seq - 1;                   // longer than the largest bucket: fed in chunks
   L.mb_max = prompt_bucket(L.max_prompt < kMaxPromptBucket ? L.max_prompt : kMaxPromptBucket);
@@ -388,8 +394,8 @@ struct ProfScope {
 
 template <int MODE>
 void launch_gemv(const GemvArgs& a, int pairs, int grid_override, hipStream_t s) {
-  const int grid = grid_override > 0 ? grid_override : gemv_grid(pairs);
-  hipLaunchKernelGGL((gemv_kernel<MODE, kGemvU>), dim3(grid), dim3(LL_WG),
+  const int grid = grid_override > 0 ? grid_override : gemv_grid(pairs, GEMV_WG(MODE));
+  hipLaunchKernelGGL((gemv_kernel<MODE, kGemvU>), dim3(grid), dim3(GEMV_WG(MODE)),
                      gemv_lds_bytes(a.K, MODE == GM_QKV || MODE == GM_GATEUP || MODE == GM_LMHEAD), s, a);
 }
 
@@ -469,21 +475,24 @@ void enqueue_decode_multi(Instance* I, hipStream_t s) {
     if (I->runs(LL_KC_ATTN)) {
       ProfScope ps(I, s, LL_KC_ATTN);
       dim3 grid(c.n_heads, I->L.attn_splits);
-      if (c.head_dim == 128)
+      if (c.head_dim == 128 && I->L.attn_threads == 512)
+        hipLaunchKernelGGL((attn_decode_kernel<128, 512>), grid, dim3(512), 0, s, q, I->kcache(l),
+                           I->vcache(l), I->state(), I->at<float>(I->L.attn_part), c.max_seq);
+      else if (c.head_dim == 128)
         hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(ATTN_THREADS), 0, s, q, I->kcache(l),
+                           I->vcache(l), I->state(), I->at<float>(I->L.attn_part), c.max_seq);
+      else if (I->L.attn_threads == 512)
+        hipLaunchKernelGGL((attn_decode_kernel<64, 512>), grid, dim3(512), 0, s, q, I->kcache(l),
                            I->vcache(l), I->state(), I->at<float>(I->L.attn_part), c.max_seq);
       else
         hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(ATTN_THREADS), 0, s, q, I->kcache(l),
                            I->vcache(l), I->state(), I->at<float>(I->L.attn_part), c.max_seq);
-      if (I->L.attn_splits > 2)
-        hipLaunchKernelGGL(attn_merge_kernel, dim3(c.n_heads), dim3(128), 0, s, I->at<float>(I->L.attn_part), o,
-                           I->L.attn_splits, c.head_dim);
     }
     if (I->runs(LL_KC_OPROJ)) {
       ProfScope ps(I, s, LL_KC_OPROJ);
       GemvArgs a{};
       a.w0 = (const half_t*)W.wo; a.xin = o; a.out = x; a.N = d; a.K = d;
-      if (I->L.attn_splits <= 2) a.attn_part = I->at<float>(I->L.attn_part);   // else o holds the merged heads
+      a.attn_part = I->at<float>(I->L.attn_part);
       a.attn_splits = I->L.attn_splits; a.head_dim = c.head_dim;
       launch_gemv<GM_ORES>(a, d / 2, 0, s);
     }
