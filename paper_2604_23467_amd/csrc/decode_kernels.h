@@ -129,7 +129,7 @@ __global__ __launch_bounds__(GEMV_WG(MODE)) void gemv_kernel(GemvArgs a) {
   // head, o = sum_s w_s acc_s with w_s = exp(m_s - M) / sum_s l_s exp(m_s - M).  Every thread
   // fetches the (m, l) headers next to the accumulators it stages and forms the weights
   // itself, so the whole merge costs one L2 round trip and no extra barrier.
-  constexpr int SU = 4;
+  constexpr int SU = MODE == GM_ORES ? 2 : 4;      // 512 threads x 2 x 4 elements cover d_model 4096 in one pass
   constexpr int MP = MODE == GM_ORES ? ATTN_MERGE_MAX : 1;    // partials merged in the prologue
   struct StageRegs {
     f4 v[MP][SU];
