@@ -22,12 +22,12 @@ struct BatchState {
 };
 
 // Attention of slot b's new query (position pos[b], already written to the cache) for one head.
-// grid = (heads, rows of the step = 16 or 32), 1024 threads (256 keys in flight: a 500-key sequence
-// takes two trips); tb = rows / 16 selects the output's fragment-major layout.  As in the single-sequence kernel a key row is read
+// grid = (heads, rows of the step = 16 or 32), 512 threads (two workgroups per CU; two trips of 128 keys
+// in flight); tb = rows / 16 selects the output's fragment-major layout.  As in the single-sequence kernel a key row is read
 // by HD / 8 adjacent lanes with one 16-byte load each and every lane group keeps an online-softmax
 // state over the keys it is dealt; groups merge by shuffles, waves through LDS.  Output: fp16,
 // in the fragment-major operand layout of the O projection.
-#define BT_ATTN_THREADS 1024
+#define BT_ATTN_THREADS 512
 template <int HD>
 __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
     const half_t* __restrict__ Q, const half_t* __restrict__ kc, const half_t* __restrict__ vc,
@@ -42,13 +42,16 @@ __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
   const int h = blockIdx.x, b = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int gi = lane / LPR, li = lane % LPR;
-  if (!bs->active[b]) {
+  // One round trip for everything the key loop needs: the slot's state, the query and the WHOLE page-table
+  // row (entries past the sequence's end are not used; reading them saves waiting for the position first).
+  const int active = bs->active[b];
+  const int n_keys = bs->pos[b] + 1;
+  const h8 q = load_h8(Q + (size_t)b * d + h * HD + li * 8);
+  for (int i = tid; i < pt_stride; i += BT_ATTN_THREADS) s_pt[i] = page_table[b * pt_stride + i];
+  if (!active) {
     if (tid < HD / 8) *reinterpret_cast<h8*>(O + act_offset(b, h * HD + tid * 8, d, tb)) = h8{0, 0, 0, 0, 0, 0, 0, 0};
     return;
   }
-  const int n_keys = bs->pos[b] + 1;
-  const h8 q = load_h8(Q + (size_t)b * d + h * HD + li * 8);   // requested ahead of the page table: one round trip for both
-  for (int i = tid; i * page_tokens < n_keys; i += BT_ATTN_THREADS) s_pt[i] = page_table[b * pt_stride + i];
   __syncthreads();
   const float scale = 1.0f / sqrtf((float)HD);
   float qv[8];
@@ -60,9 +63,12 @@ __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
   float m = -INFINITY, l = 0.f, acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-  constexpr int STRIDE = NW * GPW;
-  for (int base = wave * GPW; base < n_keys; base += STRIDE * UK) {
-    h8 kk[UK], vv[UK];
+  constexpr int STRIDE = NW * GPW, TRIP = STRIDE * UK;     // keys one trip of the workgroup covers
+  // Trips are double-buffered: the requests of trip t + 1 go out before trip t is used, so a long sequence
+  // costs one memory round trip plus the arithmetic of its trips, not a round trip per trip.  A trip past
+  // the sequence's end is still requested (every key clamped to the last one: cache hits), which keeps
+  // the number of loads in flight the same on every path and the waits exact.
+  auto issue = [&](int base, h8 (&kk)[UK], h8 (&vv)[UK]) {
 #pragma unroll
     for (int j = 0; j < UK; ++j) {
       const int u = min(base + j * STRIDE + gi, n_keys - 1);
@@ -71,23 +77,45 @@ __global__ __launch_bounds__(BT_ATTN_THREADS) void bt_attn_kernel(
       kk[j] = load_stream(kh + row * HD);
       vv[j] = load_stream(vh + row * HD);
     }
-    __builtin_amdgcn_sched_barrier(0);     // all requests out before the first use
+  };
+  // One online-softmax step per trip, not per key: the trip's scores first, then one new maximum, one
+  // correction of the running state and one exponential per key (branch-free: inside a branch the
+  // compiler sinks a value row's load to its use and waits for it there).
+  auto consume = [&](int base, const h8 (&kk)[UK], const h8 (&vv)[UK]) {
+    float dot[UK], mn = m;
 #pragma unroll
     for (int j = 0; j < UK; ++j) {
-      float dot = 0.f;
+      float t = 0.f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) dot += qv[e] * (float)kk[j][e];
-      dot = group_sum<LPR>(dot);
-      // branch-free, as in attn_decode_kernel: a branch here makes the compiler sink a value row's load into it
-      const bool ok = base + j * STRIDE + gi < n_keys;
-      const float mn = ok ? fmaxf(m, dot) : m;
-      const float corr = (m == mn) ? 1.0f : __expf(m - mn);
-      const float p = ok ? __expf(dot - mn) : 0.f;
-      l = l * corr + p;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] = acc[e] * corr + p * (float)vv[j][e];
-      m = mn;
+      for (int e = 0; e < 8; ++e) t += qv[e] * (float)kk[j][e];
+      t = group_sum<LPR>(t);
+      dot[j] = (base + j * STRIDE + gi < n_keys) ? t : -INFINITY;
+      mn = fmaxf(mn, dot[j]);
     }
+    const float corr = (m == mn) ? 1.0f : __expf(m - mn);     // also m = mn = -inf
+    l *= corr;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] *= corr;
+#pragma unroll
+    for (int j = 0; j < UK; ++j) {
+      const float p = (dot[j] > -INFINITY) ? __expf(dot[j] - mn) : 0.f;
+      l += p;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += p * (float)vv[j][e];
+    }
+    m = mn;
+  };
+  h8 ka[UK], va[UK], kb[UK], vb[UK];
+  issue(wave * GPW, ka, va);
+  for (int base = wave * GPW; base < n_keys; base += 2 * TRIP) {
+    issue(base + TRIP, kb, vb);
+    __builtin_amdgcn_sched_barrier(0);
+    consume(base, ka, va);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(base + 2 * TRIP, ka, va);
+    __builtin_amdgcn_sched_barrier(0);
+    consume(base + TRIP, kb, vb);
+    __builtin_amdgcn_sched_barrier(0);
   }
   {
     float M = m;
