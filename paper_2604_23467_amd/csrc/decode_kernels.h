@@ -543,23 +543,31 @@ __global__ __launch_bounds__(NTHR) void attn_decode_kernel(
       vv[j] = load_stream(vh + (size_t)u * HD);
     }
     __builtin_amdgcn_sched_barrier(0);     // all 16 requests out before the first use: one round trip, not several
+    // One online-softmax step per batch, not per key: the batch's scores, one new maximum, one correction
+    // of the running state, one exponential per key.  No branch around any of it: inside one the compiler
+    // sinks a value row's load to where it is used and waits for it there, a second round trip behind the first.
+    float dot[UK], mn = m;
 #pragma unroll
     for (int j = 0; j < UK; ++j) {
-      float dot = 0.f;
+      float t = 0.f;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) dot += q0[e] * (float)kk[j][e] + q1[e] * (float)kk[j][4 + e];
-      dot = group_sum<LPR>(dot) * scale;
-      // no branch around the update: inside one the compiler sinks the value row's load to where it is
-      // used and waits for it there, a second memory round trip behind the first
-      const bool ok = base + j * stride + gi < n_keys;
-      const float mn = ok ? fmaxf(m, dot) : m;
-      const float corr = (m == mn) ? 1.0f : __expf(m - mn);     // also m = mn = -inf
-      const float p = ok ? __expf(dot - mn) : 0.f;
-      l = l * corr + p;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] = acc[e] * corr + p * (float)vv[j][e];
-      m = mn;
+      for (int e = 0; e < 4; ++e) t += q0[e] * (float)kk[j][e] + q1[e] * (float)kk[j][4 + e];
+      t = group_sum<LPR>(t) * scale;
+      dot[j] = (base + j * stride + gi < n_keys) ? t : -INFINITY;
+      mn = fmaxf(mn, dot[j]);
     }
+    const float corr = (m == mn) ? 1.0f : __expf(m - mn);     // also m = mn = -inf
+    l *= corr;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] *= corr;
+#pragma unroll
+    for (int j = 0; j < UK; ++j) {
+      const float p = (dot[j] > -INFINITY) ? __expf(dot[j] - mn) : 0.f;
+      l += p;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += p * (float)vv[j][e];
+    }
+    m = mn;
   };
   // the first batch stands outside the loop: straight-line code, in which the wait for the query leaves
   // the keys and values requested after it in flight (a loop header waits for everything)
