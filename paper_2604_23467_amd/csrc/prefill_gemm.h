@@ -9,9 +9,10 @@
 // along M: BM = 128 with 8 waves of 64 x 64 (two waves per SIMD hide each other's waits: measured
 // 3 % faster than 4 waves of 128 x 64), BM = 64 with 4 waves of 64 x 64 for prompts of at most 64
 // rows.  A 256 x 256 tile with two stages was also tried and lost (fewer tiles, shallower
-// pipeline).  The wide tile is what the memory system needs: every
-// slab moves (BM + 256) x 128 bytes from L2 for BM x 256 x 128 flop, and with M <= 512 split
-// over 256 CUs it is the L2 -> CU traffic, not HBM, that bounds these GEMMs.
+// pipeline).  Every slab moves (BM + 256) x 128 bytes from L2 for BM x 256 x 128 flop; the same direct
+// loads alone run at 53 B/clk per CU from L2 (measured), three times what the kernel needs, so it is
+// not that traffic by itself that bounds these GEMMs but how badly the phases of a slab overlap (see
+// the timing-only decomposition further down).
 //
 // Both operands go global -> LDS directly (global_load_lds_dwordx4: no staging registers)
 // into a ring of NS stages, refilled as soon as every wave holds a slab's last fragments in registers.  A direct load
@@ -78,7 +79,9 @@ struct GemmArgs {
 // instructions and the two overlap poorly; without the matrix instructions (loads, LDS reads, stores)
 // 58 / 21 / 96 / 47 us; together 72 / 27 / 118 / 57 us.  FETCH_SIZE counts 210 / 42 / 364 / 157 MB from
 // HBM per launch against 101 / 34 / 180 / 90 MB of weights: the four row tiles of a column tile, placed
-// on one XCD, share about half of their weight fetches through its L2.
+// on one XCD, share about half of their weight fetches through its L2.  With every workgroup reading the
+// same (L2-resident) weight and activation tile the projections still take 62 / 26 / 102 / 55 us (74 / 28 /
+// 122 / 58 on the same box): cache misses are a sixth of the time at most.
 template <int BM, int NS, int WM, int WN, int BK, int OCC = 1, bool WFRAG = false>
 __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kernel(GemmArgs g) {
   static_assert(!WFRAG || BK == 64, "the fragment-major weight path pairs two 32-wide K steps per slab");
