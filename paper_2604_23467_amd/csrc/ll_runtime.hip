@@ -616,6 +616,8 @@ SliceMap launch_gemm(Instance* I, hipStream_t s, const PfBuffers& B, const half_
     hipLaunchKernelGGL((pf_gemm_kernel<128, 3, 2, 4, 64, 1, true>), grid, dim3(PF_GEMM_THREADS_OF(2, 4)), PF_GEMM_LDS_BYTES(128, 3, 64), s, ga);
   else if (gemm_bm(Mb) == 128)
     hipLaunchKernelGGL((pf_gemm_kernel<128, 3, 2, 4, 64>), grid, dim3(PF_GEMM_THREADS_OF(2, 4)), PF_GEMM_LDS_BYTES(128, 3, 64), s, ga);
+  else if (wf && nmat == 1)
+    hipLaunchKernelGGL((pf_gemm_kernel<64, 3, 1, 4, 64, 1, true>), grid, dim3(PF_GEMM_THREADS_OF(1, 4)), PF_GEMM_LDS_BYTES(64, 3, 64), s, ga);
   else
     hipLaunchKernelGGL((pf_gemm_kernel<64, 3, 1, 4, 64>), grid, dim3(PF_GEMM_THREADS_OF(1, 4)), PF_GEMM_LDS_BYTES(64, 3, 64), s, ga);
   return p.map;
@@ -1134,6 +1136,9 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<64, 3, 1, 4, 64>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(64, 3, 64)),
                    "hipFuncSetAttribute(gemm 64)")) return bail(rc);
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<64, 3, 1, 4, 64, 1, true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(64, 3, 64)),
+                   "hipFuncSetAttribute(gemm 64, fragment-major weights)")) return bail(rc);
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_attn_kernel<128, 4>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, PF_ATTN_LDS_BYTES(128, 4)),
                    "hipFuncSetAttribute(attention 128 x 4)")) return bail(rc);
