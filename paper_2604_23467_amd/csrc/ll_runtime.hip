@@ -107,7 +107,10 @@ bool skinny_ok(const ll_config& c) {
 // the grid has runs x mtiles workgroups.  Whatever splits a tile stays within one workgroup per CU
 // (a second, partial round would cost as much as a full one) and keeps runs of at least
 // kGemmMinSlabs slabs; whole tiles may take several rounds when they fill them well.
-int gemm_bm(int Mb) { return Mb >= 128 ? 128 : 64; }
+// O and down (one matrix of d_model columns, i.e. few column tiles) take two 64-row tiles at 65..128 rows:
+// twice the workgroups per column tile, so half as many K pieces per tile for the consumer to add up, and
+// the second row tile finds the weights in L2 (measured at 100 tokens: 4.89 -> 4.81 ms to first token).
+int gemm_bm(int Mb, int nmat = 0) { return (Mb > 128 || (Mb == 128 && nmat != 1)) ? 128 : 64; }
 
 struct GemmPlan {
   int mtiles, runs;
@@ -118,7 +121,7 @@ struct GemmPlan {
 GemmPlan gemm_plan(int N, int K, int nmat, int Mb, int ldc) {
   GemmPlan p{};
   const int kGemmWantWgs = num_cus();               // one round of workgroups
-  p.mtiles = Mb / gemm_bm(Mb);
+  p.mtiles = Mb / gemm_bm(Mb, nmat);
   p.map.nslabs = (K + 63) / 64;
   p.map.ntiles = (N + 255) / 256;
   p.map.N = N;
@@ -612,10 +615,17 @@ SliceMap launch_gemm(Instance* I, hipStream_t s, const PfBuffers& B, const half_
   ga.mtiles = p.mtiles; ga.runs = p.runs; ga.map = p.map;
   dim3 grid((p.runs + 7) / 8 * 8 * p.mtiles);      // runs are dealt to the 8 XCDs
   ga.Wf = wf;
-  if (gemm_bm(Mb) == 128 && wf && nmat == 1)
+  const bool once = p.mtiles == 1;      // a single row tile: every weight byte is used once
+  if (gemm_bm(Mb, nmat) == 128 && wf && nmat == 1 && once)
+    hipLaunchKernelGGL((pf_gemm_kernel<128, 3, 2, 4, 64, 1, true, true>), grid, dim3(PF_GEMM_THREADS_OF(2, 4)), PF_GEMM_LDS_BYTES(128, 3, 64), s, ga);
+  else if (gemm_bm(Mb, nmat) == 128 && wf && nmat == 1)
     hipLaunchKernelGGL((pf_gemm_kernel<128, 3, 2, 4, 64, 1, true>), grid, dim3(PF_GEMM_THREADS_OF(2, 4)), PF_GEMM_LDS_BYTES(128, 3, 64), s, ga);
-  else if (gemm_bm(Mb) == 128)
+  else if (gemm_bm(Mb, nmat) == 128 && once)
+    hipLaunchKernelGGL((pf_gemm_kernel<128, 3, 2, 4, 64, 1, false, true>), grid, dim3(PF_GEMM_THREADS_OF(2, 4)), PF_GEMM_LDS_BYTES(128, 3, 64), s, ga);
+  else if (gemm_bm(Mb, nmat) == 128)
     hipLaunchKernelGGL((pf_gemm_kernel<128, 3, 2, 4, 64>), grid, dim3(PF_GEMM_THREADS_OF(2, 4)), PF_GEMM_LDS_BYTES(128, 3, 64), s, ga);
+  else if (wf && nmat == 1 && !once)
+    hipLaunchKernelGGL((pf_gemm_kernel<64, 3, 1, 4, 64, 1, true, false>), grid, dim3(PF_GEMM_THREADS_OF(1, 4)), PF_GEMM_LDS_BYTES(64, 3, 64), s, ga);
   else if (wf && nmat == 1)
     hipLaunchKernelGGL((pf_gemm_kernel<64, 3, 1, 4, 64, 1, true>), grid, dim3(PF_GEMM_THREADS_OF(1, 4)), PF_GEMM_LDS_BYTES(64, 3, 64), s, ga);
   else
@@ -1133,6 +1143,15 @@ int ll_init(const ll_config* cfg, const ll_weights* w, void* workspace, size_t w
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128, 3, 2, 4, 64>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128, 3, 64)),
                    "hipFuncSetAttribute(gemm 128)")) return bail(rc);
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128, 3, 2, 4, 64, 1, true, true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128, 3, 64)),
+                   "hipFuncSetAttribute(gemm 128, fragment-major weights used once)")) return bail(rc);
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<128, 3, 2, 4, 64, 1, false, true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(128, 3, 64)),
+                   "hipFuncSetAttribute(gemm 128, weights used once)")) return bail(rc);
+  if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<64, 3, 1, 4, 64, 1, true, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(64, 3, 64)),
+                   "hipFuncSetAttribute(gemm 64, fragment-major weights shared by two row tiles)")) return bail(rc);
   if (!hip_or_bail(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<64, 3, 1, 4, 64>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, PF_GEMM_LDS_BYTES(64, 3, 64)),
                    "hipFuncSetAttribute(gemm 64)")) return bail(rc);
@@ -1726,7 +1745,7 @@ int ll_dbg_gemm_plan(int32_t N, int32_t K, int32_t nmat, int32_t rows, int32_t* 
   if (!out6 || N < 1 || K < 1 || nmat < 1 || nmat > 3 || (rows != 64 && rows != 128 && rows != 256 && rows != 512 && rows != 1024))
     return fail(LL_E_BAD_ARG, "ll_dbg_gemm_plan: bad argument");
   const GemmPlan p = gemm_plan(N, K, nmat, rows, nmat * N);
-  out6[0] = gemm_bm(rows); out6[1] = p.mtiles; out6[2] = p.runs; out6[3] = p.map.quota;
+  out6[0] = gemm_bm(rows, nmat); out6[1] = p.mtiles; out6[2] = p.runs; out6[3] = p.map.quota;
   out6[4] = p.map.nslabs; out6[5] = p.max_slices;
   return LL_OK;
 }

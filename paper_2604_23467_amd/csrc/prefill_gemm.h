@@ -82,7 +82,7 @@ struct GemmArgs {
 // on one XCD, share about half of their weight fetches through its L2.  With every workgroup reading the
 // same (L2-resident) weight and activation tile the projections still take 62 / 26 / 102 / 55 us (74 / 28 /
 // 122 / 58 on the same box): cache misses are a sixth of the time at most.
-template <int BM, int NS, int WM, int WN, int BK, int OCC = 1, bool WFRAG = false>
+template <int BM, int NS, int WM, int WN, int BK, int OCC = 1, bool WFRAG = false, bool WNT = (BM == 64)>
 __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kernel(GemmArgs g) {
   static_assert(!WFRAG || BK == 64, "the fragment-major weight path pairs two 32-wide K steps per slab");
   constexpr int NWAVES = WM * WN;
@@ -95,10 +95,10 @@ __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kerne
   constexpr int W_LD = PF_BN / RPL / NWAVES;
   constexpr int PER_SLAB = A_LD + W_LD;
   constexpr int STAGE_HALVES = (BM + PF_BN) * BK;
-  // Cache policy of the weight loads.  With one row tile per column tile (prompts of at most 64 rows) every
-  // weight byte is used once and is loaded non-temporal (4.29 -> 4.12 ms at 50 tokens); with sibling row
+  // Cache policy of the weight loads (WNT).  With one row tile per column tile (prompts of at most 128 rows)
+  // every weight byte is used once and is loaded non-temporal (4.29 -> 4.12 ms at 50 tokens); with sibling row
   // tiles the copies that the siblings find in L2 matter more (non-temporal: 11.14 -> 11.40 ms at 500).
-  constexpr int W_AUX = BM == 64 ? 2 : 0;
+  constexpr int W_AUX = WNT ? 2 : 0;
   static_assert(BK == 64 || BK == 32, "swizzles below are for 128- and 64-byte rows");
   static_assert(A_LD >= 1 && W_LD >= 1 && PER_SLAB * NS < 64, "vmcnt is a 6-bit counter");
   extern __shared__ __attribute__((aligned(16))) half_t pf_lds[];
