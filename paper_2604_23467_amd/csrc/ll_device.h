@@ -123,6 +123,14 @@ __device__ __forceinline__ void wait_vm_at_most() {
   __builtin_amdgcn_s_waitcnt((N & 15) | 0x70 | 0xF00 | ((N >> 4) << 14));
 }
 
+// s_waitcnt lgkmcnt(N): at most N LDS operations of this wave still outstanding (they complete in order);
+// the vector-memory and export counters left at "no wait"
+template <int N>
+__device__ __forceinline__ void wait_lgkm_at_most() {
+  static_assert(N >= 0 && N < 16, "lgkmcnt is a 4-bit counter");
+  __builtin_amdgcn_s_waitcnt(0xC00F | 0x70 | (N << 8));
+}
+
 // plain 16-byte load from global memory
 __device__ __forceinline__ h8 load_h8(const half_t* p) {
   return *as_global(reinterpret_cast<const h8*>(p));

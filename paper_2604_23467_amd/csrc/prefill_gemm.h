@@ -82,6 +82,13 @@ struct GemmArgs {
 // on one XCD, share about half of their weight fetches through its L2.  With every workgroup reading the
 // same (L2-resident) weight and activation tile the projections still take 62 / 26 / 102 / 55 us (74 / 28 /
 // 122 / 58 on the same box): cache misses are a sixth of the time at most.
+// Three more structures measured at 500 tokens and not kept: operands staged global -> registers -> ds_write
+// instead of direct loads (two slabs in flight in registers): 10 % slower on all four projections; the
+// weights' fragments loaded global -> registers from the fragment-major copy, only the activations through LDS
+// (four waves of 128 x 64, a third of the LDS traffic): O 28.0 -> 27.2, down 57.3 -> 54.7 us, nothing at 250
+// tokens, slower at 128; four waves of 128 x 64 on this kernel: within 2 % either way.  A timing-only build
+// that never waits for the direct loads runs as long as the real one, and one without the loads takes 37 / 17 /
+// 59 / 32 us: the loads cost their stand-alone time on top of the rest whether or not anybody waits for them.
 template <int BM, int NS, int WM, int WN, int BK, int OCC = 1, bool WFRAG = false, bool WNT = (BM == 64)>
 __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kernel(GemmArgs g) {
   static_assert(!WFRAG || BK == 64, "the fragment-major weight path pairs two 32-wide K steps per slab");
@@ -155,22 +162,21 @@ __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kerne
   // hitting the same few memory channels, since the rows lie a multiple of 2 K bytes apart.
   const int rot = (nt_all * 7) % cnt;
   const int iters = cnt * SUB;
-  auto issue = [&](int it, int stage) {
+  // one of a slab's PER_SLAB direct loads (the activations' first): ring slab `it` into `stage`
+  auto issue_one = [&](int it, int stage, int idx) {
     half_t* sa = pf_lds + stage * STAGE_HALVES;
     half_t* sw = sa + BM * BK;
     const int ps = it / SUB, sub = it - ps * SUB;         // plan slab (rotated below) and the BK-wide part of it
     const int sl = sl0 + (ps + rot < cnt ? ps + rot : ps + rot - cnt);
     const int k0 = sl * PF_SLAB + sub * BK;
     const bool kin = it < iters && k0 + lchunk * 8 < K;   // K % 8 == 0: a chunk is all in or all out
-#pragma unroll
-    for (int i = 0; i < A_LD; ++i) {
-      const half_t* src = kin ? arow[i] + k0 : g.zeros;
+    if (idx < A_LD) {
+      const half_t* src = kin ? arow[idx] + k0 : g.zeros;
       __builtin_amdgcn_global_load_lds((const LL_GLOBAL void*)src,
-                                       (__attribute__((address_space(3))) void*)(sa + (wave * A_LD + i) * RPL * BK),
+                                       (__attribute__((address_space(3))) void*)(sa + (wave * A_LD + idx) * RPL * BK),
                                        16, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < W_LD; ++i) {
+    } else {
+      const int i = idx - A_LD;
       const half_t* src;
       if (WFRAG) {          // K step 2 sl + (piece % 2); the copy is zero beyond K, steps past its end come from the zeros
         const int st = sl * 2 + ((wave * W_LD + i) & 1);
@@ -192,9 +198,26 @@ __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kerne
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+  constexpr int KS = BK / 16;
+  static_assert(KS % 2 == 0, "the fragment double buffer keeps its parity across slabs");
+  // A refill's direct loads are not issued in one burst behind the barrier but dealt over the k-steps that
+  // follow, one behind a matrix instruction each: slot 0 is the slab's last k-step (behind the hand-over),
+  // slot s is k-step s - 1 of the next slab.  A wave issues in order, so a wave waiting to issue the next load
+  // of a burst cannot issue its matrix instructions either (measured at 500 tokens: Q/K/V 62.9 -> 61.6 us,
+  // gate/up 103.9 -> 102.6 us).
+  auto slot_of = [](int idx) { return idx * KS / PER_SLAB; };
+  constexpr int N_SLOT0 = (PER_SLAB + KS - 1) / KS;      // loads with slot_of(idx) == 0
+  static_assert(N_SLOT0 <= MT * NT, "one load behind each matrix instruction at most");
+
   __syncthreads();        // a previous piece's last fragment reads are over before its ring is refilled
+  // slabs 0 .. NS - 2 whole, and slot 0 of slab NS - 1: what the loop's first k-steps expect to be under way
 #pragma unroll
-  for (int s = 0; s < NS; ++s) issue(s, s);
+  for (int s = 0; s < NS - 1; ++s)
+#pragma unroll
+    for (int idx = 0; idx < PER_SLAB; ++idx) issue_one(s, s, idx);
+#pragma unroll
+  for (int idx = 0; idx < PER_SLAB; ++idx)
+    if (slot_of(idx) == 0) issue_one(NS - 1, NS - 1, idx);
 
   // fragments of the next k-step are read from LDS while the matrix cores work on the current one
   auto load_frags = [&](int stage, int ks, h8 (&fa)[MT], h8 (&fb)[NT]) {
@@ -217,62 +240,63 @@ __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kerne
     }
   };
   // The slab hand-over sits in front of a slab's LAST k-step, not behind it: by then a wave holds the
-  // slab's last fragments in registers, so once every wave is there the slab's stage is free and is
-  // refilled at once (NS slabs in flight, not NS - 1), and the first fragments of the next slab are
-  // read while the matrix cores still work on this one; the barrier and the burst of LDS reads that
-  // opens a slab are hidden behind a k-step of matrix instructions instead of leaving them idle.
-  auto hand_over = [&](int it) {
-    // this wave's pieces of slab it + 1 have landed (younger slabs may still be in flight) ...
+  // slab's last fragments in registers, so once every wave is there the slab's stage is free and its refill
+  // starts at once, and the first fragments of the next slab are read while the matrix cores still work on
+  // this one; the barrier and the LDS reads that open a slab are hidden behind a k-step of matrix
+  // instructions instead of leaving them idle.
+  auto hand_over = [&]() {
+    // This wave's pieces of the next slab have landed: behind them stands exactly one slab's worth of
+    // younger loads per ring stage beyond two (slot 0 of a refill is issued in the k-step after this, the
+    // other slots in the k-steps before the next hand-over) ...
     wait_vm_at_most<PER_SLAB * (NS - 2)>();
-    // ... its fragment reads of slab it are done, and after the barrier so are everybody else's.
+    // ... its fragment reads of this slab are done, and after the barrier so are everybody else's.
     // A bare s_barrier: __syncthreads() carries a fence that would drain ALL loads in flight.
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    wait_lgkm_at_most<0>();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    issue(it + NS, it % NS);
   };
-  constexpr int KS = BK / 16;
-  static_assert(KS % 2 == 0, "the fragment double buffer keeps its parity across slabs");
   h8 fa[2][MT], fb[2][NT];
-  wait_vm_at_most<PER_SLAB * (NS - 1)>();
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  wait_vm_at_most<PER_SLAB * (NS - 2) + N_SLOT0>();      // slab 0 is in
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   load_frags(0, 0, fa[0], fb[0]);
-  // PIN: scheduling fences pin the pipeline.  A k-step's group is the LDS reads of the NEXT k-step followed
-  // by the matrix instructions of this one, and the hand-over follows the group of the last k-step but one;
-  // left alone the compiler sinks every read to just before its use and waits for it there.  Measured at
-  // 500 tokens: Q/K/V 72.2 -> 69.7 us, gate/up 117.1 -> 113.3 us; the kernel on fragment-major weights is
-  // faster left to the compiler (O 27.2 against 28.2 us pinned, down 56.0 against 58.4), with the hand-over
-  // inside its last k-step.
-  constexpr bool PIN = !WFRAG;
-  if (PIN) __builtin_amdgcn_sched_barrier(0);
+  // Scheduling fences pin the pipeline: per k-step the wait for this k-step's fragments, the LDS reads of the
+  // next k-step, then the matrix instructions with the refill's loads between them.  Left alone the compiler
+  // sinks every read to just before its use, and it waits for ALL outstanding LDS reads wherever it waits for
+  // one (it does not count them here): requested behind the new reads, this k-step's fragments would cost a
+  // whole LDS round trip in front of every second k-step.  Measured at 500 tokens, Q/K/V / O / gate/up / down:
+  // 64.5 / 26.4 / 105.9 / 54.1 us with the compiler's waits, 61.6 / 25.4 / 102.6 / 52.2 us as below.
+  __builtin_amdgcn_sched_barrier(0);
   for (int it = 0; it < iters; ++it) {
     const int stage = it % NS;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       if (ks + 1 < KS) {
-        load_frags(stage, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
-      } else if (!PIN) {
-        hand_over(it);
-        load_frags((it + 1) % NS, 0, fa[0], fb[0]);
-      }
-#pragma unroll
-      for (int j = 0; j < NT; ++j)
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
-      if (PIN) {
-        if (ks + 1 < KS) {
-          __builtin_amdgcn_sched_group_barrier(0x100, MT + NT, 0);   // the reads first ...
-          __builtin_amdgcn_sched_group_barrier(0x008, MT * NT, 0);   // ... then the matrix instructions
-        }
+        // the last k-step's fragments were waited for by the hand-over
+        wait_lgkm_at_most<0>();
         __builtin_amdgcn_sched_barrier(0);
-        if (ks == KS - 2) {
-          hand_over(it);
-          load_frags((it + 1) % NS, 0, fa[0], fb[0]);
+        load_frags(stage, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // refill `rf` (slab rf + NS into stage rf % NS, free since the hand-over of slab rf): this k-step's share
+      const int rf = ks == KS - 1 ? it : it - 1;
+      const int rstage = ks == KS - 1 ? stage : (stage == 0 ? NS - 1 : stage - 1);
+      const int slot = (ks + 1) % KS;
+      const int first = (slot * PER_SLAB + KS - 1) / KS;      // lowest idx with slot_of(idx) == slot
+#pragma unroll
+      for (int t = 0; t < MT * NT; ++t) {
+        const int i = t % MT, j = t / MT;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (first + t < PER_SLAB && slot_of(first + t) == slot) {
+          issue_one(rf + NS, rstage, first + t);
           __builtin_amdgcn_sched_barrier(0);
         }
+      }
+      if (ks == KS - 2) {
+        hand_over();
+        load_frags((it + 1) % NS, 0, fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
@@ -294,3 +318,4 @@ __global__ __launch_bounds__(PF_GEMM_THREADS_OF(WM, WN), OCC) void pf_gemm_kerne
   }
   }   // next piece of this workgroup's run
 }
+
