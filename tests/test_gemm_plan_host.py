@@ -70,6 +70,20 @@ def test_plan_keeps_the_chip_busy_at_the_7b_shapes():
     assert p["runs"] * p["row_tiles"] == 256 and p["quota"] > p["tile_slabs"]
 
 
+def test_row_tiles_of_the_residual_projections_at_128_rows():
+    """One matrix of d_model columns (O, down) has few column tiles: at 65..128 rows it runs as two 64-row
+    tiles per column tile, everything else at 128 rows as one tile of 128; the slices a consumer adds up
+    stay within what the plan reports either way."""
+    d, F = 4096, 11008
+    for N, K, nmat, bm, tiles in ((d, d, 1, 64, 2), (d, F, 1, 64, 2), (d, d, 3, 128, 1), (F, d, 2, 128, 1)):
+        p = binding.ll_dbg_gemm_plan(N, K, nmat, 128)
+        assert (p["row_tile"], p["row_tiles"]) == (bm, tiles), (N, K, nmat, p)
+        assert p["runs"] * p["row_tiles"] <= 256
+    for N, K, nmat in ((d, d, 1), (d, F, 1)):
+        assert binding.ll_dbg_gemm_plan(N, K, nmat, 256)["row_tile"] == 128
+        assert binding.ll_dbg_gemm_plan(N, K, nmat, 64)["row_tile"] == 64
+
+
 def test_plan_rejects_bad_arguments():
     for bad in ((0, 64, 1, 64), (64, 0, 1, 64), (64, 64, 4, 64), (64, 64, 1, 100)):
         with pytest.raises(binding.LLError) as e:
